@@ -1,0 +1,389 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix (no GPU).
+
+Each test names the passage it leans on.  The expected values come from
+hand-worked fixtures under tests/golden/, from closed forms, or from
+independent brute force written here with Python sets and scalars.
+"""
+import json
+import os
+
+import numpy as np
+import pytest
+from scipy.stats import norm
+
+import workloads as wl
+from oracle import lif_oracle as O
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def golden(name):
+    with open(os.path.join(GOLDEN, name)) as f:
+        return json.load(f)
+
+
+def cache_from_rows(rows, pointers, bias, capacity=None, dtype=np.float32):
+    rows = np.asarray(rows, dtype=dtype)
+    cap = capacity or max(len(rows), 1)
+    c = O.NeuronCache(cap, rows.shape[1], dtype)
+    c.matrix[:len(rows)] = rows
+    c.pointers[:len(rows)] = pointers
+    c.bias[:len(rows)] = bias
+    c.num_used = len(rows)
+    return c
+
+
+# ----------------------------------------------------------------------------- bundles
+def test_bundle_size_matches_paper_constants():
+    g = golden("paper_constants.json")
+    for key in ("opt_6p7b", "falcon_7b"):
+        e = g[key]
+        assert O.bundle_bytes(e["d_model"], e["num_bytes"]) == e["bundle_kib"] * 1024
+    # bundling doubles the chunk (Section 3.2); the gated variant triples it
+    assert O.bundle_bytes(4096, 2) == 2 * (4096 * 2)
+    assert O.bundle_bytes(4096, 2, glu=True) == 3 * (4096 * 2)
+    for name, w in wl.WORKLOADS.items():
+        assert w.bundle_bytes == O.bundle_bytes(w.d_model, w.elem_bytes, w.glu)
+
+
+# ----------------------------------------------------------------------------- FFN
+@pytest.mark.parametrize("fn", [O.sparse_ffn, O.sparse_ffn_loops])
+def test_ffn_hand_worked(fn):
+    g = golden("ffn_tiny.json")
+    d = g["d_model"]
+    p = g["plain"]
+    rows = np.concatenate([np.array(p["up"], float), np.array(p["down"], float)], axis=1)
+    cache = cache_from_rows(rows, [0, 1, 2], p["bias"])
+    np.testing.assert_array_equal(fn(cache, g["x"], d), p["y"])
+    q = g["glu"]
+    rows = np.concatenate([np.array(q["gate"], float), np.array(q["up"], float),
+                           np.array(q["down"], float)], axis=1)
+    cache = cache_from_rows(rows, [0, 1, 2], q["bias"])
+    np.testing.assert_array_equal(fn(cache, g["x"], d, glu=True), q["y"])
+    assert list(O.true_mask(np.array(p["up"]), p["bias"], g["x"])) == p["true_mask"]
+
+
+def test_dense_ffn_hand_worked():
+    g = golden("ffn_tiny.json")
+    p, q = g["plain"], g["glu"]
+    y = O.dense_ffn(np.array(p["up"], float), np.array(p["down"], float), p["bias"], g["x"])
+    np.testing.assert_array_equal(y, p["y"])
+    y = O.dense_ffn(np.array(q["up"], float), np.array(q["down"], float), q["bias"], g["x"],
+                    w_gate=np.array(q["gate"], float))
+    np.testing.assert_array_equal(y, q["y"])
+
+
+def _small_layer(glu=False, dtype="f32", d=64, F=192, r=16):
+    w = wl.scaled(wl.WORKLOADS["C1"], d_model=d, d_ffn=F, rank=r, glu=glu, dtype=dtype,
+                  capacity_rows=F, tokens=12, p_active=0.1)
+    return w, wl.make_layer(w), wl.make_inputs(w)
+
+
+@pytest.mark.parametrize("glu", [False, True])
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+def test_sparse_over_true_set_equals_dense(glu, dtype):
+    """ReLU-zeroed neurons contribute nothing (Section 3.1), so the sum over exactly the
+    true-active neurons, taken in ascending id, is the dense FFN bit for bit."""
+    w, L, X = _small_layer(glu, dtype)
+    w_act = L.w_gate if glu else L.w_up
+    for x in X[:4]:
+        tm = O.true_mask(w_act, L.b, x)
+        assert 0 < tm.sum() < w.d_ffn
+        ids = np.flatnonzero(tm)
+        cache = cache_from_rows(L.bundles[ids], ids, L.b[ids], dtype=L.bundles.dtype)
+        y_dense = O.dense_ffn(L.w_up, L.w_down, L.b, x, L.w_gate)
+        y_loop = O.sparse_ffn_loops(cache, x, w.d_model, glu)
+        np.testing.assert_array_equal(y_loop, y_dense)
+        np.testing.assert_array_equal(O.dense_ffn(L.w_up, L.w_down, L.b, x, L.w_gate, only=tm), y_dense)
+        # matrix form and any slot order: equal up to fp64 rounding (Section 3.3 item 3:
+        # the order of the cached neurons does not change the output)
+        y_mat = O.sparse_ffn(cache, x, w.d_model, glu)
+        perm = np.random.default_rng(1).permutation(len(ids))
+        cache_p = cache_from_rows(L.bundles[ids[perm]], ids[perm], L.b[ids[perm]], dtype=L.bundles.dtype)
+        y_perm = O.sparse_ffn(cache_p, x, w.d_model, glu)
+        scale = np.linalg.norm(y_dense)
+        assert np.linalg.norm(y_mat - y_dense) <= 1e-12 * scale
+        assert np.linalg.norm(y_perm - y_dense) <= 1e-12 * scale
+
+
+def test_all_rows_cached_equals_dense_and_empty_cache_is_zero():
+    w, L, X = _small_layer()
+    ids = np.arange(w.d_ffn)
+    cache = cache_from_rows(L.bundles, ids, L.b)
+    y = O.sparse_ffn(cache, X[0], w.d_model)
+    y_dense = O.dense_ffn(L.w_up, L.w_down, L.b, X[0])
+    assert np.linalg.norm(y - y_dense) <= 1e-12 * np.linalg.norm(y_dense)
+    cache.num_used = 0
+    assert not O.sparse_ffn(cache, X[0], w.d_model).any()
+    assert not O.sparse_ffn_loops(cache, X[0], w.d_model).any()
+
+
+def test_ffn_batch_rows_equal_single_token_calls():
+    w, L, X = _small_layer(glu=True)
+    ids = np.arange(0, w.d_ffn, 3)
+    cache = cache_from_rows(L.bundles[ids], ids, L.b[ids])
+    Y = O.sparse_ffn(cache, X[:5], w.d_model, True)
+    for t in range(5):
+        y1 = O.sparse_ffn_loops(cache, X[t], w.d_model, True)
+        assert np.linalg.norm(Y[t] - y1) <= 1e-12 * np.linalg.norm(y1)
+
+
+def test_fp32_accumulation_leaves_headroom_under_tolerance():
+    """The GPU accumulates in fp32; the tolerance (1e-3 relative L2) must sit >= 10x above
+    what fp32 accumulation alone costs."""
+    w, L, X = _small_layer(dtype="f16", d=256, F=1024, r=16)
+    ids = np.arange(0, w.d_ffn, 2)
+    cache = cache_from_rows(L.bundles[ids], ids, L.b[ids], dtype=np.float16)
+    for x in X[:3]:
+        y64 = O.sparse_ffn(cache, x, w.d_model)
+        y32 = O.sparse_ffn(cache, x, w.d_model, acc=np.float32)
+        assert np.linalg.norm(y32 - y64) <= 1e-4 * np.linalg.norm(y64)
+
+
+# ----------------------------------------------------------------------------- predictor
+def test_predictor_hand_worked():
+    g = golden("predictor_tiny.json")
+    z = O.predictor_logits(g["x"], g["A"], g["B"], g["c"])
+    np.testing.assert_array_equal(z, g["z"])
+    mask, margin = O.predict_mask(g["x"], g["A"], g["B"], g["c"], g["theta"])
+    assert list(mask) == g["mask"]
+    assert margin == 0.0                      # z = 0 entries sit on the threshold: not active
+    assert list(O.pack_mask(mask)) == g["packed"]
+
+
+def test_pack_mask_bit_order():
+    m = np.zeros(24, bool)
+    m[[0, 9, 23]] = True
+    assert list(O.pack_mask(m)) == [0x01, 0x02, 0x80]
+    assert (O.unpack_mask(O.pack_mask(m), 24) == m).all()
+
+
+def test_full_rank_predictor_reproduces_true_mask():
+    """With r = d the truncated SVD is exact, so x A B = W x and, with c = b, the predicted
+    mask is the true mask; the sparse FFN over the predicted set is then the dense FFN."""
+    w = wl.scaled(wl.WORKLOADS["C1"], d_model=48, d_ffn=160, rank=48, p_active=0.1, dtype="f32",
+                  capacity_rows=160)
+    L = wl.make_layer(w)
+    A64 = np.linalg.svd(L.w_up.astype(np.float64), full_matrices=False)[2].T   # [d, d]
+    B64 = A64.T @ L.w_up.astype(np.float64).T
+    X = wl.make_inputs(w, tokens=6)
+    for x in X:
+        mask, margin = O.predict_mask(x, A64, B64, L.b, 0.0)
+        assert margin > 1e-9
+        tm = O.true_mask(L.w_up, L.b, x)
+        assert (mask == tm).all()
+        ids = np.flatnonzero(mask)
+        cache = cache_from_rows(L.bundles[ids], ids, L.b[ids])
+        y = O.sparse_ffn(cache, x, w.d_model)
+        y_dense = O.dense_ffn(L.w_up, L.w_down, L.b, x)
+        assert np.linalg.norm(y - y_dense) <= 1e-12 * np.linalg.norm(y_dense)
+
+
+def test_threshold_extremes_and_strictness():
+    w, L, X = _small_layer()
+    m, _ = O.predict_mask(X[0], L.A, L.B, L.c, -np.inf)
+    assert m.all()
+    m, _ = O.predict_mask(X[0], L.A, L.B, L.c, np.inf)
+    assert not m.any()
+    # strict comparison: a logit equal to the threshold is inactive
+    A = np.eye(2); B = np.array([[1.0, 0, 0, 0, 0, 0, 0, 0], [0, 1.0, 0, 0, 0, 0, 0, 0]])
+    m, _ = O.predict_mask([0.5, 0.75], A, B, None, 0.5)
+    assert list(m[:2]) == [False, True]
+
+
+def test_batch_masks_and_step_mask():
+    w, L, X = _small_layer()
+    M, _ = O.predict_mask(X[:4], L.A, L.B, L.c, 0.0)
+    for t in range(4):
+        m, _ = O.predict_mask(X[t], L.A, L.B, L.c, 0.0)
+        assert (M[t] == m).all()
+    sm = O.step_mask(M)
+    assert (sm == (M[0] | M[1] | M[2] | M[3])).all()
+
+
+def test_calibrated_rates_match_closed_form():
+    """Workload calibration: for stationary N(0, I) inputs the true and the predicted firing
+    rates both equal p (normal quantile); AR(1) keeps unit variance since rho^2 + (1-rho^2) = 1."""
+    w = wl.scaled(wl.WORKLOADS["C1"], tokens=400)
+    L = wl.make_layer(w)
+    X = wl.make_inputs(w)
+    assert abs(X.astype(np.float64).var() - 1.0) < 0.05
+    M, _ = O.predict_mask(X, L.A, L.B, L.c, L.theta)
+    T = np.stack([O.true_mask(L.w_up, L.b, x) for x in X])
+    n = M.size
+    tol = 6 * np.sqrt(w.p_active * (1 - w.p_active) / n) * 6   # tokens are correlated: wide band
+    assert abs(M.mean() - w.p_active) < tol
+    assert abs(T.mean() - w.p_active) < tol
+    assert abs(norm.cdf(norm.ppf(1 - w.p_active)) - (1 - w.p_active)) < 1e-12
+
+
+# ----------------------------------------------------------------------------- window
+def test_window_hand_worked():
+    g = golden("window_k3.json")
+    win = O.SlidingWindow(g["d_ffn"], g["k"])
+    for t, ids in enumerate(g["masks"]):
+        m = np.zeros(g["d_ffn"], bool)
+        m[ids] = True
+        added, removed = win.push(m)
+        assert list(added) == g["added"][t]
+        assert list(removed) == g["removed"][t]
+        assert list(np.flatnonzero(win.active_set())) == g["active"][t]
+
+
+@pytest.mark.parametrize("k", [1, 2, 5, 100])
+def test_window_equals_bruteforce_union_of_last_k(k):
+    rng = np.random.default_rng(7)
+    F, T = 96, 40
+    sets = [set(np.flatnonzero(rng.random(F) < 0.08).tolist()) for _ in range(T)]
+    win = O.SlidingWindow(F, k)
+    prev = set()
+    for t, s in enumerate(sets):
+        m = np.zeros(F, bool)
+        m[list(s)] = True
+        added, removed = win.push(m)
+        cur = set().union(*sets[max(0, t - k + 1):t + 1])
+        assert set(np.flatnonzero(win.active_set()).tolist()) == cur
+        assert list(added) == sorted(cur - prev)
+        assert list(removed) == sorted(prev - cur)
+        assert set(added.tolist()) <= s and not (set(removed.tolist()) & s)
+        assert len(cur) == len(prev) + len(added) - len(removed)
+        if t == 0:
+            assert list(added) == sorted(s)          # the cache starts empty (Section 3.3)
+        if k == 1:
+            assert cur == s
+        if k >= T:
+            assert len(removed) == 0
+        prev = cur
+
+
+def test_window_overflow_leaves_state_unchanged():
+    win = O.SlidingWindow(16, 2)
+    m1 = np.zeros(16, bool); m1[[1, 2, 3]] = True
+    win.push(m1, capacity=4)
+    m2 = np.zeros(16, bool); m2[[4, 5]] = True
+    with pytest.raises(OverflowError):
+        win.push(m2, capacity=4)
+    assert list(np.flatnonzero(win.active_set())) == [1, 2, 3]
+    m3 = np.zeros(16, bool); m3[[4]] = True
+    added, removed = win.push(m3, capacity=4)
+    assert list(added) == [4] and list(removed) == []
+
+
+# ----------------------------------------------------------------------------- cache
+def test_delete_hand_worked_cases():
+    for case in golden("delete_cases.json")["cases"]:
+        ptr = case["pointers"]
+        rows = np.array([[p, p + 0.5, -p] for p in ptr], dtype=np.float32).reshape(len(ptr), 3)
+        cache = cache_from_rows(rows, ptr, [p * 0.25 for p in ptr])
+        moved = O.delete_neurons(cache, case["removed"])
+        n = cache.num_used
+        assert list(cache.pointers[:n]) == case["after"]
+        assert moved == case["moved"]
+        for s in range(n):                         # rows and scalars travel with their pointer
+            p = cache.pointers[s]
+            assert list(cache.matrix[s]) == [p, p + 0.5, -p]
+            assert cache.bias[s] == p * 0.25
+
+
+def test_delete_matches_parallel_statement_and_bounds():
+    """Equivalent closed statement: with n' = n - c, the dead slots below n' (ascending) are
+    filled by the live slots at or above n' (descending).  At most c rows move, all into
+    slots below n' (Section 3.3 item 1: rewrite of order c x d_model)."""
+    rng = np.random.default_rng(3)
+    for trial in range(200):
+        n = int(rng.integers(0, 40))
+        ptr = rng.permutation(1000)[:n].astype(np.int32)
+        dead = rng.random(n) < rng.choice([0.0, 0.2, 0.6, 1.0])
+        removed = ptr[dead]
+        rows = np.stack([ptr, ptr * 2], axis=1).astype(np.float32).reshape(n, 2)
+        cache = cache_from_rows(rows, ptr, ptr.astype(np.float32), capacity=64)
+        before = cache.pointers[:n].copy()
+        moved = O.delete_neurons(cache, removed)
+        c = int(dead.sum()); n2 = n - c
+        assert cache.num_used == n2
+        holes = [s for s in range(n2) if dead[s]]
+        fillers = [s for s in range(n2, n) if not dead[s]]
+        assert len(holes) == len(fillers) == moved <= c
+        expect = before.copy()
+        for j, hslot in enumerate(holes):
+            expect[hslot] = before[fillers[len(fillers) - 1 - j]]
+        assert list(cache.pointers[:n2]) == list(expect[:n2])
+        assert set(cache.pointers[:n2].tolist()) == set(before.tolist()) - set(removed.tolist())
+        untouched = [s for s in range(n2) if not dead[s]]
+        assert (cache.pointers[untouched] == before[untouched]).all()
+
+
+def test_insert_appends_without_moving_rows_and_counts_bytes():
+    w, L, _ = _small_layer()
+    cache = O.NeuronCache(32, L.bundles.shape[1], L.bundles.dtype)
+    first = np.array([3, 7, 20], np.int32)
+    assert O.insert_neurons(cache, first, L.bundles, L.b) == 3 * w.bundle_bytes
+    snap = cache.matrix[:3].copy()
+    second = np.array([1, 100], np.int32)
+    assert O.insert_neurons(cache, second, L.bundles, L.b) == 2 * w.bundle_bytes
+    assert (cache.matrix[:3] == snap).all()
+    assert list(cache.pointers[:5]) == [3, 7, 20, 1, 100]
+    for s in range(5):
+        i = cache.pointers[s]
+        assert cache.matrix[s].tobytes() == L.bundles[i].tobytes()
+        assert cache.bias[s] == L.b[i]
+    with pytest.raises(OverflowError):
+        O.insert_neurons(cache, np.arange(100, 130, dtype=np.int32), L.bundles, L.b)
+
+
+# ----------------------------------------------------------------------------- whole path
+def _run_layer(w, L, X, k=None):
+    lay = O.OracleLayer(w.d_model, w.d_ffn, k or w.window_k, w.capacity_rows, w.glu,
+                        L.A, L.B, L.c, L.theta, L.b, L.bundles)
+    out = [lay.step(x) for x in X]
+    return lay, out
+
+
+def test_whole_path_invariants_C1():
+    w = wl.WORKLOADS["C1"]
+    L = wl.make_layer(w)
+    X = wl.make_inputs(w)
+    lay = O.OracleLayer(w.d_model, w.d_ffn, w.window_k, w.capacity_rows, w.glu,
+                        L.A, L.B, L.c, L.theta, L.b, L.bundles)
+    history = []
+    total = 0
+    for t, x in enumerate(X):
+        r = lay.step(x)
+        history.append(set(np.flatnonzero(r["masks"]).tolist()))
+        S = set().union(*history[max(0, t - w.window_k + 1):])
+        n = lay.cache.num_used
+        ptr = lay.cache.pointers[:n]
+        assert n == len(S) and set(ptr.tolist()) == S and len(set(ptr.tolist())) == n
+        assert r["loaded"] == len(r["added"]) * w.bundle_bytes       # bytes = new neurons x bundle
+        total += r["loaded"]
+        assert (lay.cache.matrix[:n] == L.bundles[ptr]).all()
+        assert (lay.cache.bias[:n] == L.b[ptr]).all()
+        # FFN over the cache = dense FFN restricted to the cached neurons
+        if t % 16 == 5:
+            only = np.zeros(w.d_ffn, bool); only[ptr] = True
+            yd = O.dense_ffn(L.w_up, L.w_down, L.b, x, only=only)
+            assert np.linalg.norm(r["y"] - yd) <= 1e-12 * np.linalg.norm(yd)
+    assert lay.bytes_loaded == total
+    assert lay.min_margin > 1e-9
+    first = len(history[0])
+    assert lay.bytes_loaded >= first * w.bundle_bytes                # first token loads its whole mask
+
+
+def test_bytes_and_occupancy_monotone_in_window_size():
+    """Larger windows load fewer bytes per token and hold more rows (Section 3.1)."""
+    w = wl.WORKLOADS["C1"]
+    L = wl.make_layer(w)
+    X = wl.make_inputs(w)
+    loaded, held = [], []
+    for k in (1, 2, 4, 8, 64):
+        lay, out = _run_layer(w, L, X, k)
+        loaded.append(lay.bytes_loaded)
+        held.append(np.mean([o["num_used"] for o in out]))
+    assert all(a >= b for a, b in zip(loaded, loaded[1:]))
+    assert all(a <= b for a, b in zip(held, held[1:]))
+    # k >= T: every neuron is loaded exactly once
+    lay, out = _run_layer(w, L, X, 64)
+    union = set()
+    for o in out:
+        union |= set(np.flatnonzero(o["masks"]).tolist())
+    assert lay.bytes_loaded == len(union) * w.bundle_bytes
