@@ -1,0 +1,224 @@
+/*
+ * lif.h - C ABI of the MI355X (gfx950) sparse-FFN hot path of "LLM in a flash"
+ * (arXiv 2312.11514): per-token FFN inference over predicted-active neurons held
+ * in an HBM neuron cache that is fed from pinned host memory (standing in for flash).
+ *
+ * One handle (lif_layer) = one FFN layer.  Per token (or per batch of tokens) the
+ * caller issues, on one HIP stream and without any host synchronisation,
+ *
+ *     lif_predict -> lif_update_window -> lif_load_bundles -> lif_sparse_ffn
+ *
+ * All counts (added / removed neurons, rows in use) stay on the device, so the four
+ * calls chain without a host round trip and can be captured into a HIP graph.
+ *
+ * Conventions
+ *   - Plain C; every call returns a status (LIF_OK = 0).  No call blocks or
+ *     synchronises except lif_get_state, lif_get_counters and lif_profile_collect.
+ *   - "device" pointers are HBM addresses valid on the GPU that is current when
+ *     lif_create is called; "host" pointers are CPU addresses.  Streams are passed
+ *     as void* holding a hipStream_t (NULL = the default stream).
+ *   - The library allocates no device memory: every array, including the scratch
+ *     workspace, is owned by the caller and must outlive the handle.
+ *   - Element type E is fp32 (LIF_F32) or IEEE fp16 (LIF_F16).  G = 2 vectors per
+ *     bundle (up row | down column), G = 3 for gated layers (gate row | up row | down column).
+ *   - Shape limits: d_model, rank multiples of 8 (fp16) or 4 (fp32); d_ffn a multiple
+ *     of 8 and at most 65536; rank at most 2048; max_batch at most 8.
+ *   - A device-detected error (capacity overflow) sets a sticky flag: until lif_reset
+ *     every hot call becomes a no-op on the device; lif_get_state reports the flag.
+ *   - Calls on one handle must not overlap (one stream at a time).
+ */
+#ifndef LIF_H
+#define LIF_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct lif_layer lif_layer;
+
+enum lif_status {
+    LIF_OK = 0,
+    LIF_INVALID_ARG = 1,   /* null pointer, unsupported shape, batch > max_batch */
+    LIF_BAD_STATE = 2,     /* calls out of order (see lif_update_window / lif_load_bundles) */
+    LIF_CAPACITY = 3,      /* reported by lif_get_state: active set exceeded capacity_rows */
+    LIF_HIP_ERROR = 4      /* a HIP runtime call failed; see lif_last_error_string */
+};
+
+enum lif_dtype { LIF_F32 = 0, LIF_F16 = 1 };
+
+/* How lif_sparse_ffn reads the cache (Section 3.3, inference over the cached rows). */
+enum lif_ffn_mode {
+    LIF_FFN_SKIP_DEAD = 0, /* do not read the down column of rows whose activation is zero */
+    LIF_FFN_FULL_BUNDLE = 1 /* read every cached bundle completely */
+};
+
+typedef struct lif_config {
+    int32_t d_model;        /* d: length of the up row and of the down column              */
+    int32_t d_ffn;          /* F: number of intermediate neurons of the layer              */
+    int32_t rank;           /* r: rank of the low-rank predictor (Section 3.1, Fig. 3b)    */
+    int32_t window_k;       /* k: sliding window in steps, current step included (Fig. 4b) */
+    int32_t capacity_rows;  /* rows preallocated in the cache ("Req_i", Section 3.3)       */
+    int32_t max_batch;      /* largest batch of tokens per step (1..8)                     */
+    int32_t glu;            /* 0: bundle = up|down, 1: bundle = gate|up|down               */
+    int32_t dtype;          /* enum lif_dtype: type of x, y, A, B and the bundles          */
+    int32_t ffn_mode;       /* enum lif_ffn_mode                                           */
+    float threshold;        /* theta: neuron i is predicted active iff logit_i > theta     */
+} lif_config;
+
+typedef struct lif_buffers {
+    /* predictor (device, read-only): logits = (x A) B + c                               */
+    const void* A;          /* [d_model x rank] row-major, E                              */
+    const void* B;          /* [rank x d_ffn]  row-major, E                               */
+    const float* c;         /* [d_ffn] per-neuron offset, fp32; may be NULL (= 0)         */
+    /* bias of the ReLU'd projection per original neuron (device, read-only)             */
+    const float* b;         /* [d_ffn] fp32                                               */
+    /* bundle store: PINNED HOST memory (hipHostMalloc or equivalent), read-only         */
+    const void* host_bundles; /* [d_ffn x G*d_model] E, row i = (gate_i |) up_i | down_i   */
+    /* neuron cache (device, read-write; Section 3.3 "matrix", "pointers", "bias")       */
+    void* matrix;           /* [capacity_rows x G*d_model] E                              */
+    int32_t* pointers;      /* [capacity_rows] slot -> original neuron id                 */
+    float* bias;            /* [capacity_rows] fp32                                       */
+    /* per original neuron: last step at which it was predicted active ("last_k_active") */
+    int32_t* last_active;   /* [d_ffn] int32 (device, read-write)                         */
+    /* scratch (device, read-write), at least lif_workspace_bytes(cfg) bytes, 256-aligned */
+    void* workspace;
+    size_t workspace_bytes;
+} lif_buffers;
+
+typedef struct lif_state {
+    int32_t num_used;       /* rows of the cache in use                                   */
+    int32_t step;           /* number of completed lif_update_window calls since reset    */
+    int32_t error;          /* LIF_OK or LIF_CAPACITY (sticky until lif_reset)            */
+    int32_t last_added;     /* |added| of the last lif_update_window                      */
+    int32_t last_removed;   /* |removed| of the last lif_update_window                    */
+    int32_t last_moved;     /* rows moved by the last deletion                            */
+} lif_state;
+
+typedef struct lif_counters {
+    uint64_t steps;         /* lif_update_window calls that committed                     */
+    uint64_t added;         /* sum of |added|                                             */
+    uint64_t removed;       /* sum of |removed|                                           */
+    uint64_t rows_moved;    /* rows rewritten inside the cache by deletions               */
+    uint64_t h2d_bytes;     /* bytes read from the host bundle store                      */
+} lif_counters;
+
+/* Kernels timed by the profiling hooks, in the order of lif_profile_collect's arrays. */
+enum lif_kernel_id {
+    LIF_K_PREDICT_XA = 0,   /* t = x A                                                    */
+    LIF_K_PREDICT_MASK = 1, /* logits = t B + c, threshold, pack                          */
+    LIF_K_WINDOW = 2,       /* window diff + compaction of added / removed ids            */
+    LIF_K_PLAN = 3,         /* dead-slot scan, hole/filler pairing                        */
+    LIF_K_LOAD = 4,         /* row moves + host-to-device bundle append                   */
+    LIF_K_FFN_UP = 5,       /* activations of all cached rows                             */
+    LIF_K_FFN_DOWN = 6,     /* y = sum of activation x down column                        */
+    LIF_K_COUNT = 7
+};
+
+/* Bytes of scratch lif_create needs for this configuration (0 if cfg is invalid). */
+size_t lif_workspace_bytes(const lif_config* cfg);
+
+/*
+ * Build a layer handle over caller-owned arrays (Section 3.3: everything is
+ * preallocated once).  Validates shapes and alignment, records the device alias of
+ * the pinned bundle store, and enqueues nothing: call lif_reset before the first step.
+ * Errors: LIF_INVALID_ARG (null/unsupported), LIF_HIP_ERROR (bundle store is not
+ * device-accessible pinned memory).
+ */
+int lif_create(const lif_config* cfg, const lif_buffers* buf, lif_layer** out);
+
+/* Frees the host-side handle only (never the caller's arrays). NULL is accepted. */
+int lif_destroy(lif_layer* layer);
+
+/*
+ * Empty the cache (Section 3.3: num_used starts at zero): num_used = 0, every
+ * neuron "never active", step = 0, error flag and counters cleared.  Enqueued on
+ * `stream`; does not touch the matrix contents.
+ */
+int lif_reset(lif_layer* layer, void* stream);
+
+/*
+ * Step 1, low-rank predictor (Section 3.1 "Anticipating ReLU Sparsity", Fig. 3b;
+ * active = positive output, Section 3.1 "The Sliding Window Technique").
+ *   x_dev          [batch x d_model] E, device, read-only
+ *   masks_dev      [batch x d_ffn/8] bytes, device, written: bit (i mod 8) of byte i/8
+ *                  of row t is 1 iff ((x_t A) B)_i + c_i > threshold
+ *   step_mask_dev  [d_ffn/8] bytes, device, written: OR of the batch's masks; may equal
+ *                  masks_dev when batch == 1
+ * Sums are accumulated in fp64 so the decision does not depend on summation order
+ * beyond ~1e-15 relative.  NaN logits compare false (inactive).
+ */
+int lif_predict(lif_layer* layer, const void* x_dev, int32_t batch,
+                uint8_t* masks_dev, uint8_t* step_mask_dev, void* stream);
+
+/*
+ * Step 2, sliding window (Section 3.1 "The Sliding Window Technique", Fig. 4b).
+ * With S_t = union of the last window_k step masks (this one included):
+ *   added_dev    [d_ffn] int32, device, written: S_t \ S_{t-1}, ascending neuron id
+ *   removed_dev  [d_ffn] int32, device, written: S_{t-1} \ S_t, ascending neuron id
+ *   n_added_dev, n_removed_dev  [1] int32, device, written: the two counts
+ * Updates last_active and advances the step counter.  If |S_t| would exceed
+ * capacity_rows nothing is changed, both counts are written as 0 and the sticky
+ * error flag is set to LIF_CAPACITY.
+ * Must alternate with lif_load_bundles (LIF_BAD_STATE otherwise): the cache has to
+ * hold S_{t-1} when the window moves.
+ */
+int lif_update_window(lif_layer* layer, const uint8_t* step_mask_dev,
+                      int32_t* added_dev, int32_t* n_added_dev,
+                      int32_t* removed_dev, int32_t* n_removed_dev, void* stream);
+
+/*
+ * Step 3, cache update (Section 3.3 items 1 and 2, Fig. 6; bundles per Section 3.2).
+ * Deletion: with c = *n_removed_dev and n' = num_used - c, the rows whose neuron left
+ * the window are overwritten by the last rows: the j-th lowest dead slot below n'
+ * receives the j-th highest live slot at or above n' (matrix row, pointer and bias
+ * move together; at most c rows move).  Insertion: the bundle of the j-th added
+ * neuron a_j is read from host_bundles[a_j] and written to row n' + j, with
+ * pointers[n'+j] = a_j and bias[n'+j] = b[a_j]; num_used = n' + *n_added_dev.
+ * The arguments must be the arrays written by the preceding lif_update_window.
+ * Adds |added| x bundle bytes to the h2d_bytes counter.  LIF_BAD_STATE if no
+ * lif_update_window is pending.
+ */
+int lif_load_bundles(lif_layer* layer, const int32_t* added_dev, const int32_t* n_added_dev,
+                     const int32_t* removed_dev, const int32_t* n_removed_dev, void* stream);
+
+/*
+ * Step 4, FFN over the cached rows (Section 3.3 item 3):
+ *   y_t = sum_{s < num_used} relu(up_s . x_t + bias_s) * down_s
+ *   gated:  y_t = sum_s relu(gate_s . x_t + bias_s) * (up_s . x_t) * down_s
+ * over every row in use (the whole window union).  Products of E-typed values,
+ * fp32 accumulation, y rounded once to E.
+ *   x_dev  [batch x d_model] E, device, read-only
+ *   y_dev  [batch x d_model] E, device, overwritten (zeros when the cache is empty)
+ * The summation order is fixed (slot order within fixed strides), so results are
+ * reproducible run to run.
+ */
+int lif_sparse_ffn(lif_layer* layer, const void* x_dev, int32_t batch, void* y_dev, void* stream);
+
+/* Synchronises `stream`, then copies the device-side state / counters to the host. */
+int lif_get_state(lif_layer* layer, lif_state* out, void* stream);
+int lif_get_counters(lif_layer* layer, lif_counters* out, void* stream);
+
+/*
+ * Per-kernel timing with HIP events recorded on the caller's stream around every
+ * kernel of the hot calls.  lif_profile_begin(layer, max_launches) creates the events
+ * (host objects only) and switches timing on; lif_profile_collect synchronises the
+ * stream, adds up elapsed milliseconds and launch counts per enum lif_kernel_id into
+ * ms[LIF_K_COUNT] / launches[LIF_K_COUNT], destroys the events and switches timing off.
+ * Launches beyond max_launches are not timed.
+ */
+int lif_profile_begin(lif_layer* layer, int32_t max_launches);
+int lif_profile_collect(lif_layer* layer, double* ms, int64_t* launches, void* stream);
+
+/* Message of the last LIF_HIP_ERROR / LIF_INVALID_ARG on the calling thread. */
+const char* lif_last_error_string(void);
+
+/* Library version, for the loader check. */
+int lif_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LIF_H */

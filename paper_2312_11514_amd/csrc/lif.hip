@@ -1,0 +1,406 @@
+// C ABI of the sparse-FFN hot path (see include/lif.h for the contract of every call).
+// Host side only: argument checks, launch geometry, call-order bookkeeping, event timing.
+#include "../../include/lif.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "lif_common.h"
+#include "lif_ffn.h"
+#include "lif_predict.h"
+#include "lif_window.h"
+
+using namespace lif;
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, const char* detail = "") {
+    snprintf(g_err, sizeof(g_err), fmt, detail);
+    return code;
+}
+
+#define LIF_HIP(call)                                                             \
+    do {                                                                          \
+        hipError_t e_ = (call);                                                   \
+        if (e_ != hipSuccess) return fail(LIF_HIP_ERROR, #call ": %s", hipGetErrorString(e_)); \
+    } while (0)
+
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+struct Layout {
+    size_t state, tpart, move_dst, hole_list, h, total;
+};
+
+int elem_bytes(const lif_config& c) { return c.dtype == LIF_F32 ? 4 : 2; }
+int vec_elems(const lif_config& c) { return 16 / elem_bytes(c); }
+int xa_chunks(const lif_config& c) { return (c.d_model + kXaRows - 1) / kXaRows; }
+
+bool config_ok(const lif_config* c, const char** why) {
+    *why = "";
+    if (!c) return (*why = "null config", false);
+    if (c->dtype != LIF_F32 && c->dtype != LIF_F16) return (*why = "dtype", false);
+    const int ve = vec_elems(*c);
+    if (c->d_model <= 0 || c->d_model % ve) return (*why = "d_model must be a positive multiple of 16 bytes", false);
+    if ((c->d_model / ve + 63) / 64 > 16) return (*why = "d_model too large (at most 1024 16-byte vectors)", false);
+    if (c->d_ffn <= 0 || c->d_ffn % 8 || c->d_ffn > kScanThreads * kMaxSpan) return (*why = "d_ffn must be a multiple of 8, at most 65536", false);
+    if (c->rank <= 0 || c->rank % ve || c->rank / ve > 256 || c->rank > 2048) return (*why = "rank", false);
+    if (c->window_k < 1 || c->window_k > (1 << 20)) return (*why = "window_k", false);
+    if (c->capacity_rows < 1 || c->capacity_rows > kScanThreads * kMaxSpan) return (*why = "capacity_rows must be in 1..65536", false);
+    if (c->max_batch < 1 || c->max_batch > 8) return (*why = "max_batch must be in 1..8", false);
+    if (c->glu != 0 && c->glu != 1) return (*why = "glu", false);
+    if (c->ffn_mode != LIF_FFN_SKIP_DEAD && c->ffn_mode != LIF_FFN_FULL_BUNDLE) return (*why = "ffn_mode", false);
+    if ((size_t)c->max_batch * c->d_model * elem_bytes(*c) > 64 * 1024) return (*why = "max_batch * d_model exceeds the 64 KiB LDS staging area", false);
+    return true;
+}
+
+Layout make_layout(const lif_config& c) {
+    Layout L;
+    size_t off = 0;
+    L.state = off;
+    off = align_up(off + sizeof(DevState), 256);
+    L.tpart = off;
+    off = align_up(off + sizeof(double) * c.max_batch * xa_chunks(c) * c.rank, 256);
+    L.move_dst = off;
+    off = align_up(off + sizeof(int32_t) * c.capacity_rows, 256);
+    L.hole_list = off;
+    off = align_up(off + sizeof(int32_t) * c.capacity_rows, 256);
+    L.h = off;
+    off = align_up(off + sizeof(float) * c.max_batch * c.capacity_rows, 256);
+    L.total = off;
+    return L;
+}
+
+}  // namespace
+
+struct lif_layer {
+    lif_config cfg;
+    lif_buffers buf;
+    Layout lay;
+    const char* host_alias;     // device-visible address of the pinned bundle store
+    DevState* st;
+    double* tpart;
+    int32_t* move_dst;
+    int32_t* hole_list;
+    float* h;
+    size_t row_elems, row_bytes;
+    bool window_pending;
+    // event timing
+    bool prof_on;
+    int prof_max;
+    std::vector<hipEvent_t> ev;     // 2 per timed launch
+    std::vector<int> ev_kernel;
+};
+
+namespace {
+
+struct Timed {
+    lif_layer* L;
+    hipStream_t s;
+    int slot;
+    Timed(lif_layer* layer, int kid, hipStream_t stream) : L(layer), s(stream), slot(-1) {
+        if (L->prof_on && (int)L->ev_kernel.size() < L->prof_max) {
+            slot = (int)L->ev_kernel.size();
+            L->ev_kernel.push_back(kid);
+            (void)hipEventRecord(L->ev[2 * slot], s);
+        }
+    }
+    ~Timed() {
+        if (slot >= 0) (void)hipEventRecord(L->ev[2 * slot + 1], s);
+    }
+};
+
+template <typename T>
+int launch_predict(lif_layer* L, const void* x, int batch, uint8_t* masks, uint8_t* step_mask, hipStream_t s) {
+    const lif_config& c = L->cfg;
+    const int nch = xa_chunks(c);
+    {
+        Timed t(L, LIF_K_PREDICT_XA, s);
+        hipLaunchKernelGGL((k_predict_xa<T>), dim3(nch, batch), dim3(256), 0, s, (const T*)x, (const T*)L->buf.A,
+                           L->tpart, c.d_model, c.rank, L->st);
+    }
+    const int grid = (c.d_ffn + kMaskCols * 8 - 1) / (kMaskCols * 8);
+    Timed t(L, LIF_K_PREDICT_MASK, s);
+    if (batch == 1 || c.rank > 1024) {
+        hipLaunchKernelGGL((k_predict_mask<T, 1>), dim3(grid), dim3(256), sizeof(double) * c.rank, s,
+                           (const T*)L->buf.B, L->buf.c, L->tpart, nch, c.rank, c.d_ffn, batch, c.threshold, masks,
+                           step_mask, L->st);
+    } else {
+        hipLaunchKernelGGL((k_predict_mask<T, 4>), dim3(grid), dim3(256), sizeof(double) * 4 * c.rank, s,
+                           (const T*)L->buf.B, L->buf.c, L->tpart, nch, c.rank, c.d_ffn, batch, c.threshold, masks,
+                           step_mask, L->st);
+    }
+    return LIF_OK;
+}
+
+template <typename T, bool GLU>
+void launch_ffn_up(lif_layer* L, const void* x, int batch, hipStream_t s) {
+    const lif_config& c = L->cfg;
+    const int nvec = c.d_model / Vec<T>::N;
+    const int ni = (nvec + 63) / 64;
+    const int grid = std::min((c.capacity_rows + 3) / 4, 512);
+    const size_t shm = (size_t)batch * c.d_model * sizeof(T);
+#define LIF_UP(NI)                                                                                           \
+    hipLaunchKernelGGL((k_ffn_up<T, NI, GLU>), dim3(grid), dim3(256), shm, s, (const T*)L->buf.matrix,          \
+                       L->buf.bias, (const T*)x, L->h, c.d_model, batch, c.capacity_rows, L->row_elems, L->st)
+    if (ni <= 1) LIF_UP(1);
+    else if (ni <= 2) LIF_UP(2);
+    else if (ni <= 4) LIF_UP(4);
+    else if (ni <= 6) LIF_UP(6);
+    else if (ni <= 8) LIF_UP(8);
+    else if (ni <= 9) LIF_UP(9);
+    else if (ni <= 12) LIF_UP(12);
+    else LIF_UP(16);
+#undef LIF_UP
+}
+
+template <typename T>
+void launch_ffn_down(lif_layer* L, int batch, void* y, hipStream_t s) {
+    const lif_config& c = L->cfg;
+    const int cols = kDownLanes * Vec<T>::N;
+    const int grid = (c.d_model + cols - 1) / cols;
+    const int down_off = (c.glu ? 2 : 1) * c.d_model;
+    const bool skip = c.ffn_mode == LIF_FFN_SKIP_DEAD;
+#define LIF_DOWN(BT, SKIP)                                                                                  \
+    hipLaunchKernelGGL((k_ffn_down<T, BT, SKIP>), dim3(grid), dim3(256), 0, s, (const T*)L->buf.matrix, L->h,  \
+                       (T*)y, c.d_model, batch, c.capacity_rows, L->row_elems, down_off, L->st)
+    if (batch == 1) { if (skip) LIF_DOWN(1, true); else LIF_DOWN(1, false); }
+    else if (batch <= 4) { if (skip) LIF_DOWN(4, true); else LIF_DOWN(4, false); }
+    else { if (skip) LIF_DOWN(8, true); else LIF_DOWN(8, false); }
+#undef LIF_DOWN
+}
+
+int check_launch() {
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(LIF_HIP_ERROR, "kernel launch: %s", hipGetErrorString(e));
+    return LIF_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int lif_version(void) { return 1; }
+
+const char* lif_last_error_string(void) { return g_err; }
+
+size_t lif_workspace_bytes(const lif_config* cfg) {
+    const char* why;
+    if (!config_ok(cfg, &why)) return 0;
+    return make_layout(*cfg).total;
+}
+
+int lif_create(const lif_config* cfg, const lif_buffers* buf, lif_layer** out) {
+    const char* why;
+    if (!out) return fail(LIF_INVALID_ARG, "out is null");
+    *out = nullptr;
+    if (!config_ok(cfg, &why)) return fail(LIF_INVALID_ARG, "invalid config: %s", why);
+    if (!buf) return fail(LIF_INVALID_ARG, "buffers are null");
+    if (!buf->A || !buf->B || !buf->b || !buf->host_bundles || !buf->matrix || !buf->pointers || !buf->bias ||
+        !buf->last_active || !buf->workspace)
+        return fail(LIF_INVALID_ARG, "a required buffer is null");
+    const void* ptrs[] = {buf->A, buf->B, buf->host_bundles, buf->matrix, buf->last_active};
+    for (const void* p : ptrs)
+        if ((uintptr_t)p % 16) return fail(LIF_INVALID_ARG, "A, B, host_bundles, matrix and last_active must be 16-byte aligned");
+    if ((uintptr_t)buf->workspace % 256) return fail(LIF_INVALID_ARG, "workspace must be 256-byte aligned");
+    Layout lay = make_layout(*cfg);
+    if (buf->workspace_bytes < lay.total) return fail(LIF_INVALID_ARG, "workspace smaller than lif_workspace_bytes");
+
+    void* alias = nullptr;
+    LIF_HIP(hipHostGetDevicePointer(&alias, const_cast<void*>(buf->host_bundles), 0));
+    if (!alias) return fail(LIF_HIP_ERROR, "bundle store has no device alias");
+
+    lif_layer* L = new (std::nothrow) lif_layer();
+    if (!L) return fail(LIF_INVALID_ARG, "out of host memory");
+    L->cfg = *cfg;
+    L->buf = *buf;
+    L->lay = lay;
+    L->host_alias = (const char*)alias;
+    char* ws = (char*)buf->workspace;
+    L->st = (DevState*)(ws + lay.state);
+    L->tpart = (double*)(ws + lay.tpart);
+    L->move_dst = (int32_t*)(ws + lay.move_dst);
+    L->hole_list = (int32_t*)(ws + lay.hole_list);
+    L->h = (float*)(ws + lay.h);
+    L->row_elems = (size_t)(cfg->glu ? 3 : 2) * cfg->d_model;
+    L->row_bytes = L->row_elems * elem_bytes(*cfg);
+    L->window_pending = false;
+    L->prof_on = false;
+    L->prof_max = 0;
+    *out = L;
+    return LIF_OK;
+}
+
+int lif_destroy(lif_layer* layer) {
+    if (!layer) return LIF_OK;
+    for (hipEvent_t e : layer->ev) (void)hipEventDestroy(e);
+    delete layer;
+    return LIF_OK;
+}
+
+int lif_reset(lif_layer* L, void* stream) {
+    if (!L) return fail(LIF_INVALID_ARG, "layer is null");
+    hipStream_t s = (hipStream_t)stream;
+    const int grid = std::min((L->cfg.d_ffn + 255) / 256, 256);
+    hipLaunchKernelGGL(k_reset, dim3(grid), dim3(256), 0, s, L->buf.last_active, L->cfg.d_ffn, L->st);
+    L->window_pending = false;
+    return check_launch();
+}
+
+int lif_predict(lif_layer* L, const void* x_dev, int32_t batch, uint8_t* masks_dev, uint8_t* step_mask_dev,
+                void* stream) {
+    if (!L || !x_dev || !masks_dev || !step_mask_dev) return fail(LIF_INVALID_ARG, "null argument");
+    if (batch < 1 || batch > L->cfg.max_batch) return fail(LIF_INVALID_ARG, "batch out of range");
+    if ((uintptr_t)x_dev % 16) return fail(LIF_INVALID_ARG, "x must be 16-byte aligned");
+    if (batch > 1 && masks_dev == step_mask_dev) return fail(LIF_INVALID_ARG, "step mask must not alias the masks when batch > 1");
+    hipStream_t s = (hipStream_t)stream;
+    if (L->cfg.dtype == LIF_F32) launch_predict<float>(L, x_dev, batch, masks_dev, step_mask_dev, s);
+    else launch_predict<_Float16>(L, x_dev, batch, masks_dev, step_mask_dev, s);
+    return check_launch();
+}
+
+int lif_update_window(lif_layer* L, const uint8_t* step_mask_dev, int32_t* added_dev, int32_t* n_added_dev,
+                      int32_t* removed_dev, int32_t* n_removed_dev, void* stream) {
+    if (!L || !step_mask_dev || !added_dev || !n_added_dev || !removed_dev || !n_removed_dev)
+        return fail(LIF_INVALID_ARG, "null argument");
+    if (L->window_pending) return fail(LIF_BAD_STATE, "lif_update_window called twice without lif_load_bundles");
+    hipStream_t s = (hipStream_t)stream;
+    const lif_config& c = L->cfg;
+    const int span = ((c.d_ffn + kScanThreads - 1) / kScanThreads + 7) / 8 * 8;
+    {
+        Timed t(L, LIF_K_WINDOW, s);
+        hipLaunchKernelGGL(k_window, dim3(1), dim3(kScanThreads), 0, s, step_mask_dev, L->buf.last_active, c.d_ffn,
+                           c.window_k, c.capacity_rows, span, added_dev, n_added_dev, removed_dev, n_removed_dev,
+                           L->st);
+    }
+    L->window_pending = true;
+    return check_launch();
+}
+
+int lif_load_bundles(lif_layer* L, const int32_t* added_dev, const int32_t* n_added_dev, const int32_t* removed_dev,
+                     const int32_t* n_removed_dev, void* stream) {
+    if (!L || !added_dev || !n_added_dev || !removed_dev || !n_removed_dev)
+        return fail(LIF_INVALID_ARG, "null argument");
+    if (!L->window_pending) return fail(LIF_BAD_STATE, "lif_load_bundles needs a preceding lif_update_window");
+    hipStream_t s = (hipStream_t)stream;
+    const lif_config& c = L->cfg;
+    const int span = (c.capacity_rows + kScanThreads - 1) / kScanThreads;
+    {
+        Timed t(L, LIF_K_PLAN, s);
+        hipLaunchKernelGGL(k_plan, dim3(1), dim3(kScanThreads), 0, s, L->buf.pointers, L->buf.last_active,
+                           n_added_dev, c.d_ffn, c.window_k, c.capacity_rows, span, L->move_dst, L->hole_list, L->st);
+    }
+    {
+        const int cpr = (int)((L->row_bytes + 4095) / 4096);
+        const long long worst = (long long)c.capacity_rows * cpr;
+        const int grid = (int)std::min<long long>(worst, 1024);
+        Timed t(L, LIF_K_LOAD, s);
+        hipLaunchKernelGGL(k_load, dim3(grid), dim3(256), 0, s, (char*)L->buf.matrix, L->buf.pointers, L->buf.bias,
+                           L->host_alias, L->buf.b, added_dev, L->move_dst, L->row_bytes, c.d_ffn, L->st);
+    }
+    L->window_pending = false;
+    return check_launch();
+}
+
+int lif_sparse_ffn(lif_layer* L, const void* x_dev, int32_t batch, void* y_dev, void* stream) {
+    if (!L || !x_dev || !y_dev) return fail(LIF_INVALID_ARG, "null argument");
+    if (batch < 1 || batch > L->cfg.max_batch) return fail(LIF_INVALID_ARG, "batch out of range");
+    if ((uintptr_t)x_dev % 16 || (uintptr_t)y_dev % 16) return fail(LIF_INVALID_ARG, "x and y must be 16-byte aligned");
+    hipStream_t s = (hipStream_t)stream;
+    const lif_config& c = L->cfg;
+    {
+        Timed t(L, LIF_K_FFN_UP, s);
+        if (c.dtype == LIF_F32) {
+            if (c.glu) launch_ffn_up<float, true>(L, x_dev, batch, s);
+            else launch_ffn_up<float, false>(L, x_dev, batch, s);
+        } else {
+            if (c.glu) launch_ffn_up<_Float16, true>(L, x_dev, batch, s);
+            else launch_ffn_up<_Float16, false>(L, x_dev, batch, s);
+        }
+    }
+    {
+        Timed t(L, LIF_K_FFN_DOWN, s);
+        if (c.dtype == LIF_F32) launch_ffn_down<float>(L, batch, y_dev, s);
+        else launch_ffn_down<_Float16>(L, batch, y_dev, s);
+    }
+    return check_launch();
+}
+
+static int read_state(lif_layer* L, DevState* host, void* stream) {
+    hipStream_t s = (hipStream_t)stream;
+    LIF_HIP(hipStreamSynchronize(s));
+    LIF_HIP(hipMemcpy(host, L->st, sizeof(DevState), hipMemcpyDeviceToHost));
+    return LIF_OK;
+}
+
+int lif_get_state(lif_layer* L, lif_state* out, void* stream) {
+    if (!L || !out) return fail(LIF_INVALID_ARG, "null argument");
+    DevState h;
+    int rc = read_state(L, &h, stream);
+    if (rc) return rc;
+    out->num_used = h.num_used;
+    out->step = h.step;
+    out->error = h.error;
+    out->last_added = h.n_added;
+    out->last_removed = h.n_removed;
+    out->last_moved = h.n_moved;
+    return LIF_OK;
+}
+
+int lif_get_counters(lif_layer* L, lif_counters* out, void* stream) {
+    if (!L || !out) return fail(LIF_INVALID_ARG, "null argument");
+    DevState h;
+    int rc = read_state(L, &h, stream);
+    if (rc) return rc;
+    out->steps = h.c_steps;
+    out->added = h.c_added;
+    out->removed = h.c_removed;
+    out->rows_moved = h.c_rows_moved;
+    out->h2d_bytes = h.c_h2d_bytes;
+    return LIF_OK;
+}
+
+int lif_profile_begin(lif_layer* L, int32_t max_launches) {
+    if (!L || max_launches < 1 || max_launches > (1 << 20)) return fail(LIF_INVALID_ARG, "bad profile request");
+    for (hipEvent_t e : L->ev) (void)hipEventDestroy(e);
+    L->ev.clear();
+    L->ev_kernel.clear();
+    L->ev.resize(2 * (size_t)max_launches);
+    for (size_t i = 0; i < L->ev.size(); ++i) {
+        hipError_t e = hipEventCreate(&L->ev[i]);
+        if (e != hipSuccess) {
+            L->ev.resize(i);
+            return fail(LIF_HIP_ERROR, "hipEventCreate: %s", hipGetErrorString(e));
+        }
+    }
+    L->prof_max = max_launches;
+    L->prof_on = true;
+    return LIF_OK;
+}
+
+int lif_profile_collect(lif_layer* L, double* ms, int64_t* launches, void* stream) {
+    if (!L || !ms || !launches) return fail(LIF_INVALID_ARG, "null argument");
+    L->prof_on = false;
+    LIF_HIP(hipStreamSynchronize((hipStream_t)stream));
+    for (int k = 0; k < LIF_K_COUNT; ++k) {
+        ms[k] = 0.0;
+        launches[k] = 0;
+    }
+    for (size_t i = 0; i < L->ev_kernel.size(); ++i) {
+        float t = 0.f;
+        LIF_HIP(hipEventElapsedTime(&t, L->ev[2 * i], L->ev[2 * i + 1]));
+        ms[L->ev_kernel[i]] += t;
+        launches[L->ev_kernel[i]] += 1;
+    }
+    for (hipEvent_t e : L->ev) (void)hipEventDestroy(e);
+    L->ev.clear();
+    L->ev_kernel.clear();
+    return LIF_OK;
+}
+
+}  // extern "C"

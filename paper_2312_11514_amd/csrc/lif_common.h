@@ -1,0 +1,98 @@
+// Shared device-side definitions of the sparse-FFN hot path (gfx950, wave64).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace lif {
+
+constexpr int kWave = 64;
+constexpr int32_t kNever = -(1 << 30);   // "never predicted active" in last_active
+
+// Device-resident state of one layer.  Lives at the start of the caller's workspace so
+// that the hot calls chain on a stream without the host ever knowing a count.
+struct DevState {
+    int32_t num_used;     // rows of the cache in use (Section 3.3 "num_used")
+    int32_t n_base;       // rows kept after the pending deletion (n' = num_used - c)
+    int32_t step;         // completed window updates
+    int32_t error;        // sticky lif_status (0 or LIF_CAPACITY)
+    int32_t n_added;      // |added| of the pending / last update
+    int32_t n_removed;    // |removed| of the pending / last update
+    int32_t n_moved;      // rows moved by the last deletion
+    int32_t pad;
+    unsigned long long c_steps, c_added, c_removed, c_rows_moved, c_h2d_bytes;
+};
+
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// 16-byte vector view of the element type.
+template <typename T> struct Vec;
+template <> struct Vec<_Float16> {
+    using type = f16x8;
+    static constexpr int N = 8;
+};
+template <> struct Vec<float> {
+    using type = f32x4;
+    static constexpr int N = 4;
+};
+
+// acc + sum_e a[e] * b[e], products of E-typed values, fp32 accumulation.
+__device__ __forceinline__ float dot_acc(f16x8 a, f16x8 b, float acc) {
+#if __has_builtin(__builtin_amdgcn_fdot2)
+    acc = __builtin_amdgcn_fdot2(__builtin_shufflevector(a, a, 0, 1), __builtin_shufflevector(b, b, 0, 1), acc, false);
+    acc = __builtin_amdgcn_fdot2(__builtin_shufflevector(a, a, 2, 3), __builtin_shufflevector(b, b, 2, 3), acc, false);
+    acc = __builtin_amdgcn_fdot2(__builtin_shufflevector(a, a, 4, 5), __builtin_shufflevector(b, b, 4, 5), acc, false);
+    acc = __builtin_amdgcn_fdot2(__builtin_shufflevector(a, a, 6, 7), __builtin_shufflevector(b, b, 6, 7), acc, false);
+#else
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc = __builtin_fmaf((float)a[e], (float)b[e], acc);
+#endif
+    return acc;
+}
+__device__ __forceinline__ float dot_acc(f32x4 a, f32x4 b, float acc) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) acc = __builtin_fmaf(a[e], b[e], acc);
+    return acc;
+}
+
+// Sum over the 64 lanes of a wave; every lane receives the result.  The butterfly
+// adds the same pairs in every lane, so all lanes hold the bit-identical sum.
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, kWave);
+    return v;
+}
+
+// Inclusive prefix sum over the lanes of a wave.
+__device__ __forceinline__ int wave_inclusive_scan(int v, int lane) {
+#pragma unroll
+    for (int o = 1; o < kWave; o <<= 1) {
+        int u = __shfl_up(v, o, kWave);
+        if (lane >= o) v += u;
+    }
+    return v;
+}
+
+// Exclusive prefix sum of one int per thread over a whole workgroup (thread order).
+// `wave_tot` is LDS scratch of at least blockDim.x / 64 ints.  Returns the exclusive
+// prefix; *total receives the workgroup sum.  Contains two barriers.
+__device__ __forceinline__ int block_exclusive_scan(int v, int* wave_tot, int* total) {
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), w = tid >> 6;
+    const int nw = (blockDim.x + kWave - 1) >> 6;
+    int inc = wave_inclusive_scan(v, lane);
+    __syncthreads();                       // wave_tot may still be read from a previous scan
+    if (lane == kWave - 1) wave_tot[w] = inc;
+    __syncthreads();
+    int before = 0, all = 0;
+    for (int i = 0; i < nw; ++i) {
+        int t = wave_tot[i];
+        if (i < w) before += t;
+        all += t;
+    }
+    *total = all;
+    return before + inc - v;
+}
+
+}  // namespace lif

@@ -1,0 +1,188 @@
+// Step 4: FFN over the cached rows (Section 3.3 item 3):
+//   y = sum_{s < num_used} relu(up_s . x + bias_s) * down_s        (gated: relu(gate_s . x + bias_s) * (up_s . x))
+//
+// Two kernels, both pure streaming of bundle bytes (1 flop per byte at fp16):
+//   ffn_up    one wave per cached row: all 16-byte loads of the row's up (and gate) vector are
+//             issued before the first use, x is staged once per workgroup in LDS, the wave
+//             reduces the dot product and writes the activation h[s].
+//   ffn_down  one workgroup per slice of output columns: it owns those columns of y, so no
+//             cross-workgroup reduction or atomics are needed and the summation order is
+//             fixed.  It compacts the rows with a non-zero activation (ballot-free ordered
+//             scan in LDS) and streams only their down columns.
+#pragma once
+
+#include "lif_common.h"
+
+namespace lif {
+
+// grid-stride over rows, block = 256 (4 waves, one row per wave at a time).
+// NI = 16-byte loads per lane and vector (ceil(d / (64 * VE))); dynamic LDS: batch * d elements.
+template <typename T, int NI, bool GLU>
+__global__ __launch_bounds__(256) void k_ffn_up(const T* __restrict__ matrix, const float* __restrict__ bias,
+                                                const T* __restrict__ x, float* __restrict__ h, int d, int batch,
+                                                int capacity, size_t row_elems, const DevState* __restrict__ st) {
+    using V = typename Vec<T>::type;
+    constexpr int VE = Vec<T>::N;
+    if (st->error) return;
+    const int n = st->num_used;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    V* xs = reinterpret_cast<V*>(smem_raw);
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int nvec = d / VE;
+    const int gw = blockIdx.x * 4 + (tid >> 6), nw = gridDim.x * 4;
+    if (blockIdx.x * 4 >= n) return;                 // whole workgroup has no row (uniform)
+
+    {
+        const V* xv = reinterpret_cast<const V*>(x);
+        for (int i = tid; i < batch * nvec; i += 256) xs[i] = xv[i];
+    }
+    __syncthreads();
+
+    for (int s = gw; s < n; s += nw) {
+        const V* row = reinterpret_cast<const V*>(matrix + (size_t)s * row_elems);
+        V u[NI], g[GLU ? NI : 1];
+#pragma unroll
+        for (int it = 0; it < NI; ++it) {
+            const int idx = it * 64 + lane;
+            if (idx < nvec) {
+                if (GLU) {
+                    g[it] = row[idx];
+                    u[it] = row[nvec + idx];
+                } else {
+                    u[it] = row[idx];
+                }
+            } else {
+                u[it] = V(0);
+                if (GLU) g[it] = V(0);
+            }
+        }
+        const float bs = bias[s];
+        for (int b = 0; b < batch; ++b) {
+            float du = 0.f, dg = 0.f;
+#pragma unroll
+            for (int it = 0; it < NI; ++it) {
+                const int idx = it * 64 + lane;
+                if (idx < nvec) {
+                    const V xv = xs[b * nvec + idx];
+                    du = dot_acc(u[it], xv, du);
+                    if (GLU) dg = dot_acc(g[it], xv, dg);
+                }
+            }
+            du = wave_sum(du);
+            float act;
+            if (GLU) {
+                dg = wave_sum(dg);
+                act = fmaxf(dg + bs, 0.f) * du;
+            } else {
+                act = fmaxf(du + bs, 0.f);
+            }
+            if (lane == 0) h[(size_t)b * capacity + s] = act;
+        }
+    }
+}
+
+constexpr int kDownLanes = 4;       // lanes per column slice (4 x 16 B = 64 B of every down column)
+constexpr int kDownRg = 64;         // row groups per workgroup
+constexpr int kDownTile = 2048;     // cached rows compacted per pass
+
+// grid = ceil(d / (4 * VE)), block = 256 = 64 row groups x 4 lanes.
+// SKIP: rows whose activation is zero for every token of the batch are not read.
+template <typename T, int BT, bool SKIP>
+__global__ __launch_bounds__(256) void k_ffn_down(const T* __restrict__ matrix, const float* __restrict__ h,
+                                                  T* __restrict__ y, int d, int batch, int capacity,
+                                                  size_t row_elems, int down_off,
+                                                  const DevState* __restrict__ st) {
+    using V = typename Vec<T>::type;
+    constexpr int VE = Vec<T>::N;
+    constexpr int TS = kDownTile / BT;
+    constexpr int PER = TS / 256;                    // slots per thread in the compaction
+    if (st->error) return;
+    const int n = st->num_used;
+    __shared__ int list[TS];
+    __shared__ float hv[BT][TS];
+    __shared__ int wave_tot[4];
+    __shared__ float red[4][kDownLanes][BT][VE];
+
+    const int tid = threadIdx.x, l = tid & (kDownLanes - 1), rg = tid >> 2;
+    const int col = blockIdx.x * (kDownLanes * VE) + l * VE;
+    const bool col_ok = col < d;
+    const T* base = matrix + down_off + col;
+
+    float acc[BT][VE];
+#pragma unroll
+    for (int b = 0; b < BT; ++b)
+#pragma unroll
+        for (int e = 0; e < VE; ++e) acc[b][e] = 0.f;
+
+    for (int s_base = 0; s_base < n; s_base += TS) {
+        // ordered compaction of the rows that contribute
+        float hloc[PER][BT];
+        unsigned flags = 0;
+#pragma unroll
+        for (int q = 0; q < PER; ++q) {
+            const int s = s_base + tid * PER + q;
+            bool any = false;
+#pragma unroll
+            for (int b = 0; b < BT; ++b) {
+                float v = 0.f;
+                if (s < n && b < batch) v = h[(size_t)b * capacity + s];
+                hloc[q][b] = v;
+                any |= (v != 0.f);
+            }
+            if (!SKIP) any = s < n;
+            if (any) flags |= 1u << q;
+        }
+        int cnt;
+        int off = block_exclusive_scan(__popc(flags), wave_tot, &cnt);
+#pragma unroll
+        for (int q = 0; q < PER; ++q) {
+            if (flags & (1u << q)) {
+                list[off] = s_base + tid * PER + q;
+#pragma unroll
+                for (int b = 0; b < BT; ++b) hv[b][off] = hloc[q][b];
+                ++off;
+            }
+        }
+        __syncthreads();
+        if (col_ok) {
+#pragma unroll 4
+            for (int i = rg; i < cnt; i += kDownRg) {
+                const int s = list[i];
+                const V v = *reinterpret_cast<const V*>(base + (size_t)s * row_elems);
+#pragma unroll
+                for (int b = 0; b < BT; ++b) {
+                    const float hb = hv[b][i];
+#pragma unroll
+                    for (int e = 0; e < VE; ++e) acc[b][e] = __builtin_fmaf(hb, (float)v[e], acc[b][e]);
+                }
+            }
+        }
+        __syncthreads();
+    }
+    // row groups of one wave sit 4 lanes apart: butterfly over lane bits 2..5, then LDS over waves
+#pragma unroll
+    for (int b = 0; b < BT; ++b)
+#pragma unroll
+        for (int e = 0; e < VE; ++e) {
+            float v = acc[b][e];
+            v += __shfl_xor(v, 4, kWave);
+            v += __shfl_xor(v, 8, kWave);
+            v += __shfl_xor(v, 16, kWave);
+            v += __shfl_xor(v, 32, kWave);
+            if ((tid & 63) < kDownLanes) red[tid >> 6][l][b][e] = v;
+        }
+    __syncthreads();
+    if (tid < kDownLanes * BT) {
+        const int b = tid / kDownLanes, l2 = tid - b * kDownLanes;
+        const int col2 = blockIdx.x * (kDownLanes * VE) + l2 * VE;
+        if (col2 < d && b < batch) {
+            V out;
+#pragma unroll
+            for (int e = 0; e < VE; ++e)
+                out[e] = (T)(((red[0][l2][b][e] + red[1][l2][b][e]) + red[2][l2][b][e]) + red[3][l2][b][e]);
+            *reinterpret_cast<V*>(y + (size_t)b * d + col2) = out;
+        }
+    }
+}
+
+}  // namespace lif

@@ -1,0 +1,163 @@
+// Step 1: low-rank predictor  mask_i = [ ((x A) B)_i + c_i > theta ]
+// (Section 3.1 "Anticipating ReLU Sparsity", Fig. 3b; active = strictly positive output).
+//
+// Both contractions accumulate in fp64: every product of two fp16 or two fp32 values is
+// exact in fp64, so the result depends on the summation order only at the 1e-16 level
+// and the thresholded bits can be compared bit for bit with a CPU evaluation.  The path
+// stays bandwidth bound (one fp64 FMA per 2 or 4 bytes read).
+#pragma once
+
+#include "lif_common.h"
+
+namespace lif {
+
+constexpr int kXaRows = 256;       // rows of A per workgroup of predict_xa
+constexpr int kMaskCols = 16;      // mask bytes (groups of 8 neurons) per workgroup of predict_mask
+constexpr int kMaskJg = 16;        // rank groups per workgroup of predict_mask
+
+// t_partial[b][chunk][j] = sum_{i in chunk} x[b][i] * A[i][j]
+// grid = (ceil(d / kXaRows), batch), block = 256.
+// Thread (rl, cl): column lanes cl cover a row of A with 16-byte loads, rl strides rows.
+template <typename T>
+__global__ __launch_bounds__(256) void k_predict_xa(const T* __restrict__ x, const T* __restrict__ A,
+                                                    double* __restrict__ tpart, int d, int r,
+                                                    const DevState* __restrict__ st) {
+    using V = typename Vec<T>::type;
+    constexpr int VE = Vec<T>::N;
+    if (st->error) return;
+    __shared__ float xs[kXaRows];
+    __shared__ double red[256 * VE];
+
+    const int tid = threadIdx.x;
+    const int lpr = r / VE;                 // lanes per row (host guarantees 1 <= lpr <= 256)
+    const int rp = 256 / lpr;               // rows per pass
+    const int rl = tid / lpr, cl = tid - rl * lpr;
+    const int chunk = blockIdx.x, b = blockIdx.y, nchunks = gridDim.x;
+    const int row0 = chunk * kXaRows;
+    const int nrows = min(kXaRows, d - row0);
+
+    for (int i = tid; i < nrows; i += 256) xs[i] = (float)x[(size_t)b * d + row0 + i];
+    __syncthreads();
+
+    double acc[VE];
+#pragma unroll
+    for (int e = 0; e < VE; ++e) acc[e] = 0.0;
+    if (rl < rp) {
+        const V* __restrict__ Av = reinterpret_cast<const V*>(A) + (size_t)row0 * lpr + cl;
+#pragma unroll 8
+        for (int i = rl; i < nrows; i += rp) {
+            V a = Av[(size_t)i * lpr];
+            double xv = (double)xs[i];
+#pragma unroll
+            for (int e = 0; e < VE; ++e) acc[e] = __builtin_fma(xv, (double)a[e], acc[e]);
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < VE; ++e) red[tid * VE + e] = acc[e];
+    __syncthreads();
+    // column j lives in lane cl = j / VE, element e = j % VE; rows-in-pass summed ascending
+    for (int j = tid; j < r; j += 256) {
+        const int jc = j / VE, je = j - jc * VE;
+        double s = 0.0;
+        for (int q = 0; q < rp; ++q) s += red[(q * lpr + jc) * VE + je];
+        tpart[((size_t)b * nchunks + chunk) * r + j] = s;
+    }
+}
+
+// logits = t B + c, threshold, pack 8 neurons per byte; step mask = OR over the batch.
+// grid = ceil(F / 128), block = 256 = 16 rank groups x 16 column lanes; each column lane
+// owns 8 consecutive neurons = one mask byte.  dynamic LDS: BT * r doubles.
+template <typename T, int BT>
+__global__ __launch_bounds__(256) void k_predict_mask(const T* __restrict__ B, const float* __restrict__ c,
+                                                      const double* __restrict__ tpart, int nchunks, int r,
+                                                      int F, int batch, float theta,
+                                                      uint8_t* __restrict__ masks, uint8_t* __restrict__ step_mask,
+                                                      const DevState* __restrict__ st) {
+    using V = typename Vec<T>::type;
+    constexpr int VE = Vec<T>::N;
+    constexpr int LPB = 8 / VE;             // 16-byte loads per group of 8 neurons
+    if (st->error) return;
+    extern __shared__ double tl[];          // [BT][r]
+    __shared__ double red[4][kMaskCols][BT][8];
+    __shared__ uint8_t bytes[BT][kMaskCols];
+
+    const int tid = threadIdx.x, wave = tid >> 6;
+    const int cl = tid & (kMaskCols - 1), jg = tid >> 4;
+    const int n0 = (blockIdx.x * kMaskCols + cl) * 8;
+    const bool col_ok = n0 < F;
+    const int mask_stride = F >> 3;
+    const double th = (double)theta;
+    uint8_t or_byte = 0;
+
+    for (int b0 = 0; b0 < batch; b0 += BT) {
+        __syncthreads();
+        for (int idx = tid; idx < BT * r; idx += 256) {
+            const int bt = idx / r, j = idx - bt * r;
+            double s = 0.0;
+            if (b0 + bt < batch) {
+                const double* p = tpart + ((size_t)(b0 + bt) * nchunks) * r + j;
+                for (int ch = 0; ch < nchunks; ++ch) s += p[(size_t)ch * r];
+            }
+            tl[idx] = s;
+        }
+        __syncthreads();
+
+        double acc[BT][8];
+#pragma unroll
+        for (int bt = 0; bt < BT; ++bt)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[bt][e] = 0.0;
+        if (col_ok) {
+#pragma unroll 4
+            for (int j = jg; j < r; j += kMaskJg) {
+                const V* bp = reinterpret_cast<const V*>(B + (size_t)j * F + n0);
+                V bv[LPB];
+#pragma unroll
+                for (int q = 0; q < LPB; ++q) bv[q] = bp[q];
+#pragma unroll
+                for (int bt = 0; bt < BT; ++bt) {
+                    const double tj = tl[bt * r + j];
+#pragma unroll
+                    for (int q = 0; q < LPB; ++q)
+#pragma unroll
+                        for (int e = 0; e < VE; ++e)
+                            acc[bt][q * VE + e] = __builtin_fma(tj, (double)bv[q][e], acc[bt][q * VE + e]);
+                }
+            }
+        }
+        // the four rank groups of a wave sit 16 lanes apart: butterfly, then LDS across waves
+#pragma unroll
+        for (int bt = 0; bt < BT; ++bt)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                double v = acc[bt][e];
+                v += __shfl_xor(v, 16, kWave);
+                v += __shfl_xor(v, 32, kWave);
+                if ((tid & 63) < kMaskCols) red[wave][cl][bt][e] = v;
+            }
+        __syncthreads();
+        if (tid < kMaskCols * BT) {
+            const int bt = tid / kMaskCols, c2 = tid - bt * kMaskCols;
+            const int n2 = (blockIdx.x * kMaskCols + c2) * 8;
+            uint8_t byte = 0;
+            if (n2 < F && b0 + bt < batch) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    double z = ((red[0][c2][bt][e] + red[1][c2][bt][e]) + red[2][c2][bt][e]) + red[3][c2][bt][e];
+                    if (c) z += (double)c[n2 + e];
+                    if (z > th) byte |= (uint8_t)(1u << e);
+                }
+                masks[(size_t)(b0 + bt) * mask_stride + (n2 >> 3)] = byte;
+            }
+            bytes[bt][c2] = byte;
+        }
+        __syncthreads();
+        if (tid < kMaskCols) {
+#pragma unroll
+            for (int bt = 0; bt < BT; ++bt) or_byte |= bytes[bt][tid];
+        }
+    }
+    if (tid < kMaskCols && n0 < F) step_mask[n0 >> 3] = or_byte;
+}
+
+}  // namespace lif
