@@ -103,6 +103,9 @@ typedef struct lif_counters {
     uint64_t removed;       /* sum of |removed|                                           */
     uint64_t rows_moved;    /* rows rewritten inside the cache by deletions               */
     uint64_t h2d_bytes;     /* bytes read from the host bundle store                      */
+    uint64_t ffn_calls;     /* lif_sparse_ffn calls                                       */
+    uint64_t ffn_rows;      /* sum over those calls of the rows in use                    */
+    uint64_t ffn_active;    /* sum over those calls of the rows with a non-zero activation */
 } lif_counters;
 
 /* Kernels timed by the profiling hooks, in the order of lif_profile_collect's arrays. */

@@ -35,7 +35,8 @@ class LifState(C.Structure):
 
 
 class LifCounters(C.Structure):
-    _fields_ = [(n, C.c_uint64) for n in ("steps", "added", "removed", "rows_moved", "h2d_bytes")]
+    _fields_ = [(n, C.c_uint64) for n in ("steps", "added", "removed", "rows_moved", "h2d_bytes",
+                                          "ffn_calls", "ffn_rows", "ffn_active")]
 
 
 EXPORTS = {

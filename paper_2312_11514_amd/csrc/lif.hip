@@ -362,6 +362,9 @@ int lif_get_counters(lif_layer* L, lif_counters* out, void* stream) {
     out->removed = h.c_removed;
     out->rows_moved = h.c_rows_moved;
     out->h2d_bytes = h.c_h2d_bytes;
+    out->ffn_calls = h.c_ffn_calls;
+    out->ffn_rows = h.c_ffn_rows;
+    out->ffn_active = h.c_ffn_active;
     return LIF_OK;
 }
 

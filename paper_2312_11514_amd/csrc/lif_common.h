@@ -21,6 +21,7 @@ struct DevState {
     int32_t n_moved;      // rows moved by the last deletion
     int32_t pad;
     unsigned long long c_steps, c_added, c_removed, c_rows_moved, c_h2d_bytes;
+    unsigned long long c_ffn_calls, c_ffn_rows, c_ffn_active;   // FFN calls, rows in use, rows with a non-zero activation
 };
 
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));

@@ -90,8 +90,7 @@ constexpr int kDownTile = 2048;     // cached rows compacted per pass
 template <typename T, int BT, bool SKIP>
 __global__ __launch_bounds__(256) void k_ffn_down(const T* __restrict__ matrix, const float* __restrict__ h,
                                                   T* __restrict__ y, int d, int batch, int capacity,
-                                                  size_t row_elems, int down_off,
-                                                  const DevState* __restrict__ st) {
+                                                  size_t row_elems, int down_off, DevState* __restrict__ st) {
     using V = typename Vec<T>::type;
     constexpr int VE = Vec<T>::N;
     constexpr int TS = kDownTile / BT;
@@ -102,6 +101,7 @@ __global__ __launch_bounds__(256) void k_ffn_down(const T* __restrict__ matrix, 
     __shared__ float hv[BT][TS];
     __shared__ int wave_tot[4];
     __shared__ float red[4][kDownLanes][BT][VE];
+    __shared__ int n_active;
 
     const int tid = threadIdx.x, l = tid & (kDownLanes - 1), rg = tid >> 2;
     const int col = blockIdx.x * (kDownLanes * VE) + l * VE;
@@ -114,10 +114,12 @@ __global__ __launch_bounds__(256) void k_ffn_down(const T* __restrict__ matrix, 
 #pragma unroll
         for (int e = 0; e < VE; ++e) acc[b][e] = 0.f;
 
+    if (tid == 0) n_active = 0;
+    __syncthreads();
     for (int s_base = 0; s_base < n; s_base += TS) {
         // ordered compaction of the rows that contribute
         float hloc[PER][BT];
-        unsigned flags = 0;
+        unsigned flags = 0, nonzero = 0;
 #pragma unroll
         for (int q = 0; q < PER; ++q) {
             const int s = s_base + tid * PER + q;
@@ -129,9 +131,11 @@ __global__ __launch_bounds__(256) void k_ffn_down(const T* __restrict__ matrix, 
                 hloc[q][b] = v;
                 any |= (v != 0.f);
             }
+            if (any) nonzero |= 1u << q;
             if (!SKIP) any = s < n;
             if (any) flags |= 1u << q;
         }
+        if (blockIdx.x == 0 && nonzero) atomicAdd(&n_active, __popc(nonzero));   // statistics only
         int cnt;
         int off = block_exclusive_scan(__popc(flags), wave_tot, &cnt);
 #pragma unroll
@@ -172,6 +176,11 @@ __global__ __launch_bounds__(256) void k_ffn_down(const T* __restrict__ matrix, 
             if ((tid & 63) < kDownLanes) red[tid >> 6][l][b][e] = v;
         }
     __syncthreads();
+    if (blockIdx.x == 0 && tid == 0) {
+        st->c_ffn_calls += 1;
+        st->c_ffn_rows += (unsigned long long)n;
+        st->c_ffn_active += (unsigned long long)n_active;
+    }
     if (tid < kDownLanes * BT) {
         const int b = tid / kDownLanes, l2 = tid - b * kDownLanes;
         const int col2 = blockIdx.x * (kDownLanes * VE) + l2 * VE;

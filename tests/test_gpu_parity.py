@@ -50,3 +50,20 @@ def test_ragged_shapes_whole_path(glu, dtype):
     w = wl.scaled(wl.WORKLOADS["C1"], name="ragged", d_model=568, d_ffn=1096, rank=40, window_k=3,
                   p_active=0.08, dtype=dtype, glu=glu, tokens=24, capacity_rows=700)
     run_stream(w, wl.make_layer(w), wl.make_inputs(w))
+
+
+def test_c2_opt_shape_fp16_whole_path():
+    """OPT-6.7B FFN shape at full size, the launch configuration bench.py times (96 tokens)."""
+    w = wl.WORKLOADS["C2"]
+    L = wl.cached_layer("C2")
+    X = wl.make_inputs(w, tokens=96)
+    stats = run_stream(w, L, X, check_every=8)
+    assert np.mean([s["n"] for s in stats[10:]]) > 800         # window union of ~3 % active masks
+    print("C2 max rel-L2 %.2e" % max(s["err"] for s in stats))
+
+
+def test_c2_full_bundle_mode_matches_oracle():
+    w = wl.WORKLOADS["C2"]
+    L = wl.cached_layer("C2")
+    X = wl.make_inputs(w, tokens=24)
+    run_stream(w, L, X, ffn_mode=1, check_every=8)
