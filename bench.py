@@ -58,7 +58,8 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="C2")
-    ap.add_argument("--ffn-mode", default="skip", choices=["skip", "full"])
+    ap.add_argument("--ffn-mode", default="skip", choices=["skip", "full"],
+                    help="skip: down columns read only for rows with a non-zero activation; full: whole bundles")
     ap.add_argument("--no-graph", action="store_true", help="launch every kernel from the host instead of a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true")
@@ -81,7 +82,8 @@ def main():
     L = wl.make_layer(w)
     X = wl.make_batch_inputs(w) if w.batch > 1 else wl.make_inputs(w)
     T = len(X)
-    mode = lif.FFN_SKIP_DEAD if args.ffn_mode == "skip" else lif.FFN_FULL_BUNDLE
+    mode = {"skip": lif.FFN_SKIP_DEAD, "full": lif.FFN_FULL_BUNDLE}[args.ffn_mode]
+    reads_all = args.ffn_mode == "full"
     gpu = GpuLayer(w, L, ffn_mode=mode)
     lay = gpu.layer
     xd = gpu.upload_x(X)                                   # [T, (batch,) d] resident in HBM
@@ -119,18 +121,44 @@ def main():
     ms_per_step = dt / args.steps * 1e3
     us_per_token = ms_per_step * 1e3 / T / w.layers
 
-    # per-kernel durations: HIP events recorded by the library on the launch stream, around every
-    # kernel of one more pass over the same stream
+    # FFN alone, on the cache state the stream ends in: R back-to-back lif_sparse_ffn calls in a HIP graph,
+    # timed with HIP events on the launch stream; the byte count comes from the device counters of those calls
+    R = 200
+    ffn = None
+    if not args.no_profile:
+        c0 = lay.counters()
+        g2 = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g2):
+            for _ in range(R):
+                lay.sparse_ffn(xd[T - 1], yd[T - 1], w.batch)
+        g2.replay()
+        torch.cuda.synchronize()
+        c0 = lay.counters()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = 5
+        e0.record()
+        for _ in range(reps):
+            g2.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        c1 = lay.counters()
+        calls = c1["ffn_calls"] - c0["ffn_calls"]
+        assert calls == R * reps
+        rows = (c1["ffn_rows"] - c0["ffn_rows"]) / calls
+        act = (c1["ffn_active"] - c0["ffn_active"]) / calls
+        ffn = {"us": e0.elapsed_time(e1) * 1e3 / calls, "rows": rows, "active": act}
+
+    # per-kernel durations over one more eager pass of the whole stream: HIP events recorded by the library
+    # on the launch stream around every kernel (these include the event/dispatch overhead of ~2 us per launch)
     kern = {}
     if not args.no_profile:
         lay.profile_begin(7 * T + 8)
         run_stream()
         for k, (ms, n) in lay.profile_collect().items():
-            kern[k] = {"avg_us": ms / max(n, 1) * 1e3, "launches": n}
+            if n:
+                kern[k] = {"avg_us": ms / n * 1e3, "launches": n}
 
     E, d, G = w.elem_bytes, w.d_model, w.vectors_per_bundle
-    bytes_up = rows_per_tok * (G - 1) * d * E               # ffn_up reads the up (and gate) vector of every cached row
-    bytes_down = (active_per_tok if args.ffn_mode == "skip" else rows_per_tok) * d * E
     nominal = rows_per_tok * G * d * E
     out = {
         "metric": "sparse-FFN us/token/layer (whole hot path: predict + window + load + FFN)",
@@ -143,19 +171,22 @@ def main():
         "per_token": {"rows_in_cache": rows_per_tok, "rows_active": active_per_tok, "rows_added": added_per_tok,
                       "h2d_bytes": added_per_tok * w.bundle_bytes, "nominal_bundle_bytes": nominal},
     }
+    if ffn:
+        up_bytes = ffn["rows"] * (G - 1) * d * E
+        down_bytes = (ffn["rows"] if reads_all else ffn["active"]) * d * E
+        touched = up_bytes + down_bytes
+        nominal_f = ffn["rows"] * G * d * E
+        ach = touched / (ffn["us"] * 1e-6) / 1e9
+        out["roofline"] = {"bound": "hbm", "kernel": "ffn_up + ffn_down",
+                           "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
+                           "traffic": None, "algorithmic_bytes_per_launch": touched, "avg_launch_us": ffn["us"],
+                           "rows": ffn["rows"], "rows_active": ffn["active"],
+                           "nominal_bundle_bytes": nominal_f,
+                           "nominal_GBs": nominal_f / (ffn["us"] * 1e-6) / 1e9,
+                           "nominal_frac": nominal_f / (ffn["us"] * 1e-6) / 1e9 / HBM_PEAK_GBS}
     if kern:
-        up_us, down_us = kern["ffn_up"]["avg_us"], kern["ffn_down"]["avg_us"]
-        ach = bytes_up / (up_us * 1e-6) / 1e9
-        out["roofline"] = {"bound": "hbm", "kernel": "ffn_up", "achieved": ach, "peak": HBM_PEAK_GBS,
-                           "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": None,
-                           "algorithmic_bytes_per_launch": bytes_up, "avg_launch_us": up_us}
-        ffn_us = up_us + down_us
-        out["ffn"] = {"us_per_token": ffn_us,
-                      "nominal_bundle_GBs": nominal / (ffn_us * 1e-6) / 1e9,
-                      "nominal_frac_of_hbm_peak": nominal / (ffn_us * 1e-6) / 1e9 / HBM_PEAK_GBS,
-                      "touched_GBs": (bytes_up + bytes_down) / (ffn_us * 1e-6) / 1e9}
         out["h2d"] = {"GBs_in_load_kernel": added_per_tok * w.bundle_bytes / (kern["load"]["avg_us"] * 1e-6) / 1e9}
-        out["kernels_avg_us"] = {k: round(v["avg_us"], 3) for k, v in kern.items()}
+        out["kernels_avg_us_event_timed"] = {k: round(v["avg_us"], 3) for k, v in kern.items()}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, L, X)
     print(json.dumps(out))

@@ -112,12 +112,11 @@ typedef struct lif_counters {
 enum lif_kernel_id {
     LIF_K_PREDICT_XA = 0,   /* t = x A                                                    */
     LIF_K_PREDICT_MASK = 1, /* logits = t B + c, threshold, pack                          */
-    LIF_K_WINDOW = 2,       /* window diff + compaction of added / removed ids            */
-    LIF_K_PLAN = 3,         /* dead-slot scan, hole/filler pairing                        */
-    LIF_K_LOAD = 4,         /* row moves + host-to-device bundle append                   */
-    LIF_K_FFN_UP = 5,       /* activations of all cached rows                             */
-    LIF_K_FFN_DOWN = 6,     /* y = sum of activation x down column                        */
-    LIF_K_COUNT = 7
+    LIF_K_WINDOW = 2,       /* window diff, added / removed ids, deletion plan            */
+    LIF_K_LOAD = 3,         /* row moves + host-to-device bundle append                   */
+    LIF_K_FFN_UP = 4,       /* activations of all cached rows                             */
+    LIF_K_FFN_DOWN = 5,     /* y = sum of activation x down column                        */
+    LIF_K_COUNT = 6
 };
 
 /* Bytes of scratch lif_create needs for this configuration (0 if cfg is invalid). */
@@ -196,7 +195,7 @@ int lif_load_bundles(lif_layer* layer, const int32_t* added_dev, const int32_t* 
  *   x_dev  [batch x d_model] E, device, read-only
  *   y_dev  [batch x d_model] E, device, overwritten (zeros when the cache is empty)
  * The summation order is fixed (slot order within fixed strides), so results are
- * reproducible run to run.
+ * reproducible run to run bit for bit.
  */
 int lif_sparse_ffn(lif_layer* layer, const void* x_dev, int32_t batch, void* y_dev, void* stream);
 

@@ -14,7 +14,7 @@ LIB_PATH = os.path.join(HERE, "liblif.so")
 LIF_OK, LIF_INVALID_ARG, LIF_BAD_STATE, LIF_CAPACITY, LIF_HIP_ERROR = 0, 1, 2, 3, 4
 LIF_F32, LIF_F16 = 0, 1
 FFN_SKIP_DEAD, FFN_FULL_BUNDLE = 0, 1
-KERNEL_NAMES = ("predict_xa", "predict_mask", "window", "plan", "load", "ffn_up", "ffn_down")
+KERNEL_NAMES = ("predict_xa", "predict_mask", "window", "load", "ffn_up", "ffn_down")
 STATUS_NAMES = {0: "OK", 1: "INVALID_ARG", 2: "BAD_STATE", 3: "CAPACITY", 4: "HIP_ERROR"}
 
 

@@ -144,10 +144,11 @@ void launch_ffn_up(lif_layer* L, const void* x, int batch, hipStream_t s) {
     const int nvec = c.d_model / Vec<T>::N;
     const int ni = (nvec + 63) / 64;
     const int grid = std::min((c.capacity_rows + 3) / 4, 512);
-    const size_t shm = (size_t)batch * c.d_model * sizeof(T);
-#define LIF_UP(NI)                                                                                           \
-    hipLaunchKernelGGL((k_ffn_up<T, NI, GLU>), dim3(grid), dim3(256), shm, s, (const T*)L->buf.matrix,          \
+    const size_t shm = batch == 1 ? 0 : (size_t)batch * c.d_model * sizeof(T);
+#define LIF_UP_X(NI, XREG)                                                                                   \
+    hipLaunchKernelGGL((k_ffn_up<T, NI, GLU, XREG>), dim3(grid), dim3(256), shm, s, (const T*)L->buf.matrix,    \
                        L->buf.bias, (const T*)x, L->h, c.d_model, batch, c.capacity_rows, L->row_elems, L->st)
+#define LIF_UP(NI) do { if (batch == 1) LIF_UP_X(NI, true); else LIF_UP_X(NI, false); } while (0)
     if (ni <= 1) LIF_UP(1);
     else if (ni <= 2) LIF_UP(2);
     else if (ni <= 4) LIF_UP(4);
@@ -157,6 +158,7 @@ void launch_ffn_up(lif_layer* L, const void* x, int batch, hipStream_t s) {
     else if (ni <= 12) LIF_UP(12);
     else LIF_UP(16);
 #undef LIF_UP
+#undef LIF_UP_X
 }
 
 template <typename T>
@@ -271,12 +273,30 @@ int lif_update_window(lif_layer* L, const uint8_t* step_mask_dev, int32_t* added
     if (L->window_pending) return fail(LIF_BAD_STATE, "lif_update_window called twice without lif_load_bundles");
     hipStream_t s = (hipStream_t)stream;
     const lif_config& c = L->cfg;
-    const int span = ((c.d_ffn + kScanThreads - 1) / kScanThreads + 7) / 8 * 8;
+    const int span_f = (c.d_ffn + kScanThreads - 1) / kScanThreads;      // neurons per thread, rounded up below
+    const int span_c = (c.capacity_rows + kScanThreads - 1) / kScanThreads;
     {
         Timed t(L, LIF_K_WINDOW, s);
-        hipLaunchKernelGGL(k_window, dim3(1), dim3(kScanThreads), 0, s, step_mask_dev, L->buf.last_active, c.d_ffn,
-                           c.window_k, c.capacity_rows, span, added_dev, n_added_dev, removed_dev, n_removed_dev,
-                           L->st);
+#define LIF_WIN(SF, SC)                                                                                      \
+    hipLaunchKernelGGL((k_window_plan<SF, SC>), dim3(1), dim3(kScanThreads), 0, s, step_mask_dev,                \
+                       L->buf.last_active, L->buf.pointers, c.d_ffn, c.window_k, c.capacity_rows, added_dev,     \
+                       n_added_dev, removed_dev, n_removed_dev, L->move_dst, L->hole_list, L->st)
+#define LIF_WIN_C(SF)                                   \
+    do {                                                \
+        if (span_c <= 1) LIF_WIN(SF, 1);                \
+        else if (span_c <= 2) LIF_WIN(SF, 2);           \
+        else if (span_c <= 4) LIF_WIN(SF, 4);           \
+        else if (span_c <= 8) LIF_WIN(SF, 8);           \
+        else if (span_c <= 16) LIF_WIN(SF, 16);         \
+        else if (span_c <= 32) LIF_WIN(SF, 32);         \
+        else LIF_WIN(SF, 64);                           \
+    } while (0)
+        if (span_f <= 8) LIF_WIN_C(8);
+        else if (span_f <= 16) LIF_WIN_C(16);
+        else if (span_f <= 32) LIF_WIN_C(32);
+        else LIF_WIN_C(64);
+#undef LIF_WIN_C
+#undef LIF_WIN
     }
     L->window_pending = true;
     return check_launch();
@@ -289,16 +309,10 @@ int lif_load_bundles(lif_layer* L, const int32_t* added_dev, const int32_t* n_ad
     if (!L->window_pending) return fail(LIF_BAD_STATE, "lif_load_bundles needs a preceding lif_update_window");
     hipStream_t s = (hipStream_t)stream;
     const lif_config& c = L->cfg;
-    const int span = (c.capacity_rows + kScanThreads - 1) / kScanThreads;
     {
-        Timed t(L, LIF_K_PLAN, s);
-        hipLaunchKernelGGL(k_plan, dim3(1), dim3(kScanThreads), 0, s, L->buf.pointers, L->buf.last_active,
-                           n_added_dev, c.d_ffn, c.window_k, c.capacity_rows, span, L->move_dst, L->hole_list, L->st);
-    }
-    {
-        const int cpr = (int)((L->row_bytes + 4095) / 4096);
+        const int cpr = (int)((L->row_bytes + kLoadChunk - 1) / kLoadChunk);
         const long long worst = (long long)c.capacity_rows * cpr;
-        const int grid = (int)std::min<long long>(worst, 1024);
+        const int grid = (int)std::min<long long>(worst, kLoadGrid);
         Timed t(L, LIF_K_LOAD, s);
         hipLaunchKernelGGL(k_load, dim3(grid), dim3(256), 0, s, (char*)L->buf.matrix, L->buf.pointers, L->buf.bias,
                            L->host_alias, L->buf.b, added_dev, L->move_dst, L->row_bytes, c.d_ffn, L->st);

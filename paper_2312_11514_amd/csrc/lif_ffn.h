@@ -16,27 +16,40 @@
 namespace lif {
 
 // grid-stride over rows, block = 256 (4 waves, one row per wave at a time).
-// NI = 16-byte loads per lane and vector (ceil(d / (64 * VE))); dynamic LDS: batch * d elements.
-template <typename T, int NI, bool GLU>
+// NI = 16-byte loads per lane and vector (ceil(d / (64 * VE))).
+// XREG (batch 1): every lane keeps its fragments of x in registers, loaded straight from
+// global memory together with the state, so the kernel pays two memory round trips (state + x,
+// then the rows).  Otherwise x is staged once per workgroup in LDS (dynamic LDS: batch * d
+// elements) and re-read per token.
+template <typename T, int NI, bool GLU, bool XREG>
 __global__ __launch_bounds__(256) void k_ffn_up(const T* __restrict__ matrix, const float* __restrict__ bias,
                                                 const T* __restrict__ x, float* __restrict__ h, int d, int batch,
                                                 int capacity, size_t row_elems, const DevState* __restrict__ st) {
     using V = typename Vec<T>::type;
     constexpr int VE = Vec<T>::N;
-    if (st->error) return;
-    const int n = st->num_used;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     V* xs = reinterpret_cast<V*>(smem_raw);
     const int tid = threadIdx.x, lane = tid & 63;
     const int nvec = d / VE;
     const int gw = blockIdx.x * 4 + (tid >> 6), nw = gridDim.x * 4;
-    if (blockIdx.x * 4 >= n) return;                 // whole workgroup has no row (uniform)
+    const V* xv = reinterpret_cast<const V*>(x);
 
-    {
-        const V* xv = reinterpret_cast<const V*>(x);
-        for (int i = tid; i < batch * nvec; i += 256) xs[i] = xv[i];
+    V xr[XREG ? NI : 1];
+    if (XREG) {
+#pragma unroll
+        for (int it = 0; it < NI; ++it) {
+            const int idx = it * 64 + lane;
+            xr[it] = (idx < nvec) ? xv[idx] : V(0);
+        }
     }
-    __syncthreads();
+    const int err = st->error;
+    const int n = st->num_used;
+    if (err || blockIdx.x * 4 >= n) return;          // whole workgroup has no row (uniform)
+
+    if (!XREG) {
+        for (int i = tid; i < batch * nvec; i += 256) xs[i] = xv[i];
+        __syncthreads();
+    }
 
     for (int s = gw; s < n; s += nw) {
         const V* row = reinterpret_cast<const V*>(matrix + (size_t)s * row_elems);
@@ -57,15 +70,18 @@ __global__ __launch_bounds__(256) void k_ffn_up(const T* __restrict__ matrix, co
             }
         }
         const float bs = bias[s];
-        for (int b = 0; b < batch; ++b) {
+        for (int b = 0; b < (XREG ? 1 : batch); ++b) {
             float du = 0.f, dg = 0.f;
 #pragma unroll
             for (int it = 0; it < NI; ++it) {
                 const int idx = it * 64 + lane;
-                if (idx < nvec) {
-                    const V xv = xs[b * nvec + idx];
-                    du = dot_acc(u[it], xv, du);
-                    if (GLU) dg = dot_acc(g[it], xv, dg);
+                if (XREG) {
+                    du = dot_acc(u[it], xr[it], du);              // both are 0 past the end of the vector
+                    if (GLU) dg = dot_acc(g[it], xr[it], dg);
+                } else if (idx < nvec) {
+                    const V xb = xs[b * nvec + idx];
+                    du = dot_acc(u[it], xb, du);
+                    if (GLU) dg = dot_acc(g[it], xb, dg);
                 }
             }
             du = wave_sum(du);
@@ -95,8 +111,6 @@ __global__ __launch_bounds__(256) void k_ffn_down(const T* __restrict__ matrix, 
     constexpr int VE = Vec<T>::N;
     constexpr int TS = kDownTile / BT;
     constexpr int PER = TS / 256;                    // slots per thread in the compaction
-    if (st->error) return;
-    const int n = st->num_used;
     __shared__ int list[TS];
     __shared__ float hv[BT][TS];
     __shared__ int wave_tot[4];
@@ -115,7 +129,21 @@ __global__ __launch_bounds__(256) void k_ffn_down(const T* __restrict__ matrix, 
         for (int e = 0; e < VE; ++e) acc[b][e] = 0.f;
 
     if (tid == 0) n_active = 0;
+    // the activations of the first tile are requested before the row count is known (the
+    // activation array spans the whole capacity, so the addresses are valid; values past
+    // num_used are masked below): one memory round trip less on the critical path
+    float hfirst[PER][BT];
+#pragma unroll
+    for (int q = 0; q < PER; ++q)
+#pragma unroll
+        for (int b = 0; b < BT; ++b) {
+            const int s = tid * PER + q;
+            hfirst[q][b] = (s < capacity && b < batch) ? h[(size_t)b * capacity + s] : 0.f;
+        }
+    const int err = st->error;
+    const int n = err ? 0 : st->num_used;
     __syncthreads();
+    if (err) return;
     for (int s_base = 0; s_base < n; s_base += TS) {
         // ordered compaction of the rows that contribute
         float hloc[PER][BT];
@@ -127,7 +155,7 @@ __global__ __launch_bounds__(256) void k_ffn_down(const T* __restrict__ matrix, 
 #pragma unroll
             for (int b = 0; b < BT; ++b) {
                 float v = 0.f;
-                if (s < n && b < batch) v = h[(size_t)b * capacity + s];
+                if (s < n && b < batch) v = (s_base == 0) ? hfirst[q][b] : h[(size_t)b * capacity + s];
                 hloc[q][b] = v;
                 any |= (v != 0.f);
             }

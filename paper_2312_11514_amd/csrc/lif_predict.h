@@ -5,6 +5,9 @@
 // exact in fp64, so the result depends on the summation order only at the 1e-16 level
 // and the thresholded bits can be compared bit for bit with a CPU evaluation.  The path
 // stays bandwidth bound (one fp64 FMA per 2 or 4 bytes read).
+//
+// Both kernels are a few microseconds long, i.e. latency bound: each issues all of its
+// global loads (weights, partial sums, offsets, state) before the first dependent use.
 #pragma once
 
 #include "lif_common.h"
@@ -12,8 +15,10 @@
 namespace lif {
 
 constexpr int kXaRows = 256;       // rows of A per workgroup of predict_xa
-constexpr int kMaskCols = 16;      // mask bytes (groups of 8 neurons) per workgroup of predict_mask
-constexpr int kMaskJg = 16;        // rank groups per workgroup of predict_mask
+constexpr int kXaBatch = 16;       // rows of A a thread keeps in flight
+constexpr int kMaskCols = 8;       // mask bytes (groups of 8 neurons) per workgroup of predict_mask
+constexpr int kMaskJg = 32;        // rank groups per workgroup of predict_mask
+constexpr int kMaskRows = 8;       // rows of B a thread keeps in flight
 
 // t_partial[b][chunk][j] = sum_{i in chunk} x[b][i] * A[i][j]
 // grid = (ceil(d / kXaRows), batch), block = 256.
@@ -24,7 +29,6 @@ __global__ __launch_bounds__(256) void k_predict_xa(const T* __restrict__ x, con
                                                     const DevState* __restrict__ st) {
     using V = typename Vec<T>::type;
     constexpr int VE = Vec<T>::N;
-    if (st->error) return;
     __shared__ float xs[kXaRows];
     __shared__ double red[256 * VE];
 
@@ -35,26 +39,43 @@ __global__ __launch_bounds__(256) void k_predict_xa(const T* __restrict__ x, con
     const int chunk = blockIdx.x, b = blockIdx.y, nchunks = gridDim.x;
     const int row0 = chunk * kXaRows;
     const int nrows = min(kXaRows, d - row0);
+    const bool lane_ok = rl < rp;
+    const V* __restrict__ Av = reinterpret_cast<const V*>(A) + (size_t)row0 * lpr + cl;
 
-    for (int i = tid; i < nrows; i += 256) xs[i] = (float)x[(size_t)b * d + row0 + i];
+    // loads first: x, the first batch of A rows, the error flag
+    const float xreg = (tid < nrows) ? (float)x[(size_t)b * d + row0 + tid] : 0.f;
+    V a[kXaBatch];
+#pragma unroll
+    for (int u = 0; u < kXaBatch; ++u) {
+        const int i = rl + u * rp;
+        a[u] = (lane_ok && i < nrows) ? Av[(size_t)i * lpr] : V(0);
+    }
+    const int err = st->error;
+    xs[tid] = xreg;
     __syncthreads();
 
     double acc[VE];
 #pragma unroll
     for (int e = 0; e < VE; ++e) acc[e] = 0.0;
-    if (rl < rp) {
-        const V* __restrict__ Av = reinterpret_cast<const V*>(A) + (size_t)row0 * lpr + cl;
-#pragma unroll 8
-        for (int i = rl; i < nrows; i += rp) {
-            V a = Av[(size_t)i * lpr];
-            double xv = (double)xs[i];
 #pragma unroll
-            for (int e = 0; e < VE; ++e) acc[e] = __builtin_fma(xv, (double)a[e], acc[e]);
+    for (int u = 0; u < kXaBatch; ++u) {
+        const int i = rl + u * rp;
+        const double xv = (double)xs[min(i, kXaRows - 1)];
+#pragma unroll
+        for (int e = 0; e < VE; ++e) acc[e] = __builtin_fma(xv, (double)a[u][e], acc[e]);   // a[u] is 0 past the end
+    }
+    if (lane_ok) {
+        for (int i = rl + kXaBatch * rp; i < nrows; i += rp) {     // only when rank / VE > 16
+            const V av = Av[(size_t)i * lpr];
+            const double xv = (double)xs[i];
+#pragma unroll
+            for (int e = 0; e < VE; ++e) acc[e] = __builtin_fma(xv, (double)av[e], acc[e]);
         }
     }
 #pragma unroll
     for (int e = 0; e < VE; ++e) red[tid * VE + e] = acc[e];
     __syncthreads();
+    if (err) return;
     // column j lives in lane cl = j / VE, element e = j % VE; rows-in-pass summed ascending
     for (int j = tid; j < r; j += 256) {
         const int jc = j / VE, je = j - jc * VE;
@@ -65,8 +86,9 @@ __global__ __launch_bounds__(256) void k_predict_xa(const T* __restrict__ x, con
 }
 
 // logits = t B + c, threshold, pack 8 neurons per byte; step mask = OR over the batch.
-// grid = ceil(F / 128), block = 256 = 16 rank groups x 16 column lanes; each column lane
-// owns 8 consecutive neurons = one mask byte.  dynamic LDS: BT * r doubles.
+// grid = ceil(F / 64), block = 256 = 32 rank groups x 8 column lanes; each column lane owns
+// 8 consecutive neurons = one mask byte.  t = sum of the chunk partials, reduced redundantly
+// by every workgroup in a fixed order.  dynamic LDS: BT * r doubles.
 template <typename T, int BT>
 __global__ __launch_bounds__(256) void k_predict_mask(const T* __restrict__ B, const float* __restrict__ c,
                                                       const double* __restrict__ tpart, int nchunks, int r,
@@ -76,18 +98,35 @@ __global__ __launch_bounds__(256) void k_predict_mask(const T* __restrict__ B, c
     using V = typename Vec<T>::type;
     constexpr int VE = Vec<T>::N;
     constexpr int LPB = 8 / VE;             // 16-byte loads per group of 8 neurons
-    if (st->error) return;
     extern __shared__ double tl[];          // [BT][r]
     __shared__ double red[4][kMaskCols][BT][8];
     __shared__ uint8_t bytes[BT][kMaskCols];
 
     const int tid = threadIdx.x, wave = tid >> 6;
-    const int cl = tid & (kMaskCols - 1), jg = tid >> 4;
+    const int cl = tid & (kMaskCols - 1), jg = tid >> 3;
     const int n0 = (blockIdx.x * kMaskCols + cl) * 8;
     const bool col_ok = n0 < F;
     const int mask_stride = F >> 3;
     const double th = (double)theta;
     uint8_t or_byte = 0;
+
+    // loads that do not depend on t: the first kMaskRows rows of B of this thread, the offsets, the flag
+    V bv[kMaskRows][LPB];
+#pragma unroll
+    for (int u = 0; u < kMaskRows; ++u) {
+        const int j = jg + u * kMaskJg;
+#pragma unroll
+        for (int q = 0; q < LPB; ++q)
+            bv[u][q] = (col_ok && j < r) ? reinterpret_cast<const V*>(B + (size_t)j * F + n0)[q] : V(0);
+    }
+    float cv[8];
+    {
+        const int c2 = tid & (kMaskCols - 1);
+        const int n2 = (blockIdx.x * kMaskCols + c2) * 8;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) cv[e] = (c && tid < kMaskCols * BT && n2 < F) ? c[n2 + e] : 0.f;
+    }
+    const int err = st->error;
 
     for (int b0 = 0; b0 < batch; b0 += BT) {
         __syncthreads();
@@ -96,6 +135,7 @@ __global__ __launch_bounds__(256) void k_predict_mask(const T* __restrict__ B, c
             double s = 0.0;
             if (b0 + bt < batch) {
                 const double* p = tpart + ((size_t)(b0 + bt) * nchunks) * r + j;
+#pragma unroll 8
                 for (int ch = 0; ch < nchunks; ++ch) s += p[(size_t)ch * r];
             }
             tl[idx] = s;
@@ -107,13 +147,25 @@ __global__ __launch_bounds__(256) void k_predict_mask(const T* __restrict__ B, c
         for (int bt = 0; bt < BT; ++bt)
 #pragma unroll
             for (int e = 0; e < 8; ++e) acc[bt][e] = 0.0;
-        if (col_ok) {
-#pragma unroll 4
-            for (int j = jg; j < r; j += kMaskJg) {
-                const V* bp = reinterpret_cast<const V*>(B + (size_t)j * F + n0);
-                V bv[LPB];
 #pragma unroll
-                for (int q = 0; q < LPB; ++q) bv[q] = bp[q];
+        for (int u = 0; u < kMaskRows; ++u) {
+            const int j = min(jg + u * kMaskJg, r - 1);           // bv[u] is 0 past the end
+#pragma unroll
+            for (int bt = 0; bt < BT; ++bt) {
+                const double tj = tl[bt * r + j];
+#pragma unroll
+                for (int q = 0; q < LPB; ++q)
+#pragma unroll
+                    for (int e = 0; e < VE; ++e)
+                        acc[bt][q * VE + e] = __builtin_fma(tj, (double)bv[u][q][e], acc[bt][q * VE + e]);
+            }
+        }
+        if (col_ok) {
+            for (int j = jg + kMaskRows * kMaskJg; j < r; j += kMaskJg) {      // only when rank > 256
+                const V* bp = reinterpret_cast<const V*>(B + (size_t)j * F + n0);
+                V bw[LPB];
+#pragma unroll
+                for (int q = 0; q < LPB; ++q) bw[q] = bp[q];
 #pragma unroll
                 for (int bt = 0; bt < BT; ++bt) {
                     const double tj = tl[bt * r + j];
@@ -121,16 +173,17 @@ __global__ __launch_bounds__(256) void k_predict_mask(const T* __restrict__ B, c
                     for (int q = 0; q < LPB; ++q)
 #pragma unroll
                         for (int e = 0; e < VE; ++e)
-                            acc[bt][q * VE + e] = __builtin_fma(tj, (double)bv[q][e], acc[bt][q * VE + e]);
+                            acc[bt][q * VE + e] = __builtin_fma(tj, (double)bw[q][e], acc[bt][q * VE + e]);
                 }
             }
         }
-        // the four rank groups of a wave sit 16 lanes apart: butterfly, then LDS across waves
+        // the eight rank groups of a wave sit 8 lanes apart: butterfly, then LDS across the 4 waves
 #pragma unroll
         for (int bt = 0; bt < BT; ++bt)
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 double v = acc[bt][e];
+                v += __shfl_xor(v, 8, kWave);
                 v += __shfl_xor(v, 16, kWave);
                 v += __shfl_xor(v, 32, kWave);
                 if ((tid & 63) < kMaskCols) red[wave][cl][bt][e] = v;
@@ -144,10 +197,10 @@ __global__ __launch_bounds__(256) void k_predict_mask(const T* __restrict__ B, c
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
                     double z = ((red[0][c2][bt][e] + red[1][c2][bt][e]) + red[2][c2][bt][e]) + red[3][c2][bt][e];
-                    if (c) z += (double)c[n2 + e];
+                    z += (double)cv[e];
                     if (z > th) byte |= (uint8_t)(1u << e);
                 }
-                masks[(size_t)(b0 + bt) * mask_stride + (n2 >> 3)] = byte;
+                if (!err) masks[(size_t)(b0 + bt) * mask_stride + (n2 >> 3)] = byte;
             }
             bytes[bt][c2] = byte;
         }
@@ -157,7 +210,7 @@ __global__ __launch_bounds__(256) void k_predict_mask(const T* __restrict__ B, c
             for (int bt = 0; bt < BT; ++bt) or_byte |= bytes[bt][tid];
         }
     }
-    if (tid < kMaskCols && n0 < F) step_mask[n0 >> 3] = or_byte;
+    if (tid < kMaskCols && n0 < F && !err) step_mask[n0 >> 3] = or_byte;
 }
 
 }  // namespace lif

@@ -12,19 +12,85 @@ namespace lif {
 
 constexpr int kScanThreads = 1024;   // single-workgroup kernels: 16 waves
 constexpr int kMaxSpan = 64;         // neurons / slots per thread (bitmaps are 64-bit)
+constexpr int kHoleLds = 4096;       // holes kept in LDS; longer lists spill to the global scratch list
 
-// One workgroup walks all F neurons in thread-contiguous spans, so that a workgroup-wide
-// prefix sum over per-thread popcounts yields ids in ascending order.
-// span = neurons per thread, multiple of 8, <= 64.
-__global__ __launch_bounds__(kScanThreads) void k_window(const uint8_t* __restrict__ step_mask,
-                                                         int32_t* __restrict__ last_active, int F, int k,
-                                                         int capacity, int span, int32_t* __restrict__ added,
-                                                         int32_t* __restrict__ n_added,
-                                                         int32_t* __restrict__ removed,
-                                                         int32_t* __restrict__ n_removed, DevState* st) {
-    __shared__ int wave_tot[kScanThreads / kWave];
+// Exclusive prefix sums of two counts per thread in one pass (both < 2^31 in total, packed
+// into one 64-bit lane value).  Same contract as block_exclusive_scan.
+__device__ __forceinline__ void block_exclusive_scan2(int va, int vb, unsigned long long* wave_tot, int* off_a,
+                                                      int* off_b, int* tot_a, int* tot_b) {
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), w = tid >> 6;
+    const int nw = (blockDim.x + kWave - 1) >> 6;
+    const unsigned long long v = ((unsigned long long)(unsigned)vb << 32) | (unsigned)va;
+    unsigned long long inc = v;
+#pragma unroll
+    for (int o = 1; o < kWave; o <<= 1) {
+        unsigned long long u = __shfl_up(inc, o, kWave);
+        if (lane >= o) inc += u;
+    }
+    __syncthreads();
+    if (lane == kWave - 1) wave_tot[w] = inc;
+    __syncthreads();
+    unsigned long long before = 0, all = 0;
+    for (int i = 0; i < nw; ++i) {
+        const unsigned long long t = wave_tot[i];
+        if (i < w) before += t;
+        all += t;
+    }
+    const unsigned long long ex = before + inc - v;
+    *off_a = (int)(unsigned)(ex & 0xffffffffull);
+    *off_b = (int)(unsigned)(ex >> 32);
+    *tot_a = (int)(unsigned)(all & 0xffffffffull);
+    *tot_b = (int)(unsigned)(all >> 32);
+}
+
+// One workgroup does the window update and the deletion plan back to back.
+//
+// Window: the workgroup walks all F neurons in thread-contiguous spans, so that a
+// workgroup-wide prefix sum over per-thread popcounts yields ids in ascending order.
+//
+// Deletion plan (Section 3.3 item 1): a slot is dead iff its neuron was just removed (looked
+// up in an LDS bitmap of the removed ids).  With n' = n - c, the dead slots below n'
+// ("holes", ascending) are filled by the live slots at or above n' ("fillers"): hole j takes
+// the (H-1-j)-th filler - the lowest hole receives the last row, exactly what the
+// sequential swap-with-last loop does.  Sources (>= n') and destinations (< n') are
+// disjoint, so the moves can later run in any order.
+// Output of the plan: move_dst[q] for tail slot n' + q = destination slot, or -1 if dead.
+//
+// Every global load (state, mask bytes, last_active, pointers) is issued before the first
+// use, so the kernel pays one memory round trip, not one per phase.
+// SPAN_F = neurons per thread (multiple of 8, <= 64); SPAN_C = cache slots per thread (<= 64).
+template <int SPAN_F, int SPAN_C>
+__global__ __launch_bounds__(kScanThreads) void k_window_plan(
+    const uint8_t* __restrict__ step_mask, int32_t* __restrict__ last_active, const int32_t* __restrict__ pointers,
+    int F, int k, int capacity, int32_t* __restrict__ added, int32_t* __restrict__ n_added,
+    int32_t* __restrict__ removed, int32_t* __restrict__ n_removed, int32_t* __restrict__ move_dst,
+    int32_t* __restrict__ hole_list, DevState* st) {
+    __shared__ unsigned long long wave_tot[kScanThreads / kWave];
+    __shared__ unsigned rem_bm[kScanThreads * kMaxSpan / 32];
+    __shared__ int hole_lds[kHoleLds];
     const int tid = threadIdx.x;
-    if (st->error) {
+
+    // ---- issue all loads ----
+    const int i0 = tid * SPAN_F, s0 = tid * SPAN_C;
+    int4 la[SPAN_F / 4];
+    unsigned mbyte[SPAN_F / 8];
+    int ptr[SPAN_C];
+#pragma unroll
+    for (int g = 0; g < SPAN_F / 8; ++g) {
+        const int i = i0 + g * 8;
+        const bool ok = i < F;
+        mbyte[g] = ok ? step_mask[i >> 3] : 0u;
+        la[2 * g] = ok ? *reinterpret_cast<const int4*>(last_active + i) : make_int4(kNever, kNever, kNever, kNever);
+        la[2 * g + 1] = ok ? *reinterpret_cast<const int4*>(last_active + i + 4) : make_int4(kNever, kNever, kNever, kNever);
+    }
+#pragma unroll
+    for (int q = 0; q < SPAN_C; ++q) ptr[q] = (s0 + q < capacity) ? pointers[s0 + q] : -1;
+    const int err = st->error;
+    const int t = st->step;
+    const int n = st->num_used;
+    for (int wd = tid; wd < (F + 31) / 32; wd += kScanThreads) rem_bm[wd] = 0u;
+
+    if (err) {
         if (tid == 0) {
             *n_added = 0;
             *n_removed = 0;
@@ -33,36 +99,31 @@ __global__ __launch_bounds__(kScanThreads) void k_window(const uint8_t* __restri
         }
         return;
     }
-    const int t = st->step;
-    const int n_prev = st->num_used;
-    const int i0 = tid * span;
+
+    // ---- window ----
     unsigned long long abits = 0, rbits = 0, mbits = 0;
-    for (int g = 0; g < span; g += 8) {
-        const int i = i0 + g;
-        if (i < F) {
-            const unsigned m = step_mask[i >> 3];
-            const int4 la0 = *reinterpret_cast<const int4*>(last_active + i);
-            const int4 la1 = *reinterpret_cast<const int4*>(last_active + i + 4);
-            const int la[8] = {la0.x, la0.y, la0.z, la0.w, la1.x, la1.y, la1.z, la1.w};
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const bool in_prev = la[e] >= t - k;               // in S_{t-1}
-                const bool hit = (m >> e) & 1u;
-                const bool in_now = hit || la[e] >= t - k + 1;     // in S_t
-                const unsigned long long bit = 1ull << (g + e);
-                if (hit) mbits |= bit;
-                if (in_now && !in_prev) abits |= bit;
-                if (in_prev && !in_now) rbits |= bit;
-            }
+    for (int g = 0; g < SPAN_F / 8; ++g) {
+        const int v[8] = {la[2 * g].x, la[2 * g].y, la[2 * g].z, la[2 * g].w,
+                          la[2 * g + 1].x, la[2 * g + 1].y, la[2 * g + 1].z, la[2 * g + 1].w};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const bool in_prev = v[e] >= t - k;                 // in S_{t-1}
+            const bool hit = (mbyte[g] >> e) & 1u;
+            const bool in_now = hit || v[e] >= t - k + 1;       // in S_t
+            const unsigned long long bit = 1ull << (g * 8 + e);
+            if (hit) mbits |= bit;
+            if (in_now && !in_prev) abits |= bit;
+            if (in_prev && !in_now) rbits |= bit;
         }
     }
-    int tot_a, tot_r;
-    int off_a = block_exclusive_scan(__popcll(abits), wave_tot, &tot_a);
-    int off_r = block_exclusive_scan(__popcll(rbits), wave_tot, &tot_r);
+    int off_a, off_r, tot_a, tot_r;
+    block_exclusive_scan2(__popcll(abits), __popcll(rbits), wave_tot, &off_a, &off_r, &tot_a, &tot_r);
 
-    if (n_prev + tot_a - tot_r > capacity) {       // uniform: leave the window untouched
+    const int n2 = n - tot_r;
+    if (n2 < 0 || n2 + tot_a > capacity) {          // uniform: leave the window untouched
         if (tid == 0) {
-            st->error = 3;                          // LIF_CAPACITY
+            st->error = 3;                           // LIF_CAPACITY
             *n_added = 0;
             *n_removed = 0;
             st->n_added = 0;
@@ -77,7 +138,9 @@ __global__ __launch_bounds__(kScanThreads) void k_window(const uint8_t* __restri
     }
     while (rbits) {
         const int bpos = __ffsll((long long)rbits) - 1;
-        removed[off_r++] = i0 + bpos;
+        const int id = i0 + bpos;
+        removed[off_r++] = id;
+        atomicOr(&rem_bm[id >> 5], 1u << (id & 31));
         rbits &= rbits - 1;
     }
     while (mbits) {
@@ -85,87 +148,58 @@ __global__ __launch_bounds__(kScanThreads) void k_window(const uint8_t* __restri
         last_active[i0 + bpos] = t;
         mbits &= mbits - 1;
     }
-    if (tid == 0) {
-        *n_added = tot_a;
-        *n_removed = tot_r;
-        st->n_added = tot_a;
-        st->n_removed = tot_r;
-        st->step = t + 1;
-        st->c_steps += 1;
-        st->c_added += (unsigned long long)tot_a;
-        st->c_removed += (unsigned long long)tot_r;
-    }
-}
+    __syncthreads();
 
-// Deletion plan.  A slot is dead iff its neuron left the window.  With n' = n - #dead, the
-// dead slots below n' ("holes", ascending) are filled by the live slots at or above n'
-// ("fillers"): hole j takes the (H-1-j)-th filler - the lowest hole receives the last row,
-// exactly what the sequential swap-with-last loop does.  Sources (>= n') and destinations
-// (< n') are disjoint, so the moves can run in any order.
-// Output: move_dst[q] for tail slot n' + q: destination slot, or -1 if that slot is dead.
-// span = slots per thread (<= 64), capacity <= 1024 * span.
-__global__ __launch_bounds__(kScanThreads) void k_plan(const int32_t* __restrict__ pointers,
-                                                       const int32_t* __restrict__ last_active,
-                                                       const int32_t* __restrict__ n_added_p, int F, int k,
-                                                       int capacity, int span, int32_t* __restrict__ move_dst,
-                                                       int32_t* __restrict__ hole_list, DevState* st) {
-    __shared__ int wave_tot[kScanThreads / kWave];
-    const int tid = threadIdx.x;
-    if (st->error) return;
-    const int n = st->num_used;
-    const int horizon = st->step - k;      // dead iff last_active < step - k (step already advanced)
-    const int s0 = tid * span;
-    unsigned long long deadbits = 0;
-    for (int q = 0; q < span; ++q) {
-        const int s = s0 + q;
-        if (s < n) {
-            const int id = pointers[s];
-            const bool dead = (id < 0 || id >= F) ? true : (last_active[id] < horizon);
-            if (dead) deadbits |= 1ull << q;
-        }
-    }
-    int c;
-    block_exclusive_scan(__popcll(deadbits), wave_tot, &c);
-    const int n2 = n - c;
+    // ---- deletion plan ----
     unsigned long long holebits = 0, fillbits = 0;
-    for (int q = 0; q < span; ++q) {
+#pragma unroll
+    for (int q = 0; q < SPAN_C; ++q) {
         const int s = s0 + q;
         if (s < n) {
-            const bool dead = (deadbits >> q) & 1ull;
+            const int id = ptr[q];
+            const bool dead = (id < 0 || id >= F) ? true : ((rem_bm[id >> 5] >> (id & 31)) & 1u);
             if (s < n2 && dead) holebits |= 1ull << q;
             if (s >= n2 && !dead) fillbits |= 1ull << q;
         }
     }
-    int H, Fc;
-    int off_h = block_exclusive_scan(__popcll(holebits), wave_tot, &H);
-    int off_f = block_exclusive_scan(__popcll(fillbits), wave_tot, &Fc);
+    int off_h, off_f, H, Fc;
+    block_exclusive_scan2(__popcll(holebits), __popcll(fillbits), wave_tot, &off_h, &off_f, &H, &Fc);
+    const bool in_lds = H <= kHoleLds;
     {
         unsigned long long hb = holebits;
         while (hb) {
             const int q = __ffsll((long long)hb) - 1;
-            hole_list[off_h++] = s0 + q;
+            if (in_lds) hole_lds[off_h] = s0 + q;
+            else hole_list[off_h] = s0 + q;
+            ++off_h;
             hb &= hb - 1;
         }
     }
-    __syncthreads();   // hole_list (global) is read by other threads of this workgroup below
-    for (int q = 0; q < span; ++q) {
+    __syncthreads();   // the hole list (LDS, or global scratch when long) is read by other threads below
+#pragma unroll
+    for (int q = 0; q < SPAN_C; ++q) {
         const int s = s0 + q;
         if (s >= n2 && s < n) {
             int dst = -1;
             if ((fillbits >> q) & 1ull) {
-                dst = hole_list[H - 1 - off_f];
+                const int j = H - 1 - off_f;
+                if (j >= 0 && j < H) dst = in_lds ? hole_lds[j] : hole_list[j];
                 ++off_f;
             }
             move_dst[s - n2] = dst;
         }
     }
     if (tid == 0) {
-        int a = *n_added_p;
-        a = max(0, min(a, capacity - n2));
+        *n_added = tot_a;
+        *n_removed = tot_r;
+        st->n_added = tot_a;
+        st->n_removed = tot_r;
         st->n_base = n2;
-        st->n_removed = c;
-        st->n_added = a;
         st->n_moved = H;
+        st->step = t + 1;
+        st->c_steps += 1;
+        st->c_added += (unsigned long long)tot_a;
+        st->c_removed += (unsigned long long)tot_r;
         st->c_rows_moved += (unsigned long long)H;
     }
 }
@@ -176,7 +210,14 @@ __global__ __launch_bounds__(kScanThreads) void k_plan(const int32_t* __restrict
 //   bundle of added[q] from pinned host memory and write it to slot s.
 // Every 16-byte piece of slot s is read (1) and overwritten (2) by the same thread in
 // program order, holes lie below n' and appends at or above it, so no two work items
-// touch the same bytes.  grid-stride over (item, 4 KiB chunk); block = 256.
+// touch the same bytes.  grid-stride over (item, 16 KiB chunk); block = 256, four 16-byte
+// loads per thread in flight.
+// The host link wants FEW requests in flight: measured on MI355X / PCIe Gen5, 146 bundles of
+// 16 KiB take 45 us with 32-64 workgroups (128-256 KiB in flight) and 58 us with 146 or more.
+constexpr int kLoadPer = 4;
+constexpr size_t kLoadChunk = 256 * 16 * kLoadPer;
+constexpr int kLoadGrid = 32;
+
 __global__ __launch_bounds__(256) void k_load(char* __restrict__ matrix, int32_t* __restrict__ pointers,
                                               float* __restrict__ bias, const char* __restrict__ host,
                                               const float* __restrict__ b, const int32_t* __restrict__ added,
@@ -185,22 +226,40 @@ __global__ __launch_bounds__(256) void k_load(char* __restrict__ matrix, int32_t
     if (st->error) return;
     const int n2 = st->n_base, c = st->n_removed, a = st->n_added;
     const int items = max(c, a);
-    const int cpr = (int)((row_bytes + 4095) / 4096);
+    const int cpr = (int)((row_bytes + kLoadChunk - 1) / kLoadChunk);
     const long long total = (long long)items * cpr;
     const int tid = threadIdx.x;
     for (long long it = blockIdx.x; it < total; it += gridDim.x) {
         const int q = (int)(it / cpr), ch = (int)(it - (long long)q * cpr);
-        const size_t off = (size_t)ch * 4096 + (size_t)tid * 16;
-        const bool inb = off < row_bytes;
         const int s = n2 + q;
         const int dst = (q < c) ? move_dst[q] : -1;
         int nid = (q < a) ? added[q] : -1;
         if (nid >= F) nid = -1;
-        uint4 mv = {0, 0, 0, 0}, hv = {0, 0, 0, 0};
-        if (inb && dst >= 0) mv = *reinterpret_cast<const uint4*>(matrix + (size_t)s * row_bytes + off);
-        if (inb && nid >= 0) hv = *reinterpret_cast<const uint4*>(host + (size_t)nid * row_bytes + off);
-        if (inb && dst >= 0) *reinterpret_cast<uint4*>(matrix + (size_t)dst * row_bytes + off) = mv;
-        if (inb && nid >= 0) *reinterpret_cast<uint4*>(matrix + (size_t)s * row_bytes + off) = hv;
+        const size_t off0 = (size_t)ch * kLoadChunk + (size_t)tid * 16;
+        const char* hsrc = host + (size_t)max(nid, 0) * row_bytes + off0;
+        const char* msrc = matrix + (size_t)s * row_bytes + off0;
+        char* mdst = matrix + (size_t)max(dst, 0) * row_bytes + off0;
+        char* adst = matrix + (size_t)s * row_bytes + off0;
+        uint4 hv[kLoadPer], mv[kLoadPer];
+        bool ok[kLoadPer];
+#pragma unroll
+        for (int p = 0; p < kLoadPer; ++p) {
+            ok[p] = off0 + (size_t)p * 4096 < row_bytes;
+            hv[p] = make_uint4(0, 0, 0, 0);
+            mv[p] = make_uint4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int p = 0; p < kLoadPer; ++p)
+            if (ok[p] && nid >= 0) hv[p] = *reinterpret_cast<const uint4*>(hsrc + (size_t)p * 4096);
+#pragma unroll
+        for (int p = 0; p < kLoadPer; ++p)
+            if (ok[p] && dst >= 0) mv[p] = *reinterpret_cast<const uint4*>(msrc + (size_t)p * 4096);
+#pragma unroll
+        for (int p = 0; p < kLoadPer; ++p)
+            if (ok[p] && dst >= 0) *reinterpret_cast<uint4*>(mdst + (size_t)p * 4096) = mv[p];
+#pragma unroll
+        for (int p = 0; p < kLoadPer; ++p)
+            if (ok[p] && nid >= 0) *reinterpret_cast<uint4*>(adst + (size_t)p * 4096) = hv[p];
         if (ch == 0 && tid == 0) {
             const int32_t old_ptr = pointers[s];
             const float old_bias = bias[s];
