@@ -22,7 +22,7 @@
  *   - Element type E is fp32 (LIF_F32) or IEEE fp16 (LIF_F16).  G = 2 vectors per
  *     bundle (up row | down column), G = 3 for gated layers (gate row | up row | down column).
  *   - Shape limits: d_model, rank multiples of 8 (fp16) or 4 (fp32); d_ffn a multiple
- *     of 8 and at most 65536; rank at most 2048; max_batch at most 8.
+ *     of 8 and at most 65536; rank at most 2048; max_batch at most 8; window_k at most 256.
  *   - A device-detected error (capacity overflow) sets a sticky flag: until lif_reset
  *     every hot call becomes a no-op on the device; lif_get_state reports the flag.
  *   - Calls on one handle must not overlap (one stream at a time).
@@ -81,9 +81,9 @@ typedef struct lif_buffers {
     void* matrix;           /* [capacity_rows x G*d_model] E                              */
     int32_t* pointers;      /* [capacity_rows] slot -> original neuron id                 */
     float* bias;            /* [capacity_rows] fp32                                       */
-    /* per original neuron: last step at which it was predicted active ("last_k_active") */
-    int32_t* last_active;   /* [d_ffn] int32 (device, read-write)                         */
-    /* scratch (device, read-write), at least lif_workspace_bytes(cfg) bytes, 256-aligned */
+    /* scratch (device, read-write), at least lif_workspace_bytes(cfg) bytes, 256-aligned; it
+     * also holds the window state ("last_k_active": the last window_k step masks) and the
+     * device-resident counts                                                             */
     void* workspace;
     size_t workspace_bytes;
 } lif_buffers;
@@ -136,8 +136,8 @@ int lif_destroy(lif_layer* layer);
 
 /*
  * Empty the cache (Section 3.3: num_used starts at zero): num_used = 0, every
- * neuron "never active", step = 0, error flag and counters cleared.  Enqueued on
- * `stream`; does not touch the matrix contents.
+ * window empty, step = 0, error flag and counters cleared.  Enqueued on `stream`; does
+ * not touch the matrix contents.
  */
 int lif_reset(lif_layer* layer, void* stream);
 
@@ -147,8 +147,8 @@ int lif_reset(lif_layer* layer, void* stream);
  *   x_dev          [batch x d_model] E, device, read-only
  *   masks_dev      [batch x d_ffn/8] bytes, device, written: bit (i mod 8) of byte i/8
  *                  of row t is 1 iff ((x_t A) B)_i + c_i > threshold
- *   step_mask_dev  [d_ffn/8] bytes, device, written: OR of the batch's masks; may equal
- *                  masks_dev when batch == 1
+ *   step_mask_dev  [d_ffn/8] bytes, device, 8-byte aligned, written: OR of the batch's masks;
+ *                  may equal masks_dev when batch == 1
  * Sums are accumulated in fp64 so the decision does not depend on summation order
  * beyond ~1e-15 relative.  NaN logits compare false (inactive).
  */
@@ -161,7 +161,7 @@ int lif_predict(lif_layer* layer, const void* x_dev, int32_t batch,
  *   added_dev    [d_ffn] int32, device, written: S_t \ S_{t-1}, ascending neuron id
  *   removed_dev  [d_ffn] int32, device, written: S_{t-1} \ S_t, ascending neuron id
  *   n_added_dev, n_removed_dev  [1] int32, device, written: the two counts
- * Updates last_active and advances the step counter.  If |S_t| would exceed
+ * Records the mask in the window state and advances the step counter.  If |S_t| would exceed
  * capacity_rows nothing is changed, both counts are written as 0 and the sticky
  * error flag is set to LIF_CAPACITY.
  * Must alternate with lif_load_bundles (LIF_BAD_STATE otherwise): the cache has to

@@ -26,7 +26,7 @@ class LifConfig(C.Structure):
 class LifBuffers(C.Structure):
     _fields_ = [("A", C.c_void_p), ("B", C.c_void_p), ("c", C.c_void_p), ("b", C.c_void_p),
                 ("host_bundles", C.c_void_p), ("matrix", C.c_void_p), ("pointers", C.c_void_p),
-                ("bias", C.c_void_p), ("last_active", C.c_void_p), ("workspace", C.c_void_p),
+                ("bias", C.c_void_p), ("workspace", C.c_void_p),
                 ("workspace_bytes", C.c_size_t)]
 
 
@@ -121,7 +121,6 @@ class Layer:
         self.matrix = torch.empty((capacity_rows, G * d_model), dtype=self.tdtype, device=dev)
         self.pointers = torch.empty(capacity_rows, dtype=torch.int32, device=dev)
         self.bias = torch.empty(capacity_rows, dtype=torch.float32, device=dev)
-        self.last_active = torch.empty(d_ffn, dtype=torch.int32, device=dev)
         self.workspace = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
         self.masks = torch.empty((max_batch, d_ffn // 8), dtype=torch.uint8, device=dev)
         self.step_mask = torch.empty(d_ffn // 8, dtype=torch.uint8, device=dev)
@@ -131,7 +130,7 @@ class Layer:
         self.n_removed = torch.empty(1, dtype=torch.int32, device=dev)
         self.buf = LifBuffers(A.data_ptr(), B.data_ptr(), c.data_ptr() if c is not None else None,
                               b.data_ptr(), host_bundles.data_ptr(), self.matrix.data_ptr(),
-                              self.pointers.data_ptr(), self.bias.data_ptr(), self.last_active.data_ptr(),
+                              self.pointers.data_ptr(), self.bias.data_ptr(),
                               self.workspace.data_ptr(), ws_bytes)
         h = C.c_void_p()
         _check(self.lib.lif_create(C.byref(self.cfg), C.byref(self.buf), C.byref(h)))

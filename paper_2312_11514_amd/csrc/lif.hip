@@ -34,12 +34,13 @@ int fail(int code, const char* fmt, const char* detail = "") {
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 struct Layout {
-    size_t state, tpart, move_dst, hole_list, h, total;
+    size_t state, ring, tpart, move_dst, hole_list, h, total;
 };
 
 int elem_bytes(const lif_config& c) { return c.dtype == LIF_F32 ? 4 : 2; }
 int vec_elems(const lif_config& c) { return 16 / elem_bytes(c); }
 int xa_chunks(const lif_config& c) { return (c.d_model + kXaRows - 1) / kXaRows; }
+int ring_words(const lif_config& c) { return (c.d_ffn + 63) / 64; }
 
 bool config_ok(const lif_config* c, const char** why) {
     *why = "";
@@ -50,7 +51,7 @@ bool config_ok(const lif_config* c, const char** why) {
     if ((c->d_model / ve + 63) / 64 > 16) return (*why = "d_model too large (at most 1024 16-byte vectors)", false);
     if (c->d_ffn <= 0 || c->d_ffn % 8 || c->d_ffn > kScanThreads * kMaxSpan) return (*why = "d_ffn must be a multiple of 8, at most 65536", false);
     if (c->rank <= 0 || c->rank % ve || c->rank / ve > 256 || c->rank > 2048) return (*why = "rank", false);
-    if (c->window_k < 1 || c->window_k > (1 << 20)) return (*why = "window_k", false);
+    if (c->window_k < 1 || c->window_k > 256) return (*why = "window_k must be in 1..256", false);
     if (c->capacity_rows < 1 || c->capacity_rows > kScanThreads * kMaxSpan) return (*why = "capacity_rows must be in 1..65536", false);
     if (c->max_batch < 1 || c->max_batch > 8) return (*why = "max_batch must be in 1..8", false);
     if (c->glu != 0 && c->glu != 1) return (*why = "glu", false);
@@ -64,6 +65,8 @@ Layout make_layout(const lif_config& c) {
     size_t off = 0;
     L.state = off;
     off = align_up(off + sizeof(DevState), 256);
+    L.ring = off;                      // window_k step masks, each padded to whole 64-bit words
+    off = align_up(off + (size_t)c.window_k * ring_words(c) * 8, 256);
     L.tpart = off;
     off = align_up(off + sizeof(double) * c.max_batch * xa_chunks(c) * c.rank, 256);
     L.move_dst = off;
@@ -84,6 +87,7 @@ struct lif_layer {
     Layout lay;
     const char* host_alias;     // device-visible address of the pinned bundle store
     DevState* st;
+    unsigned long long* ring;
     double* tpart;
     int32_t* move_dst;
     int32_t* hole_list;
@@ -204,11 +208,11 @@ int lif_create(const lif_config* cfg, const lif_buffers* buf, lif_layer** out) {
     if (!config_ok(cfg, &why)) return fail(LIF_INVALID_ARG, "invalid config: %s", why);
     if (!buf) return fail(LIF_INVALID_ARG, "buffers are null");
     if (!buf->A || !buf->B || !buf->b || !buf->host_bundles || !buf->matrix || !buf->pointers || !buf->bias ||
-        !buf->last_active || !buf->workspace)
+        !buf->workspace)
         return fail(LIF_INVALID_ARG, "a required buffer is null");
-    const void* ptrs[] = {buf->A, buf->B, buf->host_bundles, buf->matrix, buf->last_active};
+    const void* ptrs[] = {buf->A, buf->B, buf->host_bundles, buf->matrix};
     for (const void* p : ptrs)
-        if ((uintptr_t)p % 16) return fail(LIF_INVALID_ARG, "A, B, host_bundles, matrix and last_active must be 16-byte aligned");
+        if ((uintptr_t)p % 16) return fail(LIF_INVALID_ARG, "A, B, host_bundles and matrix must be 16-byte aligned");
     if ((uintptr_t)buf->workspace % 256) return fail(LIF_INVALID_ARG, "workspace must be 256-byte aligned");
     Layout lay = make_layout(*cfg);
     if (buf->workspace_bytes < lay.total) return fail(LIF_INVALID_ARG, "workspace smaller than lif_workspace_bytes");
@@ -225,6 +229,7 @@ int lif_create(const lif_config* cfg, const lif_buffers* buf, lif_layer** out) {
     L->host_alias = (const char*)alias;
     char* ws = (char*)buf->workspace;
     L->st = (DevState*)(ws + lay.state);
+    L->ring = (unsigned long long*)(ws + lay.ring);
     L->tpart = (double*)(ws + lay.tpart);
     L->move_dst = (int32_t*)(ws + lay.move_dst);
     L->hole_list = (int32_t*)(ws + lay.hole_list);
@@ -248,8 +253,9 @@ int lif_destroy(lif_layer* layer) {
 int lif_reset(lif_layer* L, void* stream) {
     if (!L) return fail(LIF_INVALID_ARG, "layer is null");
     hipStream_t s = (hipStream_t)stream;
-    const int grid = std::min((L->cfg.d_ffn + 255) / 256, 256);
-    hipLaunchKernelGGL(k_reset, dim3(grid), dim3(256), 0, s, L->buf.last_active, L->cfg.d_ffn, L->st);
+    const int total_words = L->cfg.window_k * ring_words(L->cfg);
+    const int grid = std::min((total_words + 255) / 256, 256);
+    hipLaunchKernelGGL(k_reset, dim3(grid), dim3(256), 0, s, L->ring, total_words, L->st);
     L->window_pending = false;
     return check_launch();
 }
@@ -270,33 +276,15 @@ int lif_update_window(lif_layer* L, const uint8_t* step_mask_dev, int32_t* added
                       int32_t* removed_dev, int32_t* n_removed_dev, void* stream) {
     if (!L || !step_mask_dev || !added_dev || !n_added_dev || !removed_dev || !n_removed_dev)
         return fail(LIF_INVALID_ARG, "null argument");
+    if ((uintptr_t)step_mask_dev % 8) return fail(LIF_INVALID_ARG, "step mask must be 8-byte aligned");
     if (L->window_pending) return fail(LIF_BAD_STATE, "lif_update_window called twice without lif_load_bundles");
     hipStream_t s = (hipStream_t)stream;
     const lif_config& c = L->cfg;
-    const int span_f = (c.d_ffn + kScanThreads - 1) / kScanThreads;      // neurons per thread, rounded up below
-    const int span_c = (c.capacity_rows + kScanThreads - 1) / kScanThreads;
     {
         Timed t(L, LIF_K_WINDOW, s);
-#define LIF_WIN(SF, SC)                                                                                      \
-    hipLaunchKernelGGL((k_window_plan<SF, SC>), dim3(1), dim3(kScanThreads), 0, s, step_mask_dev,                \
-                       L->buf.last_active, L->buf.pointers, c.d_ffn, c.window_k, c.capacity_rows, added_dev,     \
-                       n_added_dev, removed_dev, n_removed_dev, L->move_dst, L->hole_list, L->st)
-#define LIF_WIN_C(SF)                                   \
-    do {                                                \
-        if (span_c <= 1) LIF_WIN(SF, 1);                \
-        else if (span_c <= 2) LIF_WIN(SF, 2);           \
-        else if (span_c <= 4) LIF_WIN(SF, 4);           \
-        else if (span_c <= 8) LIF_WIN(SF, 8);           \
-        else if (span_c <= 16) LIF_WIN(SF, 16);         \
-        else if (span_c <= 32) LIF_WIN(SF, 32);         \
-        else LIF_WIN(SF, 64);                           \
-    } while (0)
-        if (span_f <= 8) LIF_WIN_C(8);
-        else if (span_f <= 16) LIF_WIN_C(16);
-        else if (span_f <= 32) LIF_WIN_C(32);
-        else LIF_WIN_C(64);
-#undef LIF_WIN_C
-#undef LIF_WIN
+        hipLaunchKernelGGL(k_window_plan, dim3(1), dim3(kScanThreads), 0, s, step_mask_dev, L->ring, ring_words(c),
+                           L->buf.pointers, c.d_ffn, c.window_k, c.capacity_rows, added_dev, n_added_dev, removed_dev,
+                           n_removed_dev, L->move_dst, L->hole_list, L->st);
     }
     L->window_pending = true;
     return check_launch();

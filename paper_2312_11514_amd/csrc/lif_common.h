@@ -7,7 +7,6 @@
 namespace lif {
 
 constexpr int kWave = 64;
-constexpr int32_t kNever = -(1 << 30);   // "never predicted active" in last_active
 
 // Device-resident state of one layer.  Lives at the start of the caller's workspace so
 // that the hot calls chain on a stream without the host ever knowing a count.

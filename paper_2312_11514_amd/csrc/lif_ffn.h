@@ -137,7 +137,7 @@ __global__ __launch_bounds__(256) void k_ffn_down(const T* __restrict__ matrix, 
     for (int q = 0; q < PER; ++q)
 #pragma unroll
         for (int b = 0; b < BT; ++b) {
-            const int s = tid * PER + q;
+            const int s = q * 256 + tid;
             hfirst[q][b] = (s < capacity && b < batch) ? h[(size_t)b * capacity + s] : 0.f;
         }
     const int err = st->error;
@@ -145,12 +145,12 @@ __global__ __launch_bounds__(256) void k_ffn_down(const T* __restrict__ matrix, 
     __syncthreads();
     if (err) return;
     for (int s_base = 0; s_base < n; s_base += TS) {
-        // ordered compaction of the rows that contribute
+        // compaction of the rows that contribute, in a fixed order (thread-major over slots q * 256 + tid)
         float hloc[PER][BT];
         unsigned flags = 0, nonzero = 0;
 #pragma unroll
         for (int q = 0; q < PER; ++q) {
-            const int s = s_base + tid * PER + q;
+            const int s = s_base + q * 256 + tid;
             bool any = false;
 #pragma unroll
             for (int b = 0; b < BT; ++b) {
@@ -169,7 +169,7 @@ __global__ __launch_bounds__(256) void k_ffn_down(const T* __restrict__ matrix, 
 #pragma unroll
         for (int q = 0; q < PER; ++q) {
             if (flags & (1u << q)) {
-                list[off] = s_base + tid * PER + q;
+                list[off] = s_base + q * 256 + tid;
 #pragma unroll
                 for (int b = 0; b < BT; ++b) hv[b][off] = hloc[q][b];
                 ++off;

@@ -1,21 +1,32 @@
 // Step 2: sliding window over the last k step masks (Section 3.1 "The Sliding Window
 // Technique", Fig. 4b) and Step 3: neuron-cache update (Section 3.3 items 1-2, Fig. 6).
 //
-// Window state is one int32 per original neuron: the last step at which it was predicted
-// active ("last_k_active").  A neuron is in the window after step t iff
-// last_active >= t - k + 1.  Everything is integer work: results are exact.
+// Window state ("last_k_active") is a ring of the last k step masks, one bit per neuron:
+// the active set is their bitwise OR, so a 64-bit word settles 64 neurons at once.
+// Everything is integer work: results are exact.
 #pragma once
 
 #include "lif_common.h"
 
 namespace lif {
 
-constexpr int kScanThreads = 1024;   // single-workgroup kernels: 16 waves
-constexpr int kMaxSpan = 64;         // neurons / slots per thread (bitmaps are 64-bit)
+constexpr int kScanThreads = 1024;   // single-workgroup kernels: 16 waves; one 64-neuron word or one slot per lane
+constexpr int kMaxSpan = 64;         // d_ffn <= 1024 * 64; capacity <= 1024 * 64
 constexpr int kHoleLds = 4096;       // holes kept in LDS; longer lists spill to the global scratch list
+constexpr int kRingRegs = 8;         // window masks a lane keeps in registers (larger k takes a second pass)
 
-// Exclusive prefix sums of two counts per thread in one pass (both < 2^31 in total, packed
-// into one 64-bit lane value).  Same contract as block_exclusive_scan.
+// 64 mask bits starting at neuron 64 * w; the mask has nbytes bytes (a multiple of 8 bits, maybe not of 64)
+__device__ __forceinline__ unsigned long long load_mask_word(const uint8_t* __restrict__ m, int w, int nbytes) {
+    const int b0 = w * 8;
+    if (b0 + 8 <= nbytes) return *reinterpret_cast<const unsigned long long*>(m + b0);
+    unsigned long long v = 0;
+    for (int i = 0; i < 8; ++i)
+        if (b0 + i < nbytes) v |= (unsigned long long)m[b0 + i] << (8 * i);
+    return v;
+}
+
+// Exclusive prefix sums of two counts per thread in one pass over a 1024-thread workgroup
+// (packed into one 64-bit lane value).  Contains two barriers.
 __device__ __forceinline__ void block_exclusive_scan2(int va, int vb, unsigned long long* wave_tot, int* off_a,
                                                       int* off_b, int* tot_a, int* tot_b) {
     const int tid = threadIdx.x, lane = tid & (kWave - 1), w = tid >> 6;
@@ -45,50 +56,48 @@ __device__ __forceinline__ void block_exclusive_scan2(int va, int vb, unsigned l
 
 // One workgroup does the window update and the deletion plan back to back.
 //
-// Window: the workgroup walks all F neurons in thread-contiguous spans, so that a
-// workgroup-wide prefix sum over per-thread popcounts yields ids in ascending order.
+// Window (Section 3.1): ring[j] holds the step masks of the last k steps; step t overwrites
+// ring[t mod k].  Lane w owns the 64 neurons of word w:
+//   prev = OR of all ring words (S_{t-1});  keep = OR of all but ring[t mod k];  S_t = keep | m
+//   added = m & ~prev;  removed = prev & ~(keep | m)
+// A workgroup-wide prefix sum over the popcounts puts the ids out in ascending order.
 //
 // Deletion plan (Section 3.3 item 1): a slot is dead iff its neuron was just removed (looked
-// up in an LDS bitmap of the removed ids).  With n' = n - c, the dead slots below n'
-// ("holes", ascending) are filled by the live slots at or above n' ("fillers"): hole j takes
-// the (H-1-j)-th filler - the lowest hole receives the last row, exactly what the
-// sequential swap-with-last loop does.  Sources (>= n') and destinations (< n') are
-// disjoint, so the moves can later run in any order.
+// up in the removed words, kept in LDS).  With n' = n - c, the dead slots below n' ("holes",
+// ascending) are filled by the live slots at or above n' ("fillers"): hole j takes the
+// (H-1-j)-th filler - the lowest hole receives the last row, exactly what the sequential
+// swap-with-last loop does.  Sources (>= n') and destinations (< n') are disjoint, so the
+// moves can later run in any order.  Slots are walked in blocks of 64 (one per lane), block b
+// by wave b mod 16; ballots rank the slots inside a block, a prefix over the per-block counts
+// ranks the blocks.  Only the blocks below num_used are visited.
 // Output of the plan: move_dst[q] for tail slot n' + q = destination slot, or -1 if dead.
 //
-// Every global load (state, mask bytes, last_active, pointers) is issued before the first
-// use, so the kernel pays one memory round trip, not one per phase.
-// SPAN_F = neurons per thread (multiple of 8, <= 64); SPAN_C = cache slots per thread (<= 64).
-template <int SPAN_F, int SPAN_C>
+// The loads that do not depend on the state (mask word, ring words, first block of pointers)
+// are issued together with the state itself.
 __global__ __launch_bounds__(kScanThreads) void k_window_plan(
-    const uint8_t* __restrict__ step_mask, int32_t* __restrict__ last_active, const int32_t* __restrict__ pointers,
-    int F, int k, int capacity, int32_t* __restrict__ added, int32_t* __restrict__ n_added,
-    int32_t* __restrict__ removed, int32_t* __restrict__ n_removed, int32_t* __restrict__ move_dst,
-    int32_t* __restrict__ hole_list, DevState* st) {
-    __shared__ unsigned long long wave_tot[kScanThreads / kWave];
-    __shared__ unsigned rem_bm[kScanThreads * kMaxSpan / 32];
+    const uint8_t* __restrict__ step_mask, unsigned long long* __restrict__ ring, int ring_words,
+    const int32_t* __restrict__ pointers, int F, int k, int capacity, int32_t* __restrict__ added,
+    int32_t* __restrict__ n_added, int32_t* __restrict__ removed, int32_t* __restrict__ n_removed,
+    int32_t* __restrict__ move_dst, int32_t* __restrict__ hole_list, DevState* st) {
+    constexpr int NW = kScanThreads / kWave;
+    __shared__ unsigned long long wave_tot[NW];
+    __shared__ unsigned long long rem64[kScanThreads];
     __shared__ int hole_lds[kHoleLds];
-    const int tid = threadIdx.x;
+    __shared__ int blk_h[kScanThreads], blk_f[kScanThreads];      // per 64-slot block: counts, then exclusive prefixes
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), w = tid >> 6;
+    const unsigned long long lt = (1ull << lane) - 1ull;
+    const int nwords = (F + 63) >> 6, nbytes = F >> 3;
+    const bool have = tid < nwords;
 
-    // ---- issue all loads ----
-    const int i0 = tid * SPAN_F, s0 = tid * SPAN_C;
-    int4 la[SPAN_F / 4];
-    unsigned mbyte[SPAN_F / 8];
-    int ptr[SPAN_C];
+    // ---- issue the state-independent loads ----
+    const unsigned long long m = have ? load_mask_word(step_mask, tid, nbytes) : 0ull;
+    unsigned long long rv[kRingRegs];
 #pragma unroll
-    for (int g = 0; g < SPAN_F / 8; ++g) {
-        const int i = i0 + g * 8;
-        const bool ok = i < F;
-        mbyte[g] = ok ? step_mask[i >> 3] : 0u;
-        la[2 * g] = ok ? *reinterpret_cast<const int4*>(last_active + i) : make_int4(kNever, kNever, kNever, kNever);
-        la[2 * g + 1] = ok ? *reinterpret_cast<const int4*>(last_active + i + 4) : make_int4(kNever, kNever, kNever, kNever);
-    }
-#pragma unroll
-    for (int q = 0; q < SPAN_C; ++q) ptr[q] = (s0 + q < capacity) ? pointers[s0 + q] : -1;
+    for (int j = 0; j < kRingRegs; ++j) rv[j] = (have && j < k) ? ring[(size_t)j * ring_words + tid] : 0ull;
+    int ptr0 = (tid < capacity) ? pointers[tid] : -1;
     const int err = st->error;
     const int t = st->step;
     const int n = st->num_used;
-    for (int wd = tid; wd < (F + 31) / 32; wd += kScanThreads) rem_bm[wd] = 0u;
 
     if (err) {
         if (tid == 0) {
@@ -101,22 +110,22 @@ __global__ __launch_bounds__(kScanThreads) void k_window_plan(
     }
 
     // ---- window ----
-    unsigned long long abits = 0, rbits = 0, mbits = 0;
+    const int slot = t % k;
+    unsigned long long prev = 0, keep = 0;
 #pragma unroll
-    for (int g = 0; g < SPAN_F / 8; ++g) {
-        const int v[8] = {la[2 * g].x, la[2 * g].y, la[2 * g].z, la[2 * g].w,
-                          la[2 * g + 1].x, la[2 * g + 1].y, la[2 * g + 1].z, la[2 * g + 1].w};
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const bool in_prev = v[e] >= t - k;                 // in S_{t-1}
-            const bool hit = (mbyte[g] >> e) & 1u;
-            const bool in_now = hit || v[e] >= t - k + 1;       // in S_t
-            const unsigned long long bit = 1ull << (g * 8 + e);
-            if (hit) mbits |= bit;
-            if (in_now && !in_prev) abits |= bit;
-            if (in_prev && !in_now) rbits |= bit;
+    for (int j = 0; j < kRingRegs; ++j) {
+        prev |= rv[j];
+        if (j != slot) keep |= rv[j];
+    }
+    if (have) {
+        for (int j = kRingRegs; j < k; ++j) {                 // only for windows longer than kRingRegs steps
+            const unsigned long long v = ring[(size_t)j * ring_words + tid];
+            prev |= v;
+            if (j != slot) keep |= v;
         }
     }
+    unsigned long long abits = m & ~prev;
+    unsigned long long rbits = prev & ~(keep | m);
     int off_a, off_r, tot_a, tot_r;
     block_exclusive_scan2(__popcll(abits), __popcll(rbits), wave_tot, &off_a, &off_r, &tot_a, &tot_r);
 
@@ -131,60 +140,68 @@ __global__ __launch_bounds__(kScanThreads) void k_window_plan(
         }
         return;
     }
+    rem64[tid] = rbits;
+    if (have) ring[(size_t)slot * ring_words + tid] = m;
     while (abits) {
-        const int bpos = __ffsll((long long)abits) - 1;
-        added[off_a++] = i0 + bpos;
+        added[off_a++] = tid * 64 + __ffsll((long long)abits) - 1;
         abits &= abits - 1;
     }
     while (rbits) {
-        const int bpos = __ffsll((long long)rbits) - 1;
-        const int id = i0 + bpos;
-        removed[off_r++] = id;
-        atomicOr(&rem_bm[id >> 5], 1u << (id & 31));
+        removed[off_r++] = tid * 64 + __ffsll((long long)rbits) - 1;
         rbits &= rbits - 1;
-    }
-    while (mbits) {
-        const int bpos = __ffsll((long long)mbits) - 1;
-        last_active[i0 + bpos] = t;
-        mbits &= mbits - 1;
     }
     __syncthreads();
 
-    // ---- deletion plan ----
-    unsigned long long holebits = 0, fillbits = 0;
-#pragma unroll
-    for (int q = 0; q < SPAN_C; ++q) {
-        const int s = s0 + q;
+    // ---- deletion plan: classify the slots below n, block by block ----
+    const int nblk = (n + kWave - 1) >> 6;           // <= 1024
+    unsigned long long holebits = 0, fillbits = 0;   // bit it = flag of this lane in its it-th block
+    for (int b = w, it = 0; b < nblk; b += NW, ++it) {
+        const int s = b * kWave + lane;
+        const int id = (it == 0) ? ptr0 : ((s < n) ? pointers[s] : -1);
+        bool hole = false, fill = false;
         if (s < n) {
-            const int id = ptr[q];
-            const bool dead = (id < 0 || id >= F) ? true : ((rem_bm[id >> 5] >> (id & 31)) & 1u);
-            if (s < n2 && dead) holebits |= 1ull << q;
-            if (s >= n2 && !dead) fillbits |= 1ull << q;
+            const bool dead = (id < 0 || id >= F) ? true : ((rem64[id >> 6] >> (id & 63)) & 1ull);
+            hole = s < n2 && dead;
+            fill = s >= n2 && !dead;
+        }
+        if (hole) holebits |= 1ull << it;
+        if (fill) fillbits |= 1ull << it;
+        const int ch = __popcll(__ballot(hole)), cf = __popcll(__ballot(fill));
+        if (lane == 0) {
+            blk_h[b] = ch;
+            blk_f[b] = cf;
         }
     }
-    int off_h, off_f, H, Fc;
-    block_exclusive_scan2(__popcll(holebits), __popcll(fillbits), wave_tot, &off_h, &off_f, &H, &Fc);
-    const bool in_lds = H <= kHoleLds;
+    __syncthreads();
+    int pre_h, pre_f, H, Fc;
     {
-        unsigned long long hb = holebits;
-        while (hb) {
-            const int q = __ffsll((long long)hb) - 1;
-            if (in_lds) hole_lds[off_h] = s0 + q;
-            else hole_list[off_h] = s0 + q;
-            ++off_h;
-            hb &= hb - 1;
+        const int vh = (tid < nblk) ? blk_h[tid] : 0, vf = (tid < nblk) ? blk_f[tid] : 0;
+        block_exclusive_scan2(vh, vf, wave_tot, &pre_h, &pre_f, &H, &Fc);
+        // the scan's barriers separate the reads of the counts above from these writes
+        blk_h[tid] = pre_h;
+        blk_f[tid] = pre_f;
+    }
+    __syncthreads();
+    const bool in_lds = H <= kHoleLds;
+    for (int b = w, it = 0; b < nblk; b += NW, ++it) {
+        const bool hole = (holebits >> it) & 1ull;
+        const unsigned long long bh = __ballot(hole);
+        if (hole) {
+            const int pos = blk_h[b] + __popcll(bh & lt);
+            if (in_lds) hole_lds[pos] = b * kWave + lane;
+            else hole_list[pos] = b * kWave + lane;
         }
     }
     __syncthreads();   // the hole list (LDS, or global scratch when long) is read by other threads below
-#pragma unroll
-    for (int q = 0; q < SPAN_C; ++q) {
-        const int s = s0 + q;
+    for (int b = w, it = 0; b < nblk; b += NW, ++it) {
+        const int s = b * kWave + lane;
+        const bool fill = (fillbits >> it) & 1ull;
+        const unsigned long long bf = __ballot(fill);
         if (s >= n2 && s < n) {
             int dst = -1;
-            if ((fillbits >> q) & 1ull) {
-                const int j = H - 1 - off_f;
-                if (j >= 0 && j < H) dst = in_lds ? hole_lds[j] : hole_list[j];
-                ++off_f;
+            if (fill) {
+                const int q = H - 1 - (blk_f[b] + __popcll(bf & lt));
+                if (q >= 0 && q < H) dst = in_lds ? hole_lds[q] : hole_list[q];
             }
             move_dst[s - n2] = dst;
         }
@@ -279,10 +296,10 @@ __global__ __launch_bounds__(256) void k_load(char* __restrict__ matrix, int32_t
     }
 }
 
-// Empty cache: every neuron "never active", state and counters zero.
-__global__ void k_reset(int32_t* __restrict__ last_active, int F, DevState* st) {
+// Empty cache: no mask in the window, state and counters zero.
+__global__ void k_reset(unsigned long long* __restrict__ ring, int ring_total_words, DevState* st) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    for (int j = i; j < F; j += gridDim.x * blockDim.x) last_active[j] = kNever;
+    for (int j = i; j < ring_total_words; j += gridDim.x * blockDim.x) ring[j] = 0ull;
     if (i == 0) {
         DevState z = {};
         *st = z;
