@@ -69,3 +69,186 @@ def test_c2_other_ffn_modes_match_oracle(ffn_mode):
     L = wl.cached_layer("C2")
     X = wl.make_inputs(w, tokens=24)
     run_stream(w, L, X, ffn_mode=ffn_mode, check_every=8)
+
+
+def test_c3_falcon_shape_fp16_whole_path():
+    """Falcon-7B FFN shape: d = 4544 = 71 x 64 (ragged 16-byte tail), F = 18176 = 284 x 64."""
+    w = wl.WORKLOADS["C3"]
+    L = wl.cached_layer("C3")
+    X = wl.make_inputs(w, tokens=40)
+    stats = run_stream(w, L, X, check_every=8)
+    print("C3 max rel-L2 %.2e, rows %.0f" % (max(s["err"] for s in stats), np.mean([s["n"] for s in stats[10:]])))
+
+
+def test_c4_llama_shape_gated_batch1():
+    w = wl.WORKLOADS["C4"]
+    L = wl.cached_layer("C4")
+    X = wl.make_inputs(w, tokens=32)
+    stats = run_stream(w, L, X, check_every=8)
+    print("C4 max rel-L2 %.2e, rows %.0f" % (max(s["err"] for s in stats), np.mean([s["n"] for s in stats[10:]])))
+
+
+def test_c4_llama_shape_gated_batch8():
+    """Eight independent streams share one cache: step mask = OR of the eight masks."""
+    w = wl.WORKLOADS["C4b8"]
+    L = wl.cached_layer("C4")            # same layer as the batch-1 run
+    X = wl.make_batch_inputs(w, tokens=10)
+    stats = run_stream(w, L, X, check_every=3)
+    print("C4b8 max rel-L2 %.2e, rows %.0f" % (max(s["err"] for s in stats), np.mean([s["n"] for s in stats[4:]])))
+
+
+@pytest.mark.parametrize("k", [1, 3, 12, 64])
+def test_window_sizes_including_longer_than_the_stream(k):
+    """k = 1: cache = current mask; k = 12: more masks than a lane keeps in registers; k >= T: nothing is removed."""
+    w = wl.scaled(wl.WORKLOADS["C1"], window_k=k, tokens=40)
+    stats = run_stream(w, wl.make_layer(w), wl.make_inputs(w))
+    if k >= 40:
+        assert all(s["removed"] == 0 for s in stats)
+
+
+def test_threshold_extremes_full_and_empty_cache():
+    """theta = -inf caches every neuron (num_used = capacity = F: the sparse FFN is the dense FFN);
+    theta = +inf caches nothing (y = 0)."""
+    from tests.harness import GpuLayer, compare_step, rel_l2
+    w = wl.scaled(wl.WORKLOADS["C1"], d_model=128, d_ffn=1096, rank=16, capacity_rows=1096, tokens=3, dtype="f16")
+    L = wl.make_layer(w)
+    X = wl.make_inputs(w)
+    for theta in (-np.inf, np.inf):
+        L.theta = theta
+        gpu = GpuLayer(w, L)
+        ora = make_oracle(w, L)
+        for t in range(3):
+            r = compare_step(gpu, ora, X[t], w, t)
+            assert r["n"] == (w.d_ffn if theta < 0 else 0)
+        if theta < 0:
+            yd = O.dense_ffn(L.w_up, L.w_down, L.b, X[2])
+            assert rel_l2(gpu.y[0].cpu().numpy(), yd) <= 1e-3
+        else:
+            assert not gpu.y.cpu().numpy().any()
+
+
+def test_maximum_sizes_long_hole_list():
+    """F = capacity = 65536 (the largest the window kernel takes), half the neurons flipping per step:
+    tens of thousands of holes, so the hole list spills from LDS to the global scratch list."""
+    w = wl.scaled(wl.WORKLOADS["C1"], name="max", d_model=32, d_ffn=65536, rank=8, window_k=1, p_active=0.5,
+                  rho=0.0, dtype="f16", tokens=4, capacity_rows=65536)
+    stats = run_stream(w, wl.make_layer(w), wl.make_inputs(w))
+    assert max(s["moved"] for s in stats) > 4096
+
+
+def test_capacity_overflow_sets_sticky_error_and_leaves_state():
+    from tests.harness import GpuLayer
+    import paper_2312_11514_amd as lif
+    w = wl.scaled(wl.WORKLOADS["C1"], capacity_rows=96, tokens=40)
+    L = wl.make_layer(w)
+    X = wl.make_inputs(w)
+    gpu = GpuLayer(w, L)
+    lay = gpu.layer
+    ora = make_oracle(w, L)
+    overflow_at = None
+    for t in range(w.tokens):
+        xd = gpu.upload_x(X[t])
+        before = lay.state()
+        try:
+            ora.step(X[t])
+            ok = True
+        except OverflowError:
+            ok = False
+        lay.step(xd, gpu.y)
+        st = lay.state()
+        if ok:
+            assert st["error"] == 0 and st["num_used"] == ora.cache.num_used and st["step"] == t + 1
+        else:
+            overflow_at = t
+            assert st["error"] == lif.LIF_CAPACITY
+            assert st["num_used"] == before["num_used"] and st["step"] == before["step"]
+            assert int(lay.n_added.item()) == 0 and int(lay.n_removed.item()) == 0
+            break
+    assert overflow_at is not None and overflow_at > 0, "workload never overflowed: make capacity smaller"
+    # sticky: further calls change nothing; reset clears
+    ptr_before = lay.pointers.clone()
+    y_before = gpu.y.clone()
+    lay.step(gpu.upload_x(X[overflow_at]), gpu.y)
+    st2 = lay.state()
+    assert st2["error"] == lif.LIF_CAPACITY and st2["step"] == st["step"] and st2["num_used"] == st["num_used"]
+    assert torch.equal(ptr_before, lay.pointers) and torch.equal(y_before, gpu.y)
+    lay.reset()
+    st3 = lay.state()
+    assert st3 == dict(num_used=0, step=0, error=0, last_added=0, last_removed=0, last_moved=0)
+
+
+def test_call_order_and_argument_errors():
+    from tests.harness import GpuLayer
+    import paper_2312_11514_amd as lif
+    w = wl.scaled(wl.WORKLOADS["C1"], tokens=2)
+    L = wl.make_layer(w)
+    gpu = GpuLayer(w, L)
+    lay = gpu.layer
+    xd = gpu.upload_x(wl.make_inputs(w)[0])
+    with pytest.raises(lif.LifError) as e:
+        lay.load_bundles()
+    assert e.value.status == lif.LIF_BAD_STATE
+    lay.predict(xd)
+    lay.update_window()
+    with pytest.raises(lif.LifError) as e:
+        lay.update_window()
+    assert e.value.status == lif.LIF_BAD_STATE
+    lay.load_bundles()
+    with pytest.raises(lif.LifError) as e:
+        lay.sparse_ffn(xd, gpu.y, batch=2)          # max_batch is 1
+    assert e.value.status == lif.LIF_INVALID_ARG
+    with pytest.raises(lif.LifError) as e:
+        lay.predict(None)
+    assert e.value.status == lif.LIF_INVALID_ARG
+    lay.sparse_ffn(xd, gpu.y)
+    assert lay.state()["error"] == 0
+
+
+def test_reset_reproduces_the_run_bit_for_bit():
+    """Two passes over the same stream from an empty cache give identical bytes (fixed summation order)."""
+    from tests.harness import GpuLayer
+    w = wl.WORKLOADS["C1"]
+    L = wl.make_layer(w)
+    X = wl.make_inputs(w)
+    gpu = GpuLayer(w, L)
+    xd = gpu.upload_x(X)
+    outs = []
+    for rep in range(2):
+        gpu.layer.reset()
+        ys = torch.zeros_like(xd)
+        for t in range(w.tokens):
+            gpu.layer.step(xd[t], ys[t])
+        outs.append((ys.cpu().numpy().tobytes(), gpu.layer.pointers.cpu().numpy().tobytes(), gpu.layer.counters()))
+    assert outs[0][0] == outs[1][0] and outs[0][1] == outs[1][1]
+    assert outs[0][2]["h2d_bytes"] == outs[1][2]["h2d_bytes"]
+
+
+def test_hip_graph_replay_matches_eager():
+    """The whole token stream captured once and replayed: every replay equals the eager result."""
+    from tests.harness import GpuLayer
+    w = wl.WORKLOADS["C1"]
+    L = wl.make_layer(w)
+    gpu = GpuLayer(w, L)
+    lay = gpu.layer
+    xd = gpu.upload_x(wl.make_inputs(w))
+    ys = torch.zeros_like(xd)
+
+    def run():
+        lay.reset()
+        for t in range(w.tokens):
+            lay.step(xd[t], ys[t])
+    run()
+    torch.cuda.synchronize()
+    y_eager, ptr_eager = ys.clone(), lay.pointers.clone()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        run()
+    for rep in range(3):
+        ys.zero_()
+        lay.pointers.fill_(-7)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        n = lay.state()["num_used"]
+        assert torch.equal(ys, y_eager), f"replay {rep}"
+        assert torch.equal(lay.pointers[:n], ptr_eager[:n])
