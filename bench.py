@@ -2,11 +2,11 @@
 """Benchmark of the sparse-FFN hot path on one MI355X.
 
 One step = one pass of the whole hot path (predict -> update_window -> load_bundles ->
-sparse_ffn for every token) over the workload's token stream, starting from an empty
-neuron cache.  Inputs, weights and the pinned bundle store are resident before the timed
-region starts.  Prints ONE JSON line.
+sparse_ffn for every token and every layer) over the workload's token stream, starting from
+empty neuron caches.  Inputs, weights and the pinned bundle store are resident before the
+timed region starts.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C2] [--ffn-mode skip|full]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C2|C3|C4|C4b8|C5] [--ffn-mode skip|full]
 """
 from __future__ import annotations
 
@@ -26,12 +26,11 @@ HBM_PEAK_GBS = 8000.0          # MI355X datasheet HBM3E bandwidth
 def describe(w):
     return (f"{w.name}: d_model={w.d_model} d_ffn={w.d_ffn} rank={w.rank} k={w.window_k} "
             f"p_active={w.p_active} rho={w.rho} {w.dtype} {'gated' if w.glu else 'relu'} "
-            f"batch={w.batch} tokens={w.tokens} capacity_rows={w.capacity_rows}")
+            f"batch={w.batch} tokens={w.tokens} layers={w.layers} capacity_rows={w.capacity_rows}")
 
 
 def cpu_baseline(w, L, X, budget_s=20.0):
-    """The oracle, as it stands, on the host cores: whole path per token."""
-    import numpy as np
+    """The oracle, as it stands, on the host cores: whole path per token, one layer."""
     from oracle import lif_oracle as O
     try:
         from threadpoolctl import threadpool_info
@@ -49,14 +48,15 @@ def cpu_baseline(w, L, X, budget_s=20.0):
             break
     dt = time.perf_counter() - t0
     return {"value": dt / done * 1e6, "unit": "us/token/layer", "cores": int(cores), "kind": "oracle",
-            "sample": f"first {done} tokens of the same stream, whole path (predict, window, delete, insert, FFN)"}
+            "sample": f"first {done} tokens of the same stream on layer 0, whole path "
+                      f"(predict, window, delete, insert, FFN)"}
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--workload", default="C2")
     ap.add_argument("--ffn-mode", default="skip", choices=["skip", "full"],
                     help="skip: down columns read only for rows with a non-zero activation; full: whole bundles")
@@ -69,71 +69,109 @@ def main():
               file=sys.stderr)
         sys.exit(2)
 
-    import numpy as np
     import torch
     import workloads as wl
     import paper_2312_11514_amd as lif
     from tests.harness import GpuLayer
 
     w = wl.WORKLOADS[args.workload]
-    if w.layers != 1:
-        print("bench.py: multi-layer workloads are driven by the parity tests, not by the bench line", file=sys.stderr)
-        sys.exit(2)
-    L = wl.make_layer(w)
-    X = wl.make_batch_inputs(w) if w.batch > 1 else wl.make_inputs(w)
-    T = len(X)
+    NL = w.layers
+    steps = args.steps if args.steps is not None else (20 if NL == 1 else 3)
+    warmup = args.warmup if args.warmup is not None else (3 if NL == 1 else 1)
     mode = {"skip": lif.FFN_SKIP_DEAD, "full": lif.FFN_FULL_BUNDLE}[args.ffn_mode]
     reads_all = args.ffn_mode == "full"
-    gpu = GpuLayer(w, L, ffn_mode=mode)
-    lay = gpu.layer
-    xd = gpu.upload_x(X)                                   # [T, (batch,) d] resident in HBM
-    yd = torch.zeros_like(xd)
 
-    def run_stream():
-        lay.reset()
-        for t in range(T):
-            lay.step(xd[t], yd[t], w.batch)
+    base = wl.make_layer(w)
+    X = wl.make_batch_inputs(w) if w.batch > 1 else wl.make_inputs(w)
+    T = len(X)
+    gpus = []
+    for l in range(NL):
+        Ll = wl.make_layer_variant(base, w, l)
+        gpus.append(GpuLayer(w, Ll, ffn_mode=mode))      # uploads A, B, c, b; pins the bundle store
+        del Ll
+    layers = [g.layer for g in gpus]
+    xd = gpus[0].upload_x(X)                              # [T, (batch,) d] resident in HBM
+    yd = torch.zeros((NL,) + tuple(xd.shape), dtype=xd.dtype, device=xd.device)
 
-    # eager pass: validates the chain and provides counters for the byte accounting
-    run_stream()
-    torch.cuda.synchronize()
-    st, cnt = lay.state(), lay.counters()
-    assert st["error"] == 0, st
-    rows_per_tok = cnt["ffn_rows"] / cnt["ffn_calls"]
-    active_per_tok = cnt["ffn_active"] / cnt["ffn_calls"]
-    added_per_tok = cnt["added"] / cnt["steps"]
+    if NL == 1:
+        # whole token stream of the layer in one HIP graph
+        def run_stream():
+            layers[0].reset()
+            for t in range(T):
+                layers[0].step(xd[t], yd[0, t], w.batch)
+        graph = None
+        run_stream()                                      # eager pass: validates the chain, fills counters
+        torch.cuda.synchronize()
+        if not args.no_graph:
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                run_stream()
+        step = graph.replay if graph is not None else run_stream
+        launch = "eager" if graph is None else "hip-graph of the whole token stream"
+    else:
+        # one HIP graph per token (all layers); x of the token is copied to a fixed staging buffer first
+        x_stage = torch.zeros_like(xd[0])
+        y_stage = torch.zeros((NL,) + tuple(xd[0].shape), dtype=xd.dtype, device=xd.device)
 
-    graph = None
-    if not args.no_graph:
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
-            run_stream()
-    step = graph.replay if graph is not None else run_stream
+        def token_all_layers():
+            for l, lay in enumerate(layers):
+                lay.step(x_stage, y_stage[l], w.batch)
+        for lay in layers:
+            lay.reset()
+        x_stage.copy_(xd[0])
+        token_all_layers()
+        torch.cuda.synchronize()
+        graph = None
+        if not args.no_graph:
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                token_all_layers()
+        tok = graph.replay if graph is not None else token_all_layers
 
-    for _ in range(args.warmup):
+        def step():
+            for lay in layers:
+                lay.reset()
+            for t in range(T):
+                x_stage.copy_(xd[t])
+                tok()
+        step()                                            # validation pass, fills counters
+        torch.cuda.synchronize()
+        launch = "eager" if graph is None else "one hip-graph per token (all layers), x copied to a staging buffer"
+
+    sts = [lay.state() for lay in layers]
+    assert all(s["error"] == 0 for s in sts), sts
+    cnts = [lay.counters() for lay in layers]
+    tot = {k: sum(c[k] for c in cnts) for k in cnts[0]}
+    rows_per_call = tot["ffn_rows"] / tot["ffn_calls"]
+    active_per_call = tot["ffn_active"] / tot["ffn_calls"]
+    added_per_call = tot["added"] / tot["steps"]
+
+    for _ in range(warmup):
         step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    ms_per_step = dt / args.steps * 1e3
-    us_per_token = ms_per_step * 1e3 / T / w.layers
+    ms_per_step = dt / steps * 1e3
+    us_per_token_layer = ms_per_step * 1e3 / T / NL
 
-    # FFN alone, on the cache state the stream ends in: R back-to-back lif_sparse_ffn calls in a HIP graph,
-    # timed with HIP events on the launch stream; the byte count comes from the device counters of those calls
-    R = 200
+    # FFN alone, on the cache state the stream ends in: R rounds of lif_sparse_ffn over all layers in a HIP graph,
+    # timed with HIP events on the launch stream; the byte count comes from the device counters of those calls.
+    # With one layer the rows stay warm in the 256 MB Infinity Cache; with 32 layers each call reads its rows from HBM.
     ffn = None
     if not args.no_profile:
-        c0 = lay.counters()
+        R = 200 if NL == 1 else 8
+        x_last = xd[T - 1]
         g2 = torch.cuda.CUDAGraph()
         with torch.cuda.graph(g2):
             for _ in range(R):
-                lay.sparse_ffn(xd[T - 1], yd[T - 1], w.batch)
+                for l, lay in enumerate(layers):
+                    lay.sparse_ffn(x_last, yd[l, T - 1], w.batch)
         g2.replay()
         torch.cuda.synchronize()
-        c0 = lay.counters()
+        c0 = [lay.counters() for lay in layers]
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         reps = 5
         e0.record()
@@ -141,35 +179,46 @@ def main():
             g2.replay()
         e1.record()
         torch.cuda.synchronize()
-        c1 = lay.counters()
-        calls = c1["ffn_calls"] - c0["ffn_calls"]
-        assert calls == R * reps
-        rows = (c1["ffn_rows"] - c0["ffn_rows"]) / calls
-        act = (c1["ffn_active"] - c0["ffn_active"]) / calls
+        c1 = [lay.counters() for lay in layers]
+        calls = sum(b["ffn_calls"] - a["ffn_calls"] for a, b in zip(c0, c1))
+        assert calls == R * reps * NL
+        rows = sum(b["ffn_rows"] - a["ffn_rows"] for a, b in zip(c0, c1)) / calls
+        act = sum(b["ffn_active"] - a["ffn_active"] for a, b in zip(c0, c1)) / calls
         ffn = {"us": e0.elapsed_time(e1) * 1e3 / calls, "rows": rows, "active": act}
 
-    # per-kernel durations over one more eager pass of the whole stream: HIP events recorded by the library
-    # on the launch stream around every kernel (these include the event/dispatch overhead of ~2 us per launch)
+    # per-kernel durations over one more eager pass (layer 0 only is instrumented): HIP events recorded by the
+    # library on the launch stream around every kernel (these include ~2 us of event/dispatch overhead per launch)
     kern = {}
     if not args.no_profile:
-        lay.profile_begin(7 * T + 8)
-        run_stream()
-        for k, (ms, n) in lay.profile_collect().items():
+        layers[0].profile_begin(7 * T + 8)
+        if NL == 1:
+            run_stream()
+        else:
+            for lay in layers:
+                lay.reset()
+            for t in range(T):
+                x_stage.copy_(xd[t])
+                token_all_layers()
+        for k, (ms, n) in layers[0].profile_collect().items():
             if n:
                 kern[k] = {"avg_us": ms / n * 1e3, "launches": n}
 
     E, d, G = w.elem_bytes, w.d_model, w.vectors_per_bundle
-    nominal = rows_per_tok * G * d * E
+    nominal = rows_per_call * G * d * E
     out = {
         "metric": "sparse-FFN us/token/layer (whole hot path: predict + window + load + FFN)",
-        "value": us_per_token, "unit": "us/token/layer", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "value": us_per_token_layer, "unit": "us/token/layer", "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": ms_per_step, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",
-        "config": {"workload": describe(w), "tokens_per_step": T, "ffn_mode": args.ffn_mode,
-                   "launch": "eager" if graph is None else "hip-graph of the whole token stream",
-                   "llc": "single layer: the cache working set stays warm in the 256 MB Infinity Cache"},
-        "per_token": {"rows_in_cache": rows_per_tok, "rows_active": active_per_tok, "rows_added": added_per_tok,
-                      "h2d_bytes": added_per_tok * w.bundle_bytes, "nominal_bundle_bytes": nominal},
+        "config": {"workload": describe(w), "tokens_per_step": T, "layers": NL, "ffn_mode": args.ffn_mode,
+                   "launch": launch,
+                   "llc": ("single layer: the cache working set stays warm in the 256 MB Infinity Cache" if NL == 1 else
+                           f"{NL} layers rotate {NL * nominal / 1e6:.0f} MB of cached rows per token: FFN reads come from HBM")},
+        "per_token_per_layer": {"rows_in_cache": rows_per_call, "rows_active": active_per_call,
+                                "rows_added": added_per_call, "h2d_bytes": added_per_call * w.bundle_bytes,
+                                "nominal_bundle_bytes": nominal},
+        "end_to_end_us_per_token": us_per_token_layer * NL,
+        "h2d_bytes_per_token": added_per_call * w.bundle_bytes * NL,
     }
     if ffn:
         up_bytes = ffn["rows"] * (G - 1) * d * E
@@ -177,7 +226,7 @@ def main():
         touched = up_bytes + down_bytes
         nominal_f = ffn["rows"] * G * d * E
         ach = touched / (ffn["us"] * 1e-6) / 1e9
-        out["roofline"] = {"bound": "hbm", "kernel": "ffn_up + ffn_down",
+        out["roofline"] = {"bound": "hbm", "kernel": "ffn_up + ffn_down (one lif_sparse_ffn call)",
                            "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
                            "traffic": None, "algorithmic_bytes_per_launch": touched, "avg_launch_us": ffn["us"],
                            "rows": ffn["rows"], "rows_active": ffn["active"],
@@ -185,10 +234,10 @@ def main():
                            "nominal_GBs": nominal_f / (ffn["us"] * 1e-6) / 1e9,
                            "nominal_frac": nominal_f / (ffn["us"] * 1e-6) / 1e9 / HBM_PEAK_GBS}
     if kern:
-        out["h2d"] = {"GBs_in_load_kernel": added_per_tok * w.bundle_bytes / (kern["load"]["avg_us"] * 1e-6) / 1e9}
+        out["h2d"] = {"GBs_in_load_kernel": added_per_call * w.bundle_bytes / (kern["load"]["avg_us"] * 1e-6) / 1e9}
         out["kernels_avg_us_event_timed"] = {k: round(v["avg_us"], 3) for k, v in kern.items()}
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w, L, X)
+        out["cpu_baseline"] = cpu_baseline(w, base, X)
     print(json.dumps(out))
 
 

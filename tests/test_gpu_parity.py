@@ -252,3 +252,23 @@ def test_hip_graph_replay_matches_eager():
         n = lay.state()["num_used"]
         assert torch.equal(ys, y_eager), f"replay {rep}"
         assert torch.equal(lay.pointers[:n], ptr_eager[:n])
+
+
+def test_c5_stacked_layers_share_the_stream_not_the_state():
+    """Stacked OPT-shaped layers (three of the 32), token-major order as bench.py runs them: every layer
+    has its own predictor, window and cache; bytes loaded per token = sum over layers of |added| x bundle."""
+    from tests.harness import GpuLayer, compare_step
+    w = wl.WORKLOADS["C5"]
+    base = wl.cached_layer("C2")                      # C5 layers have the C2 shape; layer 0 is the C2 layer
+    Ls = [wl.make_layer_variant(base, w, l) for l in (0, 1, 31)]
+    assert not np.array_equal(Ls[0].bundles[:64], Ls[1].bundles[:64])
+    X = wl.make_inputs(w, tokens=8)
+    gpus = [GpuLayer(w, L) for L in Ls]
+    oras = [make_oracle(w, L) for L in Ls]
+    for t in range(len(X)):
+        for gpu, ora in zip(gpus, oras):
+            compare_step(gpu, ora, X[t], w, t, check_cache=(t % 4 == 3))
+    for gpu, ora in zip(gpus, oras):
+        assert gpu.layer.counters()["h2d_bytes"] == ora.bytes_loaded
+    m = [g.layer.step_mask.cpu().numpy() for g in gpus]
+    assert not np.array_equal(m[0], m[1]) and not np.array_equal(m[1], m[2])

@@ -163,6 +163,31 @@ def make_layer(w: Workload, layer: int = 0, structured: bool = False,
     return LayerData(w_up, w_down, w_gate, b, A, B, c, 0.0, bundles)
 
 
+def make_layer_variant(base: LayerData, w: Workload, layer: int) -> LayerData:
+    """Layer `layer` of a stacked workload, derived from a base layer without a new decomposition.
+
+    Neurons are permuted by pi and the input dimensions sign-flipped by s (both seeded by the layer
+    index): up_i' = s * up_pi(i), down_i' = down_pi(i), gate likewise.  The truncated SVD is
+    equivariant under both operations, so A' = diag(s) A, B'[:, i] = B[:, pi(i)], c' = c[pi],
+    b' = b[pi] are exactly the arrays a fresh decomposition and cast would give (up to the
+    sign convention of singular vectors).  Every layer has its own bytes and, for the same token
+    stream, its own masks.  layer 0 is the base itself.
+    """
+    if layer == 0:
+        return base
+    rng = _rng(1000 + layer)
+    pi = rng.permutation(w.d_ffn)
+    sgn = np.where(rng.random(w.d_model) < 0.5, -1, 1).astype(base.w_up.dtype)
+    w_up = base.w_up[pi] * sgn
+    w_down = np.ascontiguousarray(base.w_down[pi])
+    w_gate = None if base.w_gate is None else base.w_gate[pi] * sgn
+    A = base.A * sgn[:, None]
+    B = np.ascontiguousarray(base.B[:, pi])
+    parts = ([w_gate] if w.glu else []) + [w_up, w_down]
+    bundles = np.ascontiguousarray(np.concatenate(parts, axis=1))
+    return LayerData(w_up, w_down, w_gate, base.b[pi].copy(), A, B, base.c[pi].copy(), base.theta, bundles)
+
+
 def make_inputs(w: Workload, stream: int = 0, tokens: int | None = None) -> np.ndarray:
     """AR(1) token stream x_t = rho x_{t-1} + sqrt(1-rho^2) N(0, I), x_0 ~ N(0, I),
     generated in fp64 and cast per token to the storage dtype.  Shape [T, d]."""
