@@ -63,6 +63,7 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="launch every kernel from the host instead of a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true")
+    ap.add_argument("--no-hint", action="store_true", help="do not give the library the expected number of cached rows")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
@@ -145,6 +146,19 @@ def main():
     rows_per_call = tot["ffn_rows"] / tot["ffn_calls"]
     active_per_call = tot["ffn_active"] / tot["ffn_calls"]
     added_per_call = tot["added"] / tot["steps"]
+
+    # row-count hint for the FFN launch geometry (performance only): 90 % of the mean rows in use
+    if not args.no_hint:
+        for lay in layers:
+            lay.set_expected_rows(int(0.9 * rows_per_call))
+        if graph is not None:                             # launch geometry changed: capture again
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                (run_stream if NL == 1 else token_all_layers)()
+            if NL == 1:
+                step = graph.replay
+            else:
+                tok = graph.replay
 
     for _ in range(warmup):
         step()

@@ -199,6 +199,14 @@ int lif_load_bundles(lif_layer* layer, const int32_t* added_dev, const int32_t* 
  */
 int lif_sparse_ffn(lif_layer* layer, const void* x_dev, int32_t batch, void* y_dev, void* stream);
 
+/*
+ * Performance hint: the number of rows the cache
+ * typically holds (for example the mean num_used of an earlier run).  lif_sparse_ffn then
+ * launches that many waves and lets each request its first row before the device-side row
+ * count has arrived.  0 removes the hint.  Results never depend on it.
+ */
+int lif_set_expected_rows(lif_layer* layer, int32_t rows);
+
 /* Synchronises `stream`, then copies the device-side state / counters to the host. */
 int lif_get_state(lif_layer* layer, lif_state* out, void* stream);
 int lif_get_counters(lif_layer* layer, lif_counters* out, void* stream);

@@ -50,6 +50,7 @@ EXPORTS = {
     "lif_update_window": (C.c_int, [C.c_void_p] + [C.c_void_p] * 5 + [C.c_void_p]),
     "lif_load_bundles": (C.c_int, [C.c_void_p] + [C.c_void_p] * 4 + [C.c_void_p]),
     "lif_sparse_ffn": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]),
+    "lif_set_expected_rows": (C.c_int, [C.c_void_p, C.c_int32]),
     "lif_get_state": (C.c_int, [C.c_void_p, C.POINTER(LifState), C.c_void_p]),
     "lif_get_counters": (C.c_int, [C.c_void_p, C.POINTER(LifCounters), C.c_void_p]),
     "lif_profile_begin": (C.c_int, [C.c_void_p, C.c_int32]),
@@ -177,6 +178,9 @@ class Layer:
         self.update_window()
         self.load_bundles()
         self.sparse_ffn(x, y, batch)
+
+    def set_expected_rows(self, rows: int):
+        _check(self.lib.lif_set_expected_rows(self.handle, int(rows)))
 
     # ---- introspection ---------------------------------------------------------------
     def state(self) -> dict:

@@ -11,6 +11,7 @@
 
 #include "lif_common.h"
 #include "lif_ffn.h"
+#include "lif_ffn_mfma.h"
 #include "lif_predict.h"
 #include "lif_window.h"
 
@@ -94,6 +95,7 @@ struct lif_layer {
     float* h;
     size_t row_elems, row_bytes;
     bool window_pending;
+    int expected_rows;          // hint, 0 = none
     // event timing
     bool prof_on;
     int prof_max;
@@ -147,11 +149,14 @@ void launch_ffn_up(lif_layer* L, const void* x, int batch, hipStream_t s) {
     const lif_config& c = L->cfg;
     const int nvec = c.d_model / Vec<T>::N;
     const int ni = (nvec + 63) / 64;
-    const int grid = std::min((c.capacity_rows + 3) / 4, 512);
+    // one wave per row; with a row-count hint the grid is sized to it and the first pass is speculative
+    const int spec = L->expected_rows > 0 ? 1 : 0;
+    const int grid = spec ? std::max(1, std::min(L->expected_rows, c.capacity_rows) / 4)
+                          : std::min((c.capacity_rows + 3) / 4, 512);
     const size_t shm = batch == 1 ? 0 : (size_t)batch * c.d_model * sizeof(T);
 #define LIF_UP_X(NI, XREG)                                                                                   \
     hipLaunchKernelGGL((k_ffn_up<T, NI, GLU, XREG>), dim3(grid), dim3(256), shm, s, (const T*)L->buf.matrix,    \
-                       L->buf.bias, (const T*)x, L->h, c.d_model, batch, c.capacity_rows, L->row_elems, L->st)
+                       L->buf.bias, (const T*)x, L->h, c.d_model, batch, c.capacity_rows, L->row_elems, spec, L->st)
 #define LIF_UP(NI) do { if (batch == 1) LIF_UP_X(NI, true); else LIF_UP_X(NI, false); } while (0)
     if (ni <= 1) LIF_UP(1);
     else if (ni <= 2) LIF_UP(2);
@@ -237,6 +242,7 @@ int lif_create(const lif_config* cfg, const lif_buffers* buf, lif_layer** out) {
     L->row_elems = (size_t)(cfg->glu ? 3 : 2) * cfg->d_model;
     L->row_bytes = L->row_elems * elem_bytes(*cfg);
     L->window_pending = false;
+    L->expected_rows = 0;
     L->prof_on = false;
     L->prof_max = 0;
     *out = L;
@@ -315,7 +321,19 @@ int lif_sparse_ffn(lif_layer* L, const void* x_dev, int32_t batch, void* y_dev, 
     if ((uintptr_t)x_dev % 16 || (uintptr_t)y_dev % 16) return fail(LIF_INVALID_ARG, "x and y must be 16-byte aligned");
     hipStream_t s = (hipStream_t)stream;
     const lif_config& c = L->cfg;
-    {
+    if (c.dtype == LIF_F16 && batch > 1 && c.d_model % 32 == 0) {
+        // batched tokens: the activation stage is a dense contraction -> matrix cores
+        Timed t(L, LIF_K_FFN_UP, s);
+        const int grid = (c.capacity_rows + 15) / 16;
+        if (c.glu)
+            hipLaunchKernelGGL((k_ffn_up_mfma<true>), dim3(grid), dim3(256), 0, s, (const _Float16*)L->buf.matrix,
+                               L->buf.bias, (const _Float16*)x_dev, L->h, c.d_model, batch, c.capacity_rows,
+                               L->row_elems, L->st);
+        else
+            hipLaunchKernelGGL((k_ffn_up_mfma<false>), dim3(grid), dim3(256), 0, s, (const _Float16*)L->buf.matrix,
+                               L->buf.bias, (const _Float16*)x_dev, L->h, c.d_model, batch, c.capacity_rows,
+                               L->row_elems, L->st);
+    } else {
         Timed t(L, LIF_K_FFN_UP, s);
         if (c.dtype == LIF_F32) {
             if (c.glu) launch_ffn_up<float, true>(L, x_dev, batch, s);
@@ -331,6 +349,12 @@ int lif_sparse_ffn(lif_layer* L, const void* x_dev, int32_t batch, void* y_dev, 
         else launch_ffn_down<_Float16>(L, batch, y_dev, s);
     }
     return check_launch();
+}
+
+int lif_set_expected_rows(lif_layer* L, int32_t rows) {
+    if (!L || rows < 0) return fail(LIF_INVALID_ARG, "bad row hint");
+    L->expected_rows = rows;
+    return LIF_OK;
 }
 
 static int read_state(lif_layer* L, DevState* host, void* stream) {

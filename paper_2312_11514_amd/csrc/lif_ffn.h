@@ -1,14 +1,17 @@
 // Step 4: FFN over the cached rows (Section 3.3 item 3):
 //   y = sum_{s < num_used} relu(up_s . x + bias_s) * down_s        (gated: relu(gate_s . x + bias_s) * (up_s . x))
 //
-// Two kernels, both pure streaming of bundle bytes (1 flop per byte at fp16):
+// Two kernels, both pure streaming of bundle bytes (1 flop per byte at fp16).  At the sizes of
+// one decode token (10-60 MB) they run a few microseconds, so what counts is the number of
+// dependent memory round trips; each kernel has two (state + first loads, then the rest).
 //   ffn_up    one wave per cached row: all 16-byte loads of the row's up (and gate) vector are
-//             issued before the first use, x is staged once per workgroup in LDS, the wave
-//             reduces the dot product and writes the activation h[s].
+//             issued before the first use; the wave reduces the dot product and writes the
+//             activation h[s].
 //   ffn_down  one workgroup per slice of output columns: it owns those columns of y, so no
 //             cross-workgroup reduction or atomics are needed and the summation order is
-//             fixed.  It compacts the rows with a non-zero activation (ballot-free ordered
-//             scan in LDS) and streams only their down columns.
+//             fixed.  It compacts the rows with a non-zero activation (prefix sum in LDS) and
+//             streams only their down columns.  (A variant without compaction - predicated
+//             loads over all rows - measured 1.6 us slower at the OPT-6.7B shape.)
 #pragma once
 
 #include "lif_common.h"
@@ -18,13 +21,17 @@ namespace lif {
 // grid-stride over rows, block = 256 (4 waves, one row per wave at a time).
 // NI = 16-byte loads per lane and vector (ceil(d / (64 * VE))).
 // XREG (batch 1): every lane keeps its fragments of x in registers, loaded straight from
-// global memory together with the state, so the kernel pays two memory round trips (state + x,
-// then the rows).  Otherwise x is staged once per workgroup in LDS (dynamic LDS: batch * d
+// global memory.  Otherwise x is staged once per workgroup in LDS (dynamic LDS: batch * d
 // elements) and re-read per token.
+// spec != 0: the first row of every wave is requested before the row count is known (slot <
+// capacity is always valid memory; the result is dropped if the slot is not in use), so the
+// state, x and the first rows travel in one round trip.  The host only asks for this when it
+// was told how many rows to expect and has sized the grid to that many waves.
 template <typename T, int NI, bool GLU, bool XREG>
 __global__ __launch_bounds__(256) void k_ffn_up(const T* __restrict__ matrix, const float* __restrict__ bias,
                                                 const T* __restrict__ x, float* __restrict__ h, int d, int batch,
-                                                int capacity, size_t row_elems, const DevState* __restrict__ st) {
+                                                int capacity, size_t row_elems, int spec,
+                                                const DevState* __restrict__ st) {
     using V = typename Vec<T>::type;
     constexpr int VE = Vec<T>::N;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
@@ -42,6 +49,25 @@ __global__ __launch_bounds__(256) void k_ffn_up(const T* __restrict__ matrix, co
             xr[it] = (idx < nvec) ? xv[idx] : V(0);
         }
     }
+    // speculative first row
+    V u[NI], g[GLU ? NI : 1];
+    float bs = 0.f;
+    if (spec) {
+        const bool ok = gw < capacity;
+        const V* row = reinterpret_cast<const V*>(matrix + (size_t)(ok ? gw : 0) * row_elems);
+#pragma unroll
+        for (int it = 0; it < NI; ++it) {
+            const int idx = it * 64 + lane;
+            const bool in = ok && idx < nvec;
+            if (GLU) {
+                g[it] = in ? row[idx] : V(0);
+                u[it] = in ? row[nvec + idx] : V(0);
+            } else {
+                u[it] = in ? row[idx] : V(0);
+            }
+        }
+        if (ok) bs = bias[gw];
+    }
     const int err = st->error;
     const int n = st->num_used;
     if (err || blockIdx.x * 4 >= n) return;          // whole workgroup has no row (uniform)
@@ -52,24 +78,21 @@ __global__ __launch_bounds__(256) void k_ffn_up(const T* __restrict__ matrix, co
     }
 
     for (int s = gw; s < n; s += nw) {
-        const V* row = reinterpret_cast<const V*>(matrix + (size_t)s * row_elems);
-        V u[NI], g[GLU ? NI : 1];
+        if (s != gw || !spec) {                       // not requested yet: load now that the count is known
+            const V* row = reinterpret_cast<const V*>(matrix + (size_t)s * row_elems);
 #pragma unroll
-        for (int it = 0; it < NI; ++it) {
-            const int idx = it * 64 + lane;
-            if (idx < nvec) {
+            for (int it = 0; it < NI; ++it) {
+                const int idx = it * 64 + lane;
+                const bool in = idx < nvec;
                 if (GLU) {
-                    g[it] = row[idx];
-                    u[it] = row[nvec + idx];
+                    g[it] = in ? row[idx] : V(0);
+                    u[it] = in ? row[nvec + idx] : V(0);
                 } else {
-                    u[it] = row[idx];
+                    u[it] = in ? row[idx] : V(0);
                 }
-            } else {
-                u[it] = V(0);
-                if (GLU) g[it] = V(0);
             }
+            bs = bias[s];
         }
-        const float bs = bias[s];
         for (int b = 0; b < (XREG ? 1 : batch); ++b) {
             float du = 0.f, dg = 0.f;
 #pragma unroll

@@ -272,3 +272,39 @@ def test_c5_stacked_layers_share_the_stream_not_the_state():
         assert gpu.layer.counters()["h2d_bytes"] == ora.bytes_loaded
     m = [g.layer.step_mask.cpu().numpy() for g in gpus]
     assert not np.array_equal(m[0], m[1]) and not np.array_equal(m[1], m[2])
+
+
+@pytest.mark.parametrize("hint", [16, 900, 5000])
+def test_row_count_hint_never_changes_results(hint):
+    """The speculative first pass of the FFN (hint below, near and above the rows in use) gives the same bytes."""
+    from tests.harness import GpuLayer
+    w = wl.WORKLOADS["C2"]
+    L = wl.cached_layer("C2")
+    X = wl.make_inputs(w, tokens=12)
+    ys = []
+    for use_hint in (False, True):
+        gpu = GpuLayer(w, L)
+        if use_hint:
+            gpu.layer.set_expected_rows(hint)
+        xd = gpu.upload_x(X)
+        y = torch.zeros_like(xd)
+        for t in range(len(X)):
+            gpu.layer.step(xd[t], y[t])
+        ys.append(y.cpu().numpy().tobytes())
+        assert gpu.layer.state()["error"] == 0
+    assert ys[0] == ys[1]
+
+
+@pytest.mark.parametrize("batch", [2, 5, 8])
+@pytest.mark.parametrize("glu", [False, True])
+@pytest.mark.parametrize("d_model,dtype", [(608, "f16"), (128, "f16"), (568, "f16"), (256, "f32")])
+def test_batched_tokens_small_shapes(d_model, dtype, glu, batch):
+    """Batches of 2..8 tokens sharing one cache.  fp16 with d % 32 == 0 runs the MFMA activation kernel
+    (d = 608 = 19 x 32: a k-step count that does not divide by the four waves; capacity and row counts
+    not multiples of the 16-row tile); d = 568 and fp32 run the streaming kernel."""
+    w = wl.scaled(wl.WORKLOADS["C1"], name="batched", d_model=d_model, d_ffn=1096, rank=40, window_k=3,
+                  p_active=0.06, dtype=dtype, glu=glu, tokens=10, batch=batch, capacity_rows=1003)
+    L = wl.make_layer(w)
+    X = wl.make_batch_inputs(w)
+    stats = run_stream(w, L, X)
+    assert np.mean([s["n"] for s in stats]) > 100
