@@ -35,7 +35,7 @@ int fail(int code, const char* fmt, const char* detail = "") {
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 struct Layout {
-    size_t state, ring, tpart, move_dst, hole_list, h, total;
+    size_t state, ring, tpart, move_dst, hole_list, h, ypart, total;
 };
 
 int elem_bytes(const lif_config& c) { return c.dtype == LIF_F32 ? 4 : 2; }
@@ -76,6 +76,8 @@ Layout make_layout(const lif_config& c) {
     off = align_up(off + sizeof(int32_t) * c.capacity_rows, 256);
     L.h = off;
     off = align_up(off + sizeof(float) * c.max_batch * c.capacity_rows, 256);
+    L.ypart = off;                     // per-chunk partial outputs of the batched down projection
+    off = align_up(off + (c.max_batch > 1 ? sizeof(float) * kDownChunks * c.max_batch * c.d_model : 0), 256);
     L.total = off;
     return L;
 }
@@ -93,6 +95,7 @@ struct lif_layer {
     int32_t* move_dst;
     int32_t* hole_list;
     float* h;
+    float* ypart;
     size_t row_elems, row_bytes;
     bool window_pending;
     int expected_rows;          // hint, 0 = none
@@ -175,14 +178,25 @@ void launch_ffn_down(lif_layer* L, int batch, void* y, hipStream_t s) {
     const lif_config& c = L->cfg;
     const int cols = kDownLanes * Vec<T>::N;
     const int grid = (c.d_model + cols - 1) / cols;
+    const int colsb = kDownBLanes * Vec<T>::N;
+    const int gridb = (c.d_model + colsb - 1) / colsb;
     const int down_off = (c.glu ? 2 : 1) * c.d_model;
     const bool skip = c.ffn_mode == LIF_FFN_SKIP_DEAD;
 #define LIF_DOWN(BT, SKIP)                                                                                  \
     hipLaunchKernelGGL((k_ffn_down<T, BT, SKIP>), dim3(grid), dim3(256), 0, s, (const T*)L->buf.matrix, L->h,  \
                        (T*)y, c.d_model, batch, c.capacity_rows, L->row_elems, down_off, L->st)
+#define LIF_DOWNB(BT, SKIP)                                                                                 \
+    hipLaunchKernelGGL((k_ffn_down_batched<T, BT, SKIP>), dim3(gridb, kDownChunks), dim3(256), 0, s,           \
+                       (const T*)L->buf.matrix, L->h, L->ypart, c.d_model, batch, c.capacity_rows, L->row_elems, \
+                       down_off, L->st)
     if (batch == 1) { if (skip) LIF_DOWN(1, true); else LIF_DOWN(1, false); }
-    else if (batch <= 4) { if (skip) LIF_DOWN(4, true); else LIF_DOWN(4, false); }
-    else { if (skip) LIF_DOWN(8, true); else LIF_DOWN(8, false); }
+    else {
+        if (batch <= 4) { if (skip) LIF_DOWNB(4, true); else LIF_DOWNB(4, false); }
+        else { if (skip) LIF_DOWNB(8, true); else LIF_DOWNB(8, false); }
+        hipLaunchKernelGGL((k_ffn_down_finish<T>), dim3((batch * c.d_model + 255) / 256), dim3(256), 0, s, L->ypart,
+                           (T*)y, c.d_model, batch, L->st);
+    }
+#undef LIF_DOWNB
 #undef LIF_DOWN
 }
 
@@ -239,6 +253,7 @@ int lif_create(const lif_config* cfg, const lif_buffers* buf, lif_layer** out) {
     L->move_dst = (int32_t*)(ws + lay.move_dst);
     L->hole_list = (int32_t*)(ws + lay.hole_list);
     L->h = (float*)(ws + lay.h);
+    L->ypart = (float*)(ws + lay.ypart);
     L->row_elems = (size_t)(cfg->glu ? 3 : 2) * cfg->d_model;
     L->row_bytes = L->row_elems * elem_bytes(*cfg);
     L->window_pending = false;
