@@ -200,6 +200,19 @@ int lif_load_bundles(lif_layer* layer, const int32_t* added_dev, const int32_t* 
 int lif_sparse_ffn(lif_layer* layer, const void* x_dev, int32_t batch, void* y_dev, void* stream);
 
 /*
+ * One whole step in one call: lif_predict, lif_update_window, lif_load_bundles and
+ * lif_sparse_ffn on the same x, with the same arguments, results and error behaviour as the
+ * four calls in sequence.  For batch == 1 the cache update and the activation stage of the
+ * FFN share one launch: the host-link gather keeps few compute units busy, the others compute
+ * the activations of the resident rows meanwhile, and the loaders compute those of the rows
+ * they write (Section 3.3 items 2 and 3 overlapped), with the same summation order.  y, masks,
+ * ids, counts and the cache are bit-identical to the four-call sequence.
+ */
+int lif_step(lif_layer* layer, const void* x_dev, int32_t batch, void* y_dev, uint8_t* masks_dev,
+             uint8_t* step_mask_dev, int32_t* added_dev, int32_t* n_added_dev, int32_t* removed_dev,
+             int32_t* n_removed_dev, void* stream);
+
+/*
  * Performance hint: the number of rows the cache
  * typically holds (for example the mean num_used of an earlier run).  lif_sparse_ffn then
  * launches that many waves and lets each request its first row before the device-side row

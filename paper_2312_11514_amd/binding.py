@@ -50,6 +50,7 @@ EXPORTS = {
     "lif_update_window": (C.c_int, [C.c_void_p] + [C.c_void_p] * 5 + [C.c_void_p]),
     "lif_load_bundles": (C.c_int, [C.c_void_p] + [C.c_void_p] * 4 + [C.c_void_p]),
     "lif_sparse_ffn": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]),
+    "lif_step": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p] + [C.c_void_p] * 6 + [C.c_void_p]),
     "lif_set_expected_rows": (C.c_int, [C.c_void_p, C.c_int32]),
     "lif_get_state": (C.c_int, [C.c_void_p, C.POINTER(LifState), C.c_void_p]),
     "lif_get_counters": (C.c_int, [C.c_void_p, C.POINTER(LifCounters), C.c_void_p]),
@@ -173,7 +174,13 @@ class Layer:
         _check(self.lib.lif_sparse_ffn(self.handle, _ptr(x), batch, _ptr(y), _stream()))
 
     def step(self, x, y, batch=1):
-        """predict -> update_window -> load_bundles -> sparse_ffn, no host synchronisation."""
+        """lif_step: the whole step in one call (fused cache update + activations for batch 1)."""
+        _check(self.lib.lif_step(self.handle, _ptr(x), batch, _ptr(y), _ptr(self.masks), _ptr(self.step_mask),
+                                 _ptr(self.added), _ptr(self.n_added), _ptr(self.removed), _ptr(self.n_removed),
+                                 _stream()))
+
+    def step_calls(self, x, y, batch=1):
+        """The same step as four separate calls: predict -> update_window -> load_bundles -> sparse_ffn."""
         self.predict(x, batch)
         self.update_window()
         self.load_bundles()

@@ -13,6 +13,7 @@
 #include "lif_ffn.h"
 #include "lif_ffn_mfma.h"
 #include "lif_predict.h"
+#include "lif_step.h"
 #include "lif_window.h"
 
 using namespace lif;
@@ -35,7 +36,7 @@ int fail(int code, const char* fmt, const char* detail = "") {
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 struct Layout {
-    size_t state, ring, tpart, move_dst, hole_list, h, ypart, total;
+    size_t state, ring, tpart, move_dst, hole_list, h, ypart, h_new, stamp, total;
 };
 
 int elem_bytes(const lif_config& c) { return c.dtype == LIF_F32 ? 4 : 2; }
@@ -78,6 +79,10 @@ Layout make_layout(const lif_config& c) {
     off = align_up(off + sizeof(float) * c.max_batch * c.capacity_rows, 256);
     L.ypart = off;                     // per-chunk partial outputs of the batched down projection
     off = align_up(off + (c.max_batch > 1 ? sizeof(float) * kDownChunks * c.max_batch * c.d_model : 0), 256);
+    L.h_new = off;                     // activations written by the fused load kernel (single-token steps)
+    off = align_up(off + sizeof(float) * c.capacity_rows, 256);
+    L.stamp = off;                     // step number at which h_new[slot] was written
+    off = align_up(off + sizeof(int32_t) * c.capacity_rows, 256);
     L.total = off;
     return L;
 }
@@ -96,6 +101,8 @@ struct lif_layer {
     int32_t* hole_list;
     float* h;
     float* ypart;
+    float* h_new;
+    int32_t* stamp;
     size_t row_elems, row_bytes;
     bool window_pending;
     int expected_rows;          // hint, 0 = none
@@ -174,7 +181,9 @@ void launch_ffn_up(lif_layer* L, const void* x, int batch, hipStream_t s) {
 }
 
 template <typename T>
-void launch_ffn_down(lif_layer* L, int batch, void* y, hipStream_t s) {
+void launch_ffn_down(lif_layer* L, int batch, void* y, hipStream_t s, bool use_new = false) {
+    const float* h_new = use_new ? L->h_new : nullptr;
+    const int32_t* stamp = use_new ? L->stamp : nullptr;
     const lif_config& c = L->cfg;
     const int cols = kDownLanes * Vec<T>::N;
     const int grid = (c.d_model + cols - 1) / cols;
@@ -184,7 +193,7 @@ void launch_ffn_down(lif_layer* L, int batch, void* y, hipStream_t s) {
     const bool skip = c.ffn_mode == LIF_FFN_SKIP_DEAD;
 #define LIF_DOWN(BT, SKIP)                                                                                  \
     hipLaunchKernelGGL((k_ffn_down<T, BT, SKIP>), dim3(grid), dim3(256), 0, s, (const T*)L->buf.matrix, L->h,  \
-                       (T*)y, c.d_model, batch, c.capacity_rows, L->row_elems, down_off, L->st)
+                       h_new, stamp, (T*)y, c.d_model, batch, c.capacity_rows, L->row_elems, down_off, L->st)
 #define LIF_DOWNB(BT, SKIP)                                                                                 \
     hipLaunchKernelGGL((k_ffn_down_batched<T, BT, SKIP>), dim3(gridb, kDownChunks), dim3(256), 0, s,           \
                        (const T*)L->buf.matrix, L->h, L->ypart, c.d_model, batch, c.capacity_rows, L->row_elems, \
@@ -198,6 +207,30 @@ void launch_ffn_down(lif_layer* L, int batch, void* y, hipStream_t s) {
     }
 #undef LIF_DOWNB
 #undef LIF_DOWN
+}
+
+template <typename T, bool GLU>
+void launch_load_up(lif_layer* L, const void* x, const int32_t* added, hipStream_t s) {
+    const lif_config& c = L->cfg;
+    const int nvec = c.d_model / Vec<T>::N;
+    const int ni = (nvec + 63) / 64;
+    const int spec = L->expected_rows > 0 ? 1 : 0;
+    const int up_blocks = spec ? std::max(1, std::min(L->expected_rows, c.capacity_rows) / 4)
+                               : std::min((c.capacity_rows + 3) / 4, 512);
+#define LIF_LU(NI)                                                                                            \
+    hipLaunchKernelGGL((k_load_up<T, NI, GLU>), dim3(kStepLoadWgs + up_blocks), dim3(256), 0, s,                  \
+                       (T*)L->buf.matrix, L->buf.pointers, L->buf.bias, (const T*)L->host_alias, L->buf.b, added, \
+                       L->move_dst, L->row_elems, c.d_ffn, c.d_model, c.capacity_rows, (const T*)x, L->h,         \
+                       L->h_new, L->stamp, spec, L->st)
+    if (ni <= 1) LIF_LU(1);
+    else if (ni <= 2) LIF_LU(2);
+    else if (ni <= 4) LIF_LU(4);
+    else if (ni <= 6) LIF_LU(6);
+    else if (ni <= 8) LIF_LU(8);
+    else if (ni <= 9) LIF_LU(9);
+    else if (ni <= 12) LIF_LU(12);
+    else LIF_LU(16);
+#undef LIF_LU
 }
 
 int check_launch() {
@@ -254,6 +287,8 @@ int lif_create(const lif_config* cfg, const lif_buffers* buf, lif_layer** out) {
     L->hole_list = (int32_t*)(ws + lay.hole_list);
     L->h = (float*)(ws + lay.h);
     L->ypart = (float*)(ws + lay.ypart);
+    L->h_new = (float*)(ws + lay.h_new);
+    L->stamp = (int32_t*)(ws + lay.stamp);
     L->row_elems = (size_t)(cfg->glu ? 3 : 2) * cfg->d_model;
     L->row_bytes = L->row_elems * elem_bytes(*cfg);
     L->window_pending = false;
@@ -276,7 +311,8 @@ int lif_reset(lif_layer* L, void* stream) {
     hipStream_t s = (hipStream_t)stream;
     const int total_words = L->cfg.window_k * ring_words(L->cfg);
     const int grid = std::min((total_words + 255) / 256, 256);
-    hipLaunchKernelGGL(k_reset, dim3(grid), dim3(256), 0, s, L->ring, total_words, L->st);
+    hipLaunchKernelGGL(k_reset, dim3(grid), dim3(256), 0, s, L->ring, total_words, L->stamp, L->cfg.capacity_rows,
+                       L->st);
     L->window_pending = false;
     return check_launch();
 }
@@ -362,6 +398,40 @@ int lif_sparse_ffn(lif_layer* L, const void* x_dev, int32_t batch, void* y_dev, 
         Timed t(L, LIF_K_FFN_DOWN, s);
         if (c.dtype == LIF_F32) launch_ffn_down<float>(L, batch, y_dev, s);
         else launch_ffn_down<_Float16>(L, batch, y_dev, s);
+    }
+    return check_launch();
+}
+
+int lif_step(lif_layer* L, const void* x_dev, int32_t batch, void* y_dev, uint8_t* masks_dev,
+             uint8_t* step_mask_dev, int32_t* added_dev, int32_t* n_added_dev, int32_t* removed_dev,
+             int32_t* n_removed_dev, void* stream) {
+    int rc = lif_predict(L, x_dev, batch, masks_dev, step_mask_dev, stream);
+    if (rc) return rc;
+    if (!y_dev || (uintptr_t)y_dev % 16) return fail(LIF_INVALID_ARG, "y must be a 16-byte aligned device pointer");
+    rc = lif_update_window(L, step_mask_dev, added_dev, n_added_dev, removed_dev, n_removed_dev, stream);
+    if (rc) return rc;
+    if (batch > 1) {
+        rc = lif_load_bundles(L, added_dev, n_added_dev, removed_dev, n_removed_dev, stream);
+        if (rc) return rc;
+        return lif_sparse_ffn(L, x_dev, batch, y_dev, stream);
+    }
+    hipStream_t s = (hipStream_t)stream;
+    const lif_config& c = L->cfg;
+    {
+        Timed t(L, LIF_K_LOAD, s);
+        if (c.dtype == LIF_F32) {
+            if (c.glu) launch_load_up<float, true>(L, x_dev, added_dev, s);
+            else launch_load_up<float, false>(L, x_dev, added_dev, s);
+        } else {
+            if (c.glu) launch_load_up<_Float16, true>(L, x_dev, added_dev, s);
+            else launch_load_up<_Float16, false>(L, x_dev, added_dev, s);
+        }
+    }
+    L->window_pending = false;
+    {
+        Timed t(L, LIF_K_FFN_DOWN, s);
+        if (c.dtype == LIF_F32) launch_ffn_down<float>(L, 1, y_dev, s, true);
+        else launch_ffn_down<_Float16>(L, 1, y_dev, s, true);
     }
     return check_launch();
 }

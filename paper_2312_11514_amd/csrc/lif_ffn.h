@@ -27,18 +27,20 @@ namespace lif {
 // capacity is always valid memory; the result is dropped if the slot is not in use), so the
 // state, x and the first rows travel in one round trip.  The host only asks for this when it
 // was told how many rows to expect and has sized the grid to that many waves.
+// `block` / `nblocks`: index and count of the workgroups that share this role; `n_ptr`: device
+// address of the number of rows to cover (num_used, or the rows kept by a pending deletion).
 template <typename T, int NI, bool GLU, bool XREG>
-__global__ __launch_bounds__(256) void k_ffn_up(const T* __restrict__ matrix, const float* __restrict__ bias,
-                                                const T* __restrict__ x, float* __restrict__ h, int d, int batch,
-                                                int capacity, size_t row_elems, int spec,
-                                                const DevState* __restrict__ st) {
+__device__ __forceinline__ void ffn_up_role(const T* __restrict__ matrix, const float* __restrict__ bias,
+                                            const T* __restrict__ x, float* __restrict__ h, int d, int batch,
+                                            int capacity, size_t row_elems, int spec, int block, int nblocks,
+                                            const int32_t* __restrict__ n_ptr, const DevState* __restrict__ st) {
     using V = typename Vec<T>::type;
     constexpr int VE = Vec<T>::N;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     V* xs = reinterpret_cast<V*>(smem_raw);
     const int tid = threadIdx.x, lane = tid & 63;
     const int nvec = d / VE;
-    const int gw = blockIdx.x * 4 + (tid >> 6), nw = gridDim.x * 4;
+    const int gw = block * 4 + (tid >> 6), nw = nblocks * 4;
     const V* xv = reinterpret_cast<const V*>(x);
 
     V xr[XREG ? NI : 1];
@@ -69,8 +71,8 @@ __global__ __launch_bounds__(256) void k_ffn_up(const T* __restrict__ matrix, co
         if (ok) bs = bias[gw];
     }
     const int err = st->error;
-    const int n = st->num_used;
-    if (err || blockIdx.x * 4 >= n) return;          // whole workgroup has no row (uniform)
+    const int n = *n_ptr;
+    if (err || block * 4 >= n) return;               // whole workgroup has no row (uniform)
 
     if (!XREG) {
         for (int i = tid; i < batch * nvec; i += 256) xs[i] = xv[i];
@@ -120,14 +122,26 @@ __global__ __launch_bounds__(256) void k_ffn_up(const T* __restrict__ matrix, co
     }
 }
 
+template <typename T, int NI, bool GLU, bool XREG>
+__global__ __launch_bounds__(256) void k_ffn_up(const T* __restrict__ matrix, const float* __restrict__ bias,
+                                                const T* __restrict__ x, float* __restrict__ h, int d, int batch,
+                                                int capacity, size_t row_elems, int spec,
+                                                const DevState* __restrict__ st) {
+    ffn_up_role<T, NI, GLU, XREG>(matrix, bias, x, h, d, batch, capacity, row_elems, spec, blockIdx.x, gridDim.x,
+                                  &st->num_used, st);
+}
+
 constexpr int kDownLanes = 4;       // lanes per column slice (4 x 16 B = 64 B of every down column)
 constexpr int kDownRg = 64;         // row groups per workgroup
 constexpr int kDownTile = 2048;     // cached rows compacted per pass
 
 // grid = ceil(d / (4 * VE)), block = 256 = 64 row groups x 4 lanes.
 // SKIP: rows whose activation is zero for every token of the batch are not read.
+// h_new / stamp (may be null): activations of the rows that the fused load kernel wrote during the
+// step whose number equals stamp[s]; they override h for those rows.
 template <typename T, int BT, bool SKIP>
 __global__ __launch_bounds__(256) void k_ffn_down(const T* __restrict__ matrix, const float* __restrict__ h,
+                                                  const float* __restrict__ h_new, const int32_t* __restrict__ stamp,
                                                   T* __restrict__ y, int d, int batch, int capacity,
                                                   size_t row_elems, int down_off, DevState* __restrict__ st) {
     using V = typename Vec<T>::type;
@@ -163,8 +177,24 @@ __global__ __launch_bounds__(256) void k_ffn_down(const T* __restrict__ matrix, 
             const int s = q * 256 + tid;
             hfirst[q][b] = (s < capacity && b < batch) ? h[(size_t)b * capacity + s] : 0.f;
         }
+    int sfirst[PER];
+#pragma unroll
+    for (int q = 0; q < PER; ++q) {
+        const int s = q * 256 + tid;
+        sfirst[q] = (stamp && s < capacity) ? stamp[s] : -1;
+    }
     const int err = st->error;
     const int n = err ? 0 : st->num_used;
+    const int cur_step = st->step;
+    if (stamp) {
+#pragma unroll
+        for (int q = 0; q < PER; ++q)
+            if (sfirst[q] == cur_step) {
+#pragma unroll
+                for (int b = 0; b < BT; ++b)
+                    if (b < batch) hfirst[q][b] = h_new[(size_t)b * capacity + q * 256 + tid];
+            }
+    }
     __syncthreads();
     if (err) return;
     for (int s_base = 0; s_base < n; s_base += TS) {
@@ -178,7 +208,11 @@ __global__ __launch_bounds__(256) void k_ffn_down(const T* __restrict__ matrix, 
 #pragma unroll
             for (int b = 0; b < BT; ++b) {
                 float v = 0.f;
-                if (s < n && b < batch) v = (s_base == 0) ? hfirst[q][b] : h[(size_t)b * capacity + s];
+                if (s < n && b < batch) {
+                    if (s_base == 0) v = hfirst[q][b];
+                    else v = (stamp && stamp[s] == cur_step) ? h_new[(size_t)b * capacity + s]
+                                                             : h[(size_t)b * capacity + s];
+                }
                 hloc[q][b] = v;
                 any |= (v != 0.f);
             }

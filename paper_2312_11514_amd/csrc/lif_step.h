@@ -1,0 +1,230 @@
+// Fused cache update + activation stage for single-token steps (lif_step).
+//
+// The host-to-device gather of new bundles is bound by the host link and keeps only ~32
+// workgroups busy for tens of microseconds (Section 3.3 item 2), while the activation stage of
+// the FFN (Section 3.3 item 3) streams the rows that are already resident.  Both only need the
+// token's x and the deletion plan, so one launch runs them side by side:
+//   workgroups [0, kStepLoadWgs)   loader role: row moves + pinned-host appends with the layout of
+//                                  k_load, and - since every bundle passes through their registers -
+//                                  the activation of each row they write (h_new, stamped with the step);
+//   workgroups [kStepLoadWgs, ...) activation role over the rows kept by the deletion (slots < n').
+// The activation role may read a hole while a loader overwrites it; that value is never used,
+// because the loader's stamped activation takes precedence in the down-projection kernel.
+#pragma once
+
+#include "lif_ffn.h"
+#include "lif_window.h"
+
+namespace lif {
+
+#ifndef LIF_STEP_LOAD_WGS
+#define LIF_STEP_LOAD_WGS 32
+#endif
+#ifndef LIF_STEP_LOAD_WAVES
+#define LIF_STEP_LOAD_WAVES 1
+#endif
+constexpr int kStepLoadWgs = LIF_STEP_LOAD_WGS;       // workgroups in the loader role
+constexpr int kStepLoadWaves = LIF_STEP_LOAD_WAVES;   // waves of each that load (the others exit at once)
+
+// Loader role, one wave per work item.  Work item q covers tail slot s = n' + q (see k_load):
+// the wave requests the whole host bundle of added[q] first (the long latency), moves the live
+// tail row to its hole meanwhile, then writes the bundle to slot s.  Lane l holds the same
+// 16-byte pieces of every vector as in the activation role (piece it * 64 + l), keeps x in
+// registers the same way and sums in the same order, so the activations it writes are bit
+// for bit those the activation kernel would compute.  32 waves x one bundle in flight keeps
+// the host link at its best operating point (a few hundred KiB outstanding).
+template <typename T, int NI, bool GLU>
+__device__ __forceinline__ void load_role(T* __restrict__ matrix, int32_t* __restrict__ pointers,
+                                          float* __restrict__ bias, const T* __restrict__ host,
+                                          const float* __restrict__ b, const int32_t* __restrict__ added,
+                                          const int32_t* __restrict__ move_dst, size_t row_elems, int F, int d,
+                                          int capacity, const T* __restrict__ x, float* __restrict__ h_new,
+                                          int32_t* __restrict__ stamp, int wave_id, int nwaves, DevState* st) {
+    using V = typename Vec<T>::type;
+    constexpr int VE = Vec<T>::N;
+    constexpr int G = GLU ? 3 : 2;
+    const int lane = threadIdx.x & 63;
+    const int nvec = d / VE;
+    const V* xv = reinterpret_cast<const V*>(x);
+    V xr[NI];
+#pragma unroll
+    for (int it = 0; it < NI; ++it) {
+        const int idx = it * 64 + lane;
+        xr[it] = (idx < nvec) ? xv[idx] : V(0);
+    }
+    // The bookkeeping of the first 64 work items of this wave (one per lane) is requested together
+    // with the state, before the counts are known (the arrays span the whole capacity; entries past
+    // the counts are masked afterwards): one device-memory round trip in front of the host reads.
+    int dst_l = -1, nid_l = -1;
+    {
+        const int ql = wave_id + lane * nwaves;
+        if (ql < capacity) dst_l = move_dst[ql];
+        if (ql < F) nid_l = added[ql];
+    }
+    if (st->error) return;
+    const int n2 = st->n_base, c = st->n_removed, a = st->n_added, step = st->step;
+    const int items = max(c, a);
+    for (int q0 = wave_id; q0 < items; q0 += nwaves * kWave) {
+      const int ql = q0 + lane * nwaves;                 // work item of this lane
+      if (q0 != wave_id) {                               // later batches (more than 64 items per wave)
+          dst_l = (ql < c) ? move_dst[ql] : -1;
+          nid_l = (ql < a) ? added[ql] : -1;
+      }
+      if (ql >= c) dst_l = -1;
+      if (ql >= a || nid_l >= F) nid_l = -1;
+      int optr_l = -1;
+      float obias_l = 0.f, nbias_l = 0.f;
+      if (ql < items) {
+          optr_l = pointers[n2 + ql];
+          obias_l = bias[n2 + ql];
+          if (nid_l >= 0) nbias_l = b[nid_l];
+      }
+      const int nitems = min(kWave, (items - q0 + nwaves - 1) / nwaves);
+      // Software pipeline over the items of this wave: the reads of item j+1 are requested as soon
+      // as the registers of item j are free (after its stores and per-lane dot products) and fly
+      // while item j's wave reductions and bookkeeping writes complete.  Device rows (the move) are
+      // requested before host rows so that waiting for them does not wait for the host link.
+      int dst = __shfl(dst_l, 0, kWave), nid = __shfl(nid_l, 0, kWave);
+      V hv[G][NI], mv[G][NI];
+      {
+          const V* hrow = reinterpret_cast<const V*>(host + (size_t)max(nid, 0) * row_elems);
+          const V* srow = reinterpret_cast<const V*>(matrix + (size_t)(n2 + q0) * row_elems);
+#pragma unroll
+          for (int g = 0; g < G; ++g)
+#pragma unroll
+              for (int it = 0; it < NI; ++it) {
+                  const int idx = it * 64 + lane;
+                  mv[g][it] = (dst >= 0 && idx < nvec) ? srow[g * nvec + idx] : V(0);
+              }
+#pragma unroll
+          for (int g = 0; g < G; ++g)
+#pragma unroll
+              for (int it = 0; it < NI; ++it) {
+                  const int idx = it * 64 + lane;
+                  hv[g][it] = (nid >= 0 && idx < nvec) ? hrow[g * nvec + idx] : V(0);
+              }
+      }
+      for (int j = 0; j < nitems; ++j) {
+        const int s = n2 + q0 + j * nwaves;
+        V* srow = reinterpret_cast<V*>(matrix + (size_t)s * row_elems);
+        V* drow = reinterpret_cast<V*>(matrix + (size_t)max(dst, 0) * row_elems);
+        const int32_t old_ptr = __shfl(optr_l, j, kWave);
+        const float old_bias = __shfl(obias_l, j, kWave);
+        const float new_bias = __shfl(nbias_l, j, kWave);
+        float mdu = 0.f, mdg = 0.f, hdu = 0.f, hdg = 0.f;
+        if (dst >= 0) {                                   // wave-uniform
+#pragma unroll
+            for (int g = 0; g < G; ++g)
+#pragma unroll
+                for (int it = 0; it < NI; ++it) {
+                    const int idx = it * 64 + lane;
+                    if (idx < nvec) drow[g * nvec + idx] = mv[g][it];
+                }
+#pragma unroll
+            for (int it = 0; it < NI; ++it) {
+                mdu = dot_acc(mv[GLU ? 1 : 0][it], xr[it], mdu);
+                if (GLU) mdg = dot_acc(mv[0][it], xr[it], mdg);
+            }
+        }
+        if (nid >= 0) {                                   // wave-uniform
+#pragma unroll
+            for (int g = 0; g < G; ++g)
+#pragma unroll
+                for (int it = 0; it < NI; ++it) {
+                    const int idx = it * 64 + lane;
+                    if (idx < nvec) srow[g * nvec + idx] = hv[g][it];
+                }
+#pragma unroll
+            for (int it = 0; it < NI; ++it) {
+                hdu = dot_acc(hv[GLU ? 1 : 0][it], xr[it], hdu);
+                if (GLU) hdg = dot_acc(hv[0][it], xr[it], hdg);
+            }
+        }
+        // request item j + 1
+        const int dst_n = (j + 1 < nitems) ? __shfl(dst_l, j + 1, kWave) : -1;
+        const int nid_n = (j + 1 < nitems) ? __shfl(nid_l, j + 1, kWave) : -1;
+        if (j + 1 < nitems) {
+            const V* hrow = reinterpret_cast<const V*>(host + (size_t)max(nid_n, 0) * row_elems);
+            const V* nrow = reinterpret_cast<const V*>(matrix + (size_t)(s + nwaves) * row_elems);
+#pragma unroll
+            for (int g = 0; g < G; ++g)
+#pragma unroll
+                for (int it = 0; it < NI; ++it) {
+                    const int idx = it * 64 + lane;
+                    mv[g][it] = (dst_n >= 0 && idx < nvec) ? nrow[g * nvec + idx] : V(0);
+                }
+#pragma unroll
+            for (int g = 0; g < G; ++g)
+#pragma unroll
+                for (int it = 0; it < NI; ++it) {
+                    const int idx = it * 64 + lane;
+                    hv[g][it] = (nid_n >= 0 && idx < nvec) ? hrow[g * nvec + idx] : V(0);
+                }
+        }
+        // finish item j: same order of operations as the activation kernel
+        if (dst >= 0) {
+            const float du = wave_sum(mdu);
+            float act;
+            if (GLU) {
+                const float dg = wave_sum(mdg);
+                act = fmaxf(dg + old_bias, 0.f) * du;
+            } else {
+                act = fmaxf(du + old_bias, 0.f);
+            }
+            if (lane == 0) {
+                pointers[dst] = old_ptr;
+                bias[dst] = old_bias;
+                h_new[dst] = act;
+                stamp[dst] = step;
+            }
+        }
+        if (nid >= 0) {
+            const float du = wave_sum(hdu);
+            float act;
+            if (GLU) {
+                const float dg = wave_sum(hdg);
+                act = fmaxf(dg + new_bias, 0.f) * du;
+            } else {
+                act = fmaxf(du + new_bias, 0.f);
+            }
+            if (lane == 0) {
+                pointers[s] = nid;
+                bias[s] = new_bias;
+                h_new[s] = act;
+                stamp[s] = step;
+            }
+        }
+        dst = dst_n;
+        nid = nid_n;
+      }
+    }
+    if (wave_id == 0 && lane == 0) {
+        st->num_used = n2 + a;
+        st->c_h2d_bytes += (unsigned long long)a * row_elems * sizeof(T);
+    }
+}
+
+// grid = kStepLoadWgs + up_blocks, block = 256.  Batch 1 only.
+template <typename T, int NI, bool GLU>
+__global__ __launch_bounds__(256) void k_load_up(T* __restrict__ matrix, int32_t* __restrict__ pointers,
+                                                 float* __restrict__ bias, const T* __restrict__ host,
+                                                 const float* __restrict__ b, const int32_t* __restrict__ added,
+                                                 const int32_t* __restrict__ move_dst, size_t row_elems, int F, int d,
+                                                 int capacity, const T* __restrict__ x, float* __restrict__ h,
+                                                 float* __restrict__ h_new, int32_t* __restrict__ stamp, int spec,
+                                                 DevState* st) {
+    if (blockIdx.x < kStepLoadWgs) {
+        const int w = threadIdx.x >> 6;
+        if (w >= kStepLoadWaves) return;
+        load_role<T, NI, GLU>(matrix, pointers, bias, host, b, added, move_dst, row_elems, F, d, capacity, x, h_new, stamp,
+                              blockIdx.x * kStepLoadWaves + w, kStepLoadWgs * kStepLoadWaves, st);
+    } else {
+#ifdef LIF_EXPERIMENT_NO_UP
+        return;
+#endif
+        ffn_up_role<T, NI, GLU, true>(matrix, bias, x, h, d, 1, capacity, row_elems, spec, blockIdx.x - kStepLoadWgs,
+                                      gridDim.x - kStepLoadWgs, &st->n_base, st);
+    }
+}
+
+}  // namespace lif

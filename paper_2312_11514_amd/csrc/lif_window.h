@@ -297,9 +297,11 @@ __global__ __launch_bounds__(256) void k_load(char* __restrict__ matrix, int32_t
 }
 
 // Empty cache: no mask in the window, state and counters zero.
-__global__ void k_reset(unsigned long long* __restrict__ ring, int ring_total_words, DevState* st) {
+__global__ void k_reset(unsigned long long* __restrict__ ring, int ring_total_words, int32_t* __restrict__ stamp,
+                        int capacity, DevState* st) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     for (int j = i; j < ring_total_words; j += gridDim.x * blockDim.x) ring[j] = 0ull;
+    for (int j = i; j < capacity; j += gridDim.x * blockDim.x) stamp[j] = -1;   // no activation from a fused step
     if (i == 0) {
         DevState z = {};
         *st = z;

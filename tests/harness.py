@@ -56,8 +56,9 @@ def rel_l2(y, ref):
     return float(out.max())
 
 
-def compare_step(gpu: GpuLayer, ora: O.OracleLayer, x, w, t, check_cache=True):
-    """One token (x [d]) or one batch (x [batch, d]) through both paths; asserts parity of every output."""
+def compare_step(gpu: GpuLayer, ora: O.OracleLayer, x, w, t, check_cache=True, api="calls"):
+    """One token (x [d]) or one batch (x [batch, d]) through both paths; asserts parity of every output.
+    api = "calls": the four C-ABI calls in sequence; "step": the single fused lif_step call."""
     lay = gpu.layer
     batch = 1 if x.ndim == 1 else x.shape[0]
     xd = gpu.upload_x(x)
@@ -65,13 +66,16 @@ def compare_step(gpu: GpuLayer, ora: O.OracleLayer, x, w, t, check_cache=True):
 
     ref = ora.step(x)
 
-    lay.predict(xd, batch)
-    lay.update_window()
+    if api == "step":
+        lay.step(xd, gpu.y, batch)
+    else:
+        lay.predict(xd, batch)
+        lay.update_window()
+        lay.load_bundles()
+        lay.sparse_ffn(xd, gpu.y, batch)
     na, nr = int(lay.n_added.item()), int(lay.n_removed.item())
     added = lay.added[:na].cpu().numpy()
     removed = lay.removed[:nr].cpu().numpy()
-    lay.load_bundles()
-    lay.sparse_ffn(xd, gpu.y, batch)
     st = lay.state()
 
     masks = lay.masks[:batch].cpu().numpy()

@@ -18,14 +18,14 @@ def make_oracle(w, L, capacity=None, k=None):
                          L.A, L.B, L.c, L.theta, L.b, L.bundles)
 
 
-def run_stream(w, L, X, ffn_mode=0, check_every=1):
+def run_stream(w, L, X, ffn_mode=0, check_every=1, api="calls"):
     from tests.harness import GpuLayer, compare_step
     gpu = GpuLayer(w, L, ffn_mode=ffn_mode)
     ora = make_oracle(w, L)
     stats = []
     for t in range(len(X)):
         print(f"[{w.name}] token {t}", flush=True) if t % 32 == 0 else None
-        stats.append(compare_step(gpu, ora, X[t], w, t, check_cache=(t % check_every == 0 or t == len(X) - 1)))
+        stats.append(compare_step(gpu, ora, X[t], w, t, check_cache=(t % check_every == 0 or t == len(X) - 1), api=api))
     cnt = gpu.layer.counters()
     assert cnt["h2d_bytes"] == ora.bytes_loaded
     assert cnt["rows_moved"] == ora.rows_moved
@@ -34,23 +34,25 @@ def run_stream(w, L, X, ffn_mode=0, check_every=1):
     return stats
 
 
+@pytest.mark.parametrize("api", ["calls", "step"])
 @pytest.mark.parametrize("ffn_mode", [0, 1])
-def test_c1_tiny_fp32_whole_path(ffn_mode):
+def test_c1_tiny_fp32_whole_path(ffn_mode, api):
     w = wl.WORKLOADS["C1"]
-    stats = run_stream(w, wl.make_layer(w), wl.make_inputs(w), ffn_mode)
+    stats = run_stream(w, wl.make_layer(w), wl.make_inputs(w), ffn_mode, api=api)
     assert max(s["err"] for s in stats) < 1e-5          # fp32 storage: far below the fp16 bar
     assert any(s["moved"] > 0 for s in stats) and any(s["removed"] > 0 for s in stats)
 
 
+@pytest.mark.parametrize("api", ["calls", "step"])
 @pytest.mark.parametrize("ffn_mode", [0, 1])
 @pytest.mark.parametrize("glu", [False, True])
 @pytest.mark.parametrize("dtype", ["f32", "f16"])
-def test_ragged_shapes_whole_path(glu, dtype, ffn_mode):
+def test_ragged_shapes_whole_path(glu, dtype, ffn_mode, api):
     """Shapes that end in a partial tile everywhere: d = 71 x 8 (like 4544 = 71 x 64), F not a
     multiple of 128, rank not a power of two, capacity not a multiple of 1024."""
     w = wl.scaled(wl.WORKLOADS["C1"], name="ragged", d_model=568, d_ffn=1096, rank=40, window_k=3,
                   p_active=0.08, dtype=dtype, glu=glu, tokens=24, capacity_rows=700)
-    run_stream(w, wl.make_layer(w), wl.make_inputs(w), ffn_mode)
+    run_stream(w, wl.make_layer(w), wl.make_inputs(w), ffn_mode, api=api)
 
 
 def test_c2_opt_shape_fp16_whole_path():
@@ -58,7 +60,7 @@ def test_c2_opt_shape_fp16_whole_path():
     w = wl.WORKLOADS["C2"]
     L = wl.cached_layer("C2")
     X = wl.make_inputs(w, tokens=96)
-    stats = run_stream(w, L, X, ffn_mode=0, check_every=8)
+    stats = run_stream(w, L, X, ffn_mode=0, check_every=8, api="step")
     assert np.mean([s["n"] for s in stats[10:]]) > 800         # window union of ~3 % active masks
     print("C2 max rel-L2 %.2e" % max(s["err"] for s in stats))
 
@@ -76,7 +78,7 @@ def test_c3_falcon_shape_fp16_whole_path():
     w = wl.WORKLOADS["C3"]
     L = wl.cached_layer("C3")
     X = wl.make_inputs(w, tokens=40)
-    stats = run_stream(w, L, X, check_every=8)
+    stats = run_stream(w, L, X, check_every=8, api="step")
     print("C3 max rel-L2 %.2e, rows %.0f" % (max(s["err"] for s in stats), np.mean([s["n"] for s in stats[10:]])))
 
 
@@ -84,7 +86,7 @@ def test_c4_llama_shape_gated_batch1():
     w = wl.WORKLOADS["C4"]
     L = wl.cached_layer("C4")
     X = wl.make_inputs(w, tokens=32)
-    stats = run_stream(w, L, X, check_every=8)
+    stats = run_stream(w, L, X, check_every=8, api="step")
     print("C4 max rel-L2 %.2e, rows %.0f" % (max(s["err"] for s in stats), np.mean([s["n"] for s in stats[10:]])))
 
 
@@ -308,3 +310,30 @@ def test_batched_tokens_small_shapes(d_model, dtype, glu, batch):
     X = wl.make_batch_inputs(w)
     stats = run_stream(w, L, X)
     assert np.mean([s["n"] for s in stats]) > 100
+
+
+def test_fused_step_equals_four_calls_bit_for_bit():
+    """lif_step (cache update and activations in one launch) and the four separate calls give identical
+    bytes everywhere: y, masks, pointers, bias, cache rows (the loaders sum in the activation kernel's order)."""
+    from tests.harness import GpuLayer
+    for name, tokens in (("C2", 40), ("C4", 16)):
+        w = wl.WORKLOADS[name]
+        L = wl.cached_layer(name)
+        X = wl.make_inputs(w, tokens=tokens)
+        res = []
+        for api in ("calls", "step"):
+            gpu = GpuLayer(w, L)
+            lay = gpu.layer
+            xd = gpu.upload_x(X)
+            y = torch.zeros_like(xd)
+            for t in range(tokens):
+                (lay.step if api == "step" else lay.step_calls)(xd[t], y[t])
+            n = lay.state()["num_used"]
+            res.append((y.cpu().numpy().astype(np.float64), lay.pointers[:n].cpu().numpy().tobytes(),
+                        lay.bias[:n].cpu().numpy().tobytes(), lay.matrix[:n].cpu().numpy().tobytes(),
+                        lay.masks.cpu().numpy().tobytes(), lay.counters()))
+        for a, b in zip(res[0][1:5], res[1][1:5]):
+            assert a == b, name
+        assert res[0][0].tobytes() == res[1][0].tobytes(), name
+        ca, cb = res[0][5], res[1][5]
+        assert ca["h2d_bytes"] == cb["h2d_bytes"] and ca["rows_moved"] == cb["rows_moved"]
