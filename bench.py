@@ -52,6 +52,32 @@ def cpu_baseline(w, L, X, budget_s=20.0):
                       f"(predict, window, delete, insert, FFN)"}
 
 
+def pmc_traffic(pmc_dir):
+    """HBM-side bytes per lif_sparse_ffn call from two rocprofv3 --pmc runs of this script (FETCH_SIZE, WRITE_SIZE),
+    each scaled by what the same counter reported for the 256 MiB device copy of --pmc-copy.  Expects
+    <pmc_dir>/pmc_FETCH_SIZE/*_counter_collection.csv and <pmc_dir>/pmc_WRITE_SIZE/*_counter_collection.csv."""
+    import csv
+    import glob
+    out = {}
+    for counter in ("FETCH_SIZE", "WRITE_SIZE"):
+        files = glob.glob(os.path.join(pmc_dir, f"pmc_{counter}", "*counter_collection.csv"))
+        if not files:
+            return None
+        rows = [r for r in csv.DictReader(open(files[0])) if r["Counter_Name"] == counter]
+        copies = [float(r["Counter_Value"]) for r in rows if "copyBuffer" in r["Kernel_Name"]]
+        if not copies or max(copies) <= 0:
+            return None
+        scale = 262144.0 / max(copies)                       # reported KiB -> true KiB (the copy moves 256 MiB each way)
+        up = [(int(r["Dispatch_Id"]), float(r["Counter_Value"])) for r in rows if "k_ffn_up" in r["Kernel_Name"]]
+        if not up:
+            return None
+        lo, hi = min(i for i, _ in up), max(i for i, _ in up)  # the FFN-only phase (lif_step never launches k_ffn_up alone)
+        ffn = [float(r["Counter_Value"]) for r in rows
+               if lo <= int(r["Dispatch_Id"]) <= hi and "k_ffn_" in r["Kernel_Name"]]
+        out[counter] = {"scale": scale, "bytes_per_call": sum(ffn) * scale * 1024.0 / len(up)}
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -63,6 +89,10 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="launch every kernel from the host instead of a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true")
+    ap.add_argument("--pmc-copy", action="store_true",
+                    help="also run a plain 256 MiB device copy three times (calibration of rocprofv3 FETCH_SIZE / WRITE_SIZE)")
+    ap.add_argument("--pmc-dir", default=None,
+                    help="directory with the rocprofv3 --pmc outputs of this script; fills roofline.traffic")
     ap.add_argument("--no-hint", action="store_true", help="do not give the library the expected number of cached rows")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -74,6 +104,14 @@ def main():
     import workloads as wl
     import paper_2312_11514_amd as lif
     from tests.harness import GpuLayer
+
+    if args.pmc_copy:
+        src = torch.ones(128 * 1024 * 1024, dtype=torch.float16, device="cuda:0")      # 256 MiB read + 256 MiB written
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     w = wl.WORKLOADS[args.workload]
     NL = w.layers
@@ -178,11 +216,18 @@ def main():
     if not args.no_profile:
         R = 200 if NL == 1 else 8
         x_last = xd[T - 1]
-        g2 = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(g2):
+        def ffn_rounds():
             for _ in range(R):
                 for l, lay in enumerate(layers):
                     lay.sparse_ffn(x_last, yd[l, T - 1], w.batch)
+        if args.no_graph:
+            class _Eager:
+                replay = staticmethod(ffn_rounds)
+            g2 = _Eager()
+        else:
+            g2 = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g2):
+                ffn_rounds()
         g2.replay()
         torch.cuda.synchronize()
         c0 = [lay.counters() for lay in layers]
@@ -247,6 +292,11 @@ def main():
                            "nominal_bundle_bytes": nominal_f,
                            "nominal_GBs": nominal_f / (ffn["us"] * 1e-6) / 1e9,
                            "nominal_frac": nominal_f / (ffn["us"] * 1e-6) / 1e9 / HBM_PEAK_GBS}
+    if ffn and args.pmc_dir:
+        tr = pmc_traffic(args.pmc_dir)
+        if tr:
+            out["roofline"]["traffic"] = tr["FETCH_SIZE"]["bytes_per_call"] + tr["WRITE_SIZE"]["bytes_per_call"]
+            out["roofline"]["traffic_detail"] = tr
     if kern:
         out["h2d"] = {"GBs_in_load_kernel": added_per_call * w.bundle_bytes / (kern["load"]["avg_us"] * 1e-6) / 1e9}
         out["kernels_avg_us_event_timed"] = {k: round(v["avg_us"], 3) for k, v in kern.items()}

@@ -186,7 +186,7 @@ void launch_ffn_down(lif_layer* L, int batch, void* y, hipStream_t s, bool use_n
     const int32_t* stamp = use_new ? L->stamp : nullptr;
     const lif_config& c = L->cfg;
     const int cols = kDownLanes * Vec<T>::N;
-    const int grid = (c.d_model + cols - 1) / cols;
+    const int grid = ((c.d_model + cols - 1) / cols + kXcds - 1) / kXcds * kXcds;   // whole runs of slices per XCD
     const int colsb = kDownBLanes * Vec<T>::N;
     const int gridb = (c.d_model + colsb - 1) / colsb;
     const int down_off = (c.glu ? 2 : 1) * c.d_model;

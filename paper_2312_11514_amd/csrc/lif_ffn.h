@@ -131,6 +131,7 @@ __global__ __launch_bounds__(256) void k_ffn_up(const T* __restrict__ matrix, co
                                   &st->num_used, st);
 }
 
+constexpr int kXcds = 8;            // accelerator complex dies of an MI355X, each with a private L2
 constexpr int kDownLanes = 4;       // lanes per column slice (4 x 16 B = 64 B of every down column)
 constexpr int kDownRg = 64;         // row groups per workgroup
 constexpr int kDownTile = 2048;     // cached rows compacted per pass
@@ -155,7 +156,12 @@ __global__ __launch_bounds__(256) void k_ffn_down(const T* __restrict__ matrix, 
     __shared__ int n_active;
 
     const int tid = threadIdx.x, l = tid & (kDownLanes - 1), rg = tid >> 2;
-    const int col = blockIdx.x * (kDownLanes * VE) + l * VE;
+    // XCD-aware slice order: workgroups are dealt round-robin to the 8 XCDs, each with its own L2.
+    // A slice is 64 bytes wide, an L2 line 128: giving every XCD a contiguous run of slices makes
+    // the two halves of a line meet in one L2 instead of being fetched by two.
+    const int per_xcd = gridDim.x / kXcds;                   // the host rounds the grid up to a multiple of 8
+    const int slice = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
+    const int col = slice * (kDownLanes * VE) + l * VE;
     const bool col_ok = col < d;
     const T* base = matrix + down_off + col;
 
@@ -220,7 +226,7 @@ __global__ __launch_bounds__(256) void k_ffn_down(const T* __restrict__ matrix, 
             if (!SKIP) any = s < n;
             if (any) flags |= 1u << q;
         }
-        if (blockIdx.x == 0 && nonzero) atomicAdd(&n_active, __popc(nonzero));   // statistics only
+        if (slice == 0 && nonzero) atomicAdd(&n_active, __popc(nonzero));   // statistics only
         int cnt;
         int off = block_exclusive_scan(__popc(flags), wave_tot, &cnt);
 #pragma unroll
@@ -261,14 +267,14 @@ __global__ __launch_bounds__(256) void k_ffn_down(const T* __restrict__ matrix, 
             if ((tid & 63) < kDownLanes) red[tid >> 6][l][b][e] = v;
         }
     __syncthreads();
-    if (blockIdx.x == 0 && tid == 0) {
+    if (slice == 0 && tid == 0) {
         st->c_ffn_calls += 1;
         st->c_ffn_rows += (unsigned long long)n;
         st->c_ffn_active += (unsigned long long)n_active;
     }
     if (tid < kDownLanes * BT) {
         const int b = tid / kDownLanes, l2 = tid - b * kDownLanes;
-        const int col2 = blockIdx.x * (kDownLanes * VE) + l2 * VE;
+        const int col2 = slice * (kDownLanes * VE) + l2 * VE;
         if (col2 < d && b < batch) {
             V out;
 #pragma unroll
