@@ -6,7 +6,7 @@ sparse_ffn for every token and every layer) over the workload's token stream, st
 empty neuron caches.  Inputs, weights and the pinned bundle store are resident before the
 timed region starts.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C2|C3|C4|C4b8|C5] [--ffn-mode skip|full]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C2|C3|C4|C4b8|C5|N1] [--ffn-mode skip|full]
 """
 from __future__ import annotations
 
@@ -38,7 +38,7 @@ def cpu_baseline(w, L, X, budget_s=20.0):
     except Exception:
         cores = os.cpu_count() or 1
     ora = O.OracleLayer(w.d_model, w.d_ffn, w.window_k, w.capacity_rows, w.glu, L.A, L.B, L.c, L.theta,
-                        L.b, L.bundles)
+                        L.b, L.bundles, shrink=w.shrink)
     t0 = time.perf_counter()
     done = 0
     for t in range(len(X)):
@@ -179,6 +179,7 @@ def main():
 
     sts = [lay.state() for lay in layers]
     assert all(s["error"] == 0 for s in sts), sts
+    window_len_end = sts[0]["window_len"]
     cnts = [lay.counters() for lay in layers]
     tot = {k: sum(c[k] for c in cnts) for k in cnts[0]}
     rows_per_call = tot["ffn_rows"] / tot["ffn_calls"]
@@ -276,6 +277,7 @@ def main():
         "per_token_per_layer": {"rows_in_cache": rows_per_call, "rows_active": active_per_call,
                                 "rows_added": added_per_call, "h2d_bytes": added_per_call * w.bundle_bytes,
                                 "nominal_bundle_bytes": nominal},
+        "window_len_at_end": window_len_end,
         "end_to_end_us_per_token": us_per_token_layer * NL,
         "h2d_bytes_per_token": added_per_call * w.bundle_bytes * NL,
     }

@@ -65,6 +65,9 @@ typedef struct lif_config {
     int32_t glu;            /* 0: bundle = up|down, 1: bundle = gate|up|down               */
     int32_t dtype;          /* enum lif_dtype: type of x, y, A, B and the bundles          */
     int32_t ffn_mode;       /* enum lif_ffn_mode                                           */
+    int32_t shrink_window;  /* 1: dynamic window (Appendix, Persimmon / Phi-2): when the active  */
+                            /* set would exceed capacity_rows the oldest masks leave the window  */
+                            /* until it fits; 0: such a step is a LIF_CAPACITY error             */
     float threshold;        /* theta: neuron i is predicted active iff logit_i > theta     */
 } lif_config;
 
@@ -95,6 +98,7 @@ typedef struct lif_state {
     int32_t last_added;     /* |added| of the last lif_update_window                      */
     int32_t last_removed;   /* |removed| of the last lif_update_window                    */
     int32_t last_moved;     /* rows moved by the last deletion                            */
+    int32_t window_len;     /* step masks in the window after the last update (<= window_k) */
 } lif_state;
 
 typedef struct lif_counters {
@@ -162,8 +166,11 @@ int lif_predict(lif_layer* layer, const void* x_dev, int32_t batch,
  *   removed_dev  [d_ffn] int32, device, written: S_{t-1} \ S_t, ascending neuron id
  *   n_added_dev, n_removed_dev  [1] int32, device, written: the two counts
  * Records the mask in the window state and advances the step counter.  If |S_t| would exceed
- * capacity_rows nothing is changed, both counts are written as 0 and the sticky
- * error flag is set to LIF_CAPACITY.
+ * capacity_rows: with shrink_window = 0 nothing is changed, both counts are written as 0 and
+ * the sticky error flag is set to LIF_CAPACITY; with shrink_window = 1 the oldest masks are
+ * dropped from the window for good, one by one, until the union fits (S_t = union of the
+ * newest window_len masks, window_len maximal), and only a step mask that does not fit on
+ * its own is a LIF_CAPACITY error.
  * Must alternate with lif_load_bundles (LIF_BAD_STATE otherwise): the cache has to
  * hold S_{t-1} when the window moves.
  */

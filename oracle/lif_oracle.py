@@ -31,7 +31,10 @@ Readings of the paper taken here (the paper is silent or ambiguous):
   * the FFN sums over every cached row (the window union), not only over the
     current token's mask;
   * a batch of tokens shares one cache: its step mask is the OR of the
-    per-token masks and the window counts steps.
+    per-token masks and the window counts steps;
+  * dynamic window (optional): "reduces window size dynamically whenever the
+    memory usage passes the limit" is read as dropping the oldest masks, for
+    good, until the union of the remaining ones fits the cache.
 Pins: tests/test_oracle_*.py.  Nothing here is "parity unpinned".
 """
 from __future__ import annotations
@@ -90,20 +93,35 @@ class SlidingWindow:
             s |= m
         return s
 
-    def push(self, mask, capacity=None):
+    def push(self, mask, capacity=None, shrink=False):
         """Slide by one step.  Returns (added ids, removed ids), ascending int32.
 
-        If the new active set would exceed `capacity` rows the window is left
-        unchanged and OverflowError is raised.
+        If the new active set would exceed `capacity` rows: with shrink=False the window is left
+        unchanged and OverflowError is raised; with shrink=True (dynamic window, Appendix:
+        Persimmon and Phi-2 reduce the window whenever the memory limit would be passed) the
+        oldest masks leave the window for good, one at a time, until the union fits; only a
+        mask that does not fit alone raises.
         """
         before = self.active_set()
         kept = self.masks[-(self.k - 1):] if self.k > 1 else []
-        after = np.array(mask, dtype=bool, copy=True)
-        for m in kept:
-            after = after | m
+        new_masks = kept + [np.array(mask, dtype=bool, copy=True)]
+
+        def union(ms):
+            u = np.zeros(self.F, dtype=bool)
+            for m in ms:
+                u |= m
+            return u
+
+        after = union(new_masks)
         if capacity is not None and int(after.sum()) > capacity:
-            raise OverflowError("active set exceeds the neuron cache capacity")
-        self.masks = kept + [np.array(mask, dtype=bool, copy=True)]
+            if not shrink:
+                raise OverflowError("active set exceeds the neuron cache capacity")
+            while len(new_masks) > 1 and int(union(new_masks).sum()) > capacity:
+                new_masks.pop(0)
+            after = union(new_masks)
+            if int(after.sum()) > capacity:
+                raise OverflowError("the step mask alone exceeds the neuron cache capacity")
+        self.masks = new_masks
         added = np.flatnonzero(after & ~before).astype(np.int32)
         removed = np.flatnonzero(before & ~after).astype(np.int32)
         return added, removed
@@ -234,7 +252,8 @@ class OracleLayer:
     """One FFN layer driven token by token: predict -> window -> delete -> insert -> FFN."""
 
     def __init__(self, d_model, d_ffn, window_k, capacity_rows, glu, A, B, c, theta, b,
-                 host_bundles):
+                 host_bundles, shrink=False):
+        self.shrink = shrink
         self.d, self.F, self.k, self.glu = d_model, d_ffn, window_k, glu
         self.A, self.B, self.c, self.theta, self.b = A, B, c, theta, b
         self.host = host_bundles
@@ -250,7 +269,7 @@ class OracleLayer:
         return mask
 
     def update_window(self, mask):
-        return self.window.push(step_mask(mask), self.cache.capacity)
+        return self.window.push(step_mask(mask), self.cache.capacity, self.shrink)
 
     def load_bundles(self, added, removed):
         self.rows_moved += delete_neurons(self.cache, removed)

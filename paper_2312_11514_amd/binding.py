@@ -20,7 +20,8 @@ STATUS_NAMES = {0: "OK", 1: "INVALID_ARG", 2: "BAD_STATE", 3: "CAPACITY", 4: "HI
 
 class LifConfig(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("d_model", "d_ffn", "rank", "window_k", "capacity_rows",
-                                         "max_batch", "glu", "dtype", "ffn_mode")] + [("threshold", C.c_float)]
+                                         "max_batch", "glu", "dtype", "ffn_mode", "shrink_window")] + \
+        [("threshold", C.c_float)]
 
 
 class LifBuffers(C.Structure):
@@ -31,7 +32,8 @@ class LifBuffers(C.Structure):
 
 
 class LifState(C.Structure):
-    _fields_ = [(n, C.c_int32) for n in ("num_used", "step", "error", "last_added", "last_removed", "last_moved")]
+    _fields_ = [(n, C.c_int32) for n in ("num_used", "step", "error", "last_added", "last_removed", "last_moved",
+                                         "window_len")]
 
 
 class LifCounters(C.Structure):
@@ -105,12 +107,12 @@ class Layer:
     """
 
     def __init__(self, *, d_model, d_ffn, rank, window_k, capacity_rows, max_batch=1, glu=False,
-                 dtype="f16", ffn_mode=FFN_SKIP_DEAD, threshold=0.0, A, B, c, b, host_bundles):
+                 dtype="f16", ffn_mode=FFN_SKIP_DEAD, shrink_window=False, threshold=0.0, A, B, c, b, host_bundles):
         import torch
         self.lib = load_library()
         self.torch = torch
         self.cfg = LifConfig(d_model, d_ffn, rank, window_k, capacity_rows, max_batch, int(glu),
-                             LIF_F32 if dtype == "f32" else LIF_F16, ffn_mode, threshold)
+                             LIF_F32 if dtype == "f32" else LIF_F16, ffn_mode, int(shrink_window), threshold)
         self.tdtype = torch.float32 if dtype == "f32" else torch.float16
         dev = A.device
         G = 3 if glu else 2

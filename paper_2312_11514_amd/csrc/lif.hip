@@ -57,6 +57,7 @@ bool config_ok(const lif_config* c, const char** why) {
     if (c->capacity_rows < 1 || c->capacity_rows > kScanThreads * kMaxSpan) return (*why = "capacity_rows must be in 1..65536", false);
     if (c->max_batch < 1 || c->max_batch > 8) return (*why = "max_batch must be in 1..8", false);
     if (c->glu != 0 && c->glu != 1) return (*why = "glu", false);
+    if (c->shrink_window != 0 && c->shrink_window != 1) return (*why = "shrink_window", false);
     if (c->ffn_mode != LIF_FFN_SKIP_DEAD && c->ffn_mode != LIF_FFN_FULL_BUNDLE) return (*why = "ffn_mode", false);
     if ((size_t)c->max_batch * c->d_model * elem_bytes(*c) > 64 * 1024) return (*why = "max_batch * d_model exceeds the 64 KiB LDS staging area", false);
     return true;
@@ -340,7 +341,8 @@ int lif_update_window(lif_layer* L, const uint8_t* step_mask_dev, int32_t* added
     {
         Timed t(L, LIF_K_WINDOW, s);
         hipLaunchKernelGGL(k_window_plan, dim3(1), dim3(kScanThreads), 0, s, step_mask_dev, L->ring, ring_words(c),
-                           L->buf.pointers, c.d_ffn, c.window_k, c.capacity_rows, added_dev, n_added_dev, removed_dev,
+                           L->buf.pointers, c.d_ffn, c.window_k, c.capacity_rows, c.shrink_window, added_dev, n_added_dev,
+                           removed_dev,
                            n_removed_dev, L->move_dst, L->hole_list, L->st);
     }
     L->window_pending = true;
@@ -460,6 +462,7 @@ int lif_get_state(lif_layer* L, lif_state* out, void* stream) {
     out->last_added = h.n_added;
     out->last_removed = h.n_removed;
     out->last_moved = h.n_moved;
+    out->window_len = h.window_len;
     return LIF_OK;
 }
 

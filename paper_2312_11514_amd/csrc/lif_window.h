@@ -76,7 +76,7 @@ __device__ __forceinline__ void block_exclusive_scan2(int va, int vb, unsigned l
 // are issued together with the state itself.
 __global__ __launch_bounds__(kScanThreads) void k_window_plan(
     const uint8_t* __restrict__ step_mask, unsigned long long* __restrict__ ring, int ring_words,
-    const int32_t* __restrict__ pointers, int F, int k, int capacity, int32_t* __restrict__ added,
+    const int32_t* __restrict__ pointers, int F, int k, int capacity, int shrink, int32_t* __restrict__ added,
     int32_t* __restrict__ n_added, int32_t* __restrict__ removed, int32_t* __restrict__ n_removed,
     int32_t* __restrict__ move_dst, int32_t* __restrict__ hole_list, DevState* st) {
     constexpr int NW = kScanThreads / kWave;
@@ -84,6 +84,7 @@ __global__ __launch_bounds__(kScanThreads) void k_window_plan(
     __shared__ unsigned long long rem64[kScanThreads];
     __shared__ int hole_lds[kHoleLds];
     __shared__ int blk_h[kScanThreads], blk_f[kScanThreads];      // per 64-slot block: counts, then exclusive prefixes
+    __shared__ int cnt_age[256];                                  // dynamic window: |union of the newest a masks|
     const int tid = threadIdx.x, lane = tid & (kWave - 1), w = tid >> 6;
     const unsigned long long lt = (1ull << lane) - 1ull;
     const int nwords = (F + 63) >> 6, nbytes = F >> 3;
@@ -98,6 +99,7 @@ __global__ __launch_bounds__(kScanThreads) void k_window_plan(
     const int err = st->error;
     const int t = st->step;
     const int n = st->num_used;
+    const int wl_prev = st->window_len;
 
     if (err) {
         if (tid == 0) {
@@ -124,8 +126,40 @@ __global__ __launch_bounds__(kScanThreads) void k_window_plan(
             if (j != slot) keep |= v;
         }
     }
-    unsigned long long abits = m & ~prev;
-    unsigned long long rbits = prev & ~(keep | m);
+    unsigned long long now = keep | m;                   // S_t with the full window
+    int k_eff = k;
+    if (shrink) {
+        // Dynamic window (Appendix, Persimmon / Phi-2: the window is reduced whenever the cache would
+        // pass its memory limit): keep the newest k_eff <= k masks, k_eff the largest count whose
+        // union fits the capacity.  U_a = union of the newest a masks (a = 1: this step's mask).
+        for (int a = tid; a < k; a += kScanThreads) cnt_age[a] = 0;
+        __syncthreads();
+        unsigned long long u = m;
+        for (int a = 1; a <= k; ++a) {
+            if (a > 1 && have) u |= ring[(size_t)((slot - (a - 1) + k) % k) * ring_words + tid];
+            const int pc = __popcll(u);
+            if (pc) atomicAdd(&cnt_age[a - 1], pc);
+        }
+        __syncthreads();
+        k_eff = 0;
+        for (int a = 1; a <= k; ++a)
+            if (cnt_age[a - 1] <= capacity) k_eff = a;       // the counts grow with a
+        if (k_eff == 0) {                                    // uniform: this step's mask alone does not fit
+            if (tid == 0) {
+                st->error = 3;                               // LIF_CAPACITY
+                *n_added = 0;
+                *n_removed = 0;
+                st->n_added = 0;
+                st->n_removed = 0;
+            }
+            return;
+        }
+        now = m;
+        if (have)
+            for (int a = 2; a <= k_eff; ++a) now |= ring[(size_t)((slot - (a - 1) + k) % k) * ring_words + tid];
+    }
+    unsigned long long abits = now & ~prev;
+    unsigned long long rbits = prev & ~now;
     int off_a, off_r, tot_a, tot_r;
     block_exclusive_scan2(__popcll(abits), __popcll(rbits), wave_tot, &off_a, &off_r, &tot_a, &tot_r);
 
@@ -141,7 +175,11 @@ __global__ __launch_bounds__(kScanThreads) void k_window_plan(
         return;
     }
     rem64[tid] = rbits;
-    if (have) ring[(size_t)slot * ring_words + tid] = m;
+    if (have) {
+        ring[(size_t)slot * ring_words + tid] = m;
+        for (int a = k_eff + 1; a <= k; ++a)                 // masks dropped by the dynamic window leave it for good
+            ring[(size_t)((slot - (a - 1) + k) % k) * ring_words + tid] = 0ull;
+    }
     while (abits) {
         added[off_a++] = tid * 64 + __ffsll((long long)abits) - 1;
         abits &= abits - 1;
@@ -213,6 +251,7 @@ __global__ __launch_bounds__(kScanThreads) void k_window_plan(
         st->n_removed = tot_r;
         st->n_base = n2;
         st->n_moved = H;
+        st->window_len = min(min(wl_prev + 1, k), k_eff);
         st->step = t + 1;
         st->c_steps += 1;
         st->c_added += (unsigned long long)tot_a;

@@ -17,7 +17,7 @@ def require_gpu():
 
 
 class GpuLayer:
-    def __init__(self, w, L, ffn_mode=lif.FFN_SKIP_DEAD, capacity=None, max_batch=None, use_c=True):
+    def __init__(self, w, L, ffn_mode=lif.FFN_SKIP_DEAD, capacity=None, max_batch=None, use_c=True, shrink=False):
         require_gpu()
         dev = torch.device("cuda:0")
         self.w, self.dev = w, dev
@@ -27,7 +27,7 @@ class GpuLayer:
         self.layer = lif.Layer(
             d_model=w.d_model, d_ffn=w.d_ffn, rank=w.rank, window_k=w.window_k,
             capacity_rows=capacity or w.capacity_rows, max_batch=max_batch or w.batch, glu=w.glu,
-            dtype=w.dtype, ffn_mode=ffn_mode, threshold=L.theta,
+            dtype=w.dtype, ffn_mode=ffn_mode, shrink_window=(shrink or w.shrink), threshold=L.theta,
             A=up(L.A), B=up(L.B), c=up(L.c) if use_c else None, b=up(L.b), host_bundles=self.host)
         self.y = torch.zeros((max_batch or w.batch, w.d_model), dtype=self.tdtype, device=dev)
 

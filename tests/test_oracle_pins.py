@@ -387,3 +387,48 @@ def test_bytes_and_occupancy_monotone_in_window_size():
     for o in out:
         union |= set(np.flatnonzero(o["masks"]).tolist())
     assert lay.bytes_loaded == len(union) * w.bundle_bytes
+
+
+# ----------------------------------------------------------------------------- dynamic window
+def test_dynamic_window_hand_worked():
+    g = golden("window_shrink.json")
+    win = O.SlidingWindow(g["d_ffn"], g["k"])
+    for t, ids in enumerate(g["masks"]):
+        m = np.zeros(g["d_ffn"], bool)
+        m[ids] = True
+        if g["active"][t] is None:
+            before = list(np.flatnonzero(win.active_set()))
+            with pytest.raises(OverflowError):
+                win.push(m, capacity=g["capacity"], shrink=True)
+            assert list(np.flatnonzero(win.active_set())) == before
+            continue
+        added, removed = win.push(m, capacity=g["capacity"], shrink=True)
+        assert list(added) == g["added"][t] and list(removed) == g["removed"][t]
+        assert list(np.flatnonzero(win.active_set())) == g["active"][t]
+        assert len(win.masks) == g["window_len"][t]
+
+
+def test_dynamic_window_is_the_largest_suffix_that_fits():
+    """Against set arithmetic: after each step the window is the longest suffix of (previous window + new
+    mask, at most k long) whose union fits; the active set never exceeds the capacity; with a capacity
+    that is never reached the dynamic window equals the fixed one."""
+    rng = np.random.default_rng(11)
+    F, T, k, cap = 128, 60, 5, 30
+    sets = [set(np.flatnonzero(rng.random(F) < rng.choice([0.03, 0.08, 0.15])).tolist()) for _ in range(T)]
+    win, ref_win, fixed = O.SlidingWindow(F, k), [], O.SlidingWindow(F, k)
+    for t, s in enumerate(sets):
+        m = np.zeros(F, bool)
+        m[list(s)] = True
+        ref_win = (ref_win + [s])[-k:]
+        while len(ref_win) > 1 and len(set().union(*ref_win)) > cap:
+            ref_win = ref_win[1:]
+        if len(set().union(*ref_win)) > cap:
+            pytest.skip("mask alone above capacity: not the case under test")
+        prev = set(np.flatnonzero(win.active_set()).tolist())
+        added, removed = win.push(m, capacity=cap, shrink=True)
+        cur = set().union(*ref_win)
+        assert set(np.flatnonzero(win.active_set()).tolist()) == cur and len(cur) <= cap
+        assert len(win.masks) == len(ref_win)
+        assert list(added) == sorted(cur - prev) and list(removed) == sorted(prev - cur)
+        a2, r2 = fixed.push(m, capacity=F, shrink=True)       # never shrinks
+        assert len(fixed.masks) == min(k, t + 1)

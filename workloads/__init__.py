@@ -38,6 +38,7 @@ class Workload:
     batch: int
     capacity_rows: int   # rows preallocated in the HBM neuron cache
     layers: int = 1
+    shrink: bool = False # dynamic window: drop the oldest masks instead of overflowing
 
     @property
     def np_dtype(self):
@@ -72,6 +73,9 @@ WORKLOADS = {
     "C4b8": Workload("C4b8", 4096, 11008, 256, 4, 0.10, 0.9, "f16", True, 256, 8, 11008),
     # 32 stacked OPT-6.7B-shaped layers, cache capped at half the FFN rows
     "C5": Workload("C5", 4096, 16384, 128, 5, 0.03, 0.9, "f16", False, 512, 1, 8192, layers=32),
+    # dynamic-window case: OPT shape at 10 % activity, k = 8, cache capped at 25 % of the FFN rows
+    # (the appendix's Persimmon setting: window reduced whenever the cache would pass 25 % of the FFN)
+    "N1": Workload("N1", 4096, 16384, 128, 8, 0.10, 0.9, "f16", False, 256, 1, 4096, shrink=True),
 }
 
 
