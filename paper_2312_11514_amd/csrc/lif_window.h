@@ -134,11 +134,40 @@ __global__ __launch_bounds__(kScanThreads) void k_window_plan(
         // union fits the capacity.  U_a = union of the newest a masks (a = 1: this step's mask).
         for (int a = tid; a < k; a += kScanThreads) cnt_age[a] = 0;
         __syncthreads();
-        unsigned long long u = m;
-        for (int a = 1; a <= k; ++a) {
-            if (a > 1 && have) u |= ring[(size_t)((slot - (a - 1) + k) % k) * ring_words + tid];
-            const int pc = __popcll(u);
-            if (pc) atomicAdd(&cnt_age[a - 1], pc);
+        if (k <= kRingRegs) {
+            // all ring words are in registers: age of ring entry j is (slot - j) mod k (uniform), the entry
+            // at `slot` itself is the one being overwritten.  Per-wave sums (two 16-bit counts per
+            // shuffled word), then one LDS atomic per wave and age.
+            unsigned pk[kRingRegs / 2];
+#pragma unroll
+            for (int i = 0; i < kRingRegs / 2; ++i) pk[i] = 0u;
+#pragma unroll
+            for (int a = 1; a <= kRingRegs; ++a) {
+                unsigned long long u = m;
+#pragma unroll
+                for (int j = 0; j < kRingRegs; ++j) {
+                    const int age = (slot - j + k) % k;          // 0 for j == slot
+                    if (j < k && j != slot && age < a) u |= rv[j];
+                }
+                if (a <= k) pk[(a - 1) >> 1] |= (unsigned)__popcll(u) << (((a - 1) & 1) * 16);
+            }
+#pragma unroll
+            for (int i = 0; i < kRingRegs / 2; ++i) {
+                unsigned v = pk[i];
+#pragma unroll
+                for (int msk = 32; msk >= 1; msk >>= 1) v += __shfl_xor(v, msk, kWave);   // 64 lanes x 64 bits < 2^16
+                if (lane == 0) {
+                    if (2 * i < k) atomicAdd(&cnt_age[2 * i], (int)(v & 0xffffu));
+                    if (2 * i + 1 < k) atomicAdd(&cnt_age[2 * i + 1], (int)(v >> 16));
+                }
+            }
+        } else {
+            unsigned long long u = m;
+            for (int a = 1; a <= k; ++a) {
+                if (a > 1 && have) u |= ring[(size_t)((slot - (a - 1) + k) % k) * ring_words + tid];
+                const int pc = __popcll(u);
+                if (pc) atomicAdd(&cnt_age[a - 1], pc);
+            }
         }
         __syncthreads();
         k_eff = 0;
@@ -155,8 +184,15 @@ __global__ __launch_bounds__(kScanThreads) void k_window_plan(
             return;
         }
         now = m;
-        if (have)
+        if (k <= kRingRegs) {
+#pragma unroll
+            for (int j = 0; j < kRingRegs; ++j) {
+                const int age = (slot - j + k) % k;
+                if (j < k && j != slot && age < k_eff) now |= rv[j];
+            }
+        } else if (have) {
             for (int a = 2; a <= k_eff; ++a) now |= ring[(size_t)((slot - (a - 1) + k) % k) * ring_words + tid];
+        }
     }
     unsigned long long abits = now & ~prev;
     unsigned long long rbits = prev & ~now;
