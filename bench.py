@@ -78,6 +78,93 @@ def pmc_traffic(pmc_dir):
     return out
 
 
+def sweep_window(args):
+    """Memory-latency trade-off over the window size k (the synthetic analogue of the paper's Fig. 4a / Fig. 7):
+    larger windows hold more rows in the cache and load fewer bytes per token."""
+    import torch
+    import workloads as wl
+    from tests.harness import GpuLayer
+    base_w = wl.WORKLOADS[args.workload]
+    L = wl.make_layer(base_w)
+    X = wl.make_inputs(base_w)
+    T = len(X)
+    rows = []
+    for k in (1, 2, 3, 4, 5, 6, 8, 12, 16):
+        w = wl.scaled(base_w, window_k=k, capacity_rows=base_w.d_ffn)
+        gpu = GpuLayer(w, L)
+        lay = gpu.layer
+        xd = gpu.upload_x(X)
+        yd = torch.zeros_like(xd)
+
+        def run():
+            lay.reset()
+            for t in range(T):
+                lay.step(xd[t], yd[t])
+        run()
+        torch.cuda.synchronize()
+        cnt = lay.counters()
+        lay.set_expected_rows(int(0.9 * cnt["ffn_rows"] / cnt["ffn_calls"]))
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            run()
+        for _ in range(2):
+            g.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(5):
+            g.replay()
+        torch.cuda.synchronize()
+        us = (time.perf_counter() - t0) / 5 / T * 1e6
+        rows.append({"k": k, "rows_in_cache": cnt["ffn_rows"] / cnt["ffn_calls"],
+                     "cache_fraction_of_ffn": cnt["ffn_rows"] / cnt["ffn_calls"] / w.d_ffn,
+                     "rows_added_per_token": cnt["added"] / cnt["steps"],
+                     "h2d_bytes_per_token": cnt["added"] / cnt["steps"] * w.bundle_bytes,
+                     "us_per_token": us})
+        lay.close()
+        del gpu, lay
+    print(json.dumps({"sweep": "window size k", "workload": describe(base_w), "rows": rows}))
+
+
+def sweep_chunk(args):
+    """Host-to-device throughput of the bundle gather against the chunk size (the analogue of the paper's
+    Fig. 2b and of Table 1's bundling row: one read of 2*d*E bytes per neuron instead of two reads of d*E).
+    Same bytes per step (about 2.4 MB of new bundles) at every chunk size; masks are forced through the
+    predictor offset so that exactly `rows` new neurons appear per step."""
+    import numpy as np
+    import torch
+    import paper_2312_11514_amd as lif
+    dev = torch.device("cuda:0")
+    F, r = 16384, 32
+    rng = np.random.default_rng(0)
+    out = []
+    for d in (256, 512, 1024, 2048, 4096, 8192):
+        bundle = 2 * d * 2
+        rows = max(1, int(round(2.4e6 / bundle)))
+        host = torch.from_numpy(rng.standard_normal((F, 2 * d), dtype=np.float32).astype(np.float16)).pin_memory()
+        A = torch.zeros((d, r), dtype=torch.float16, device=dev)
+        B = torch.zeros((r, F), dtype=torch.float16, device=dev)
+        c = torch.zeros(F, device=dev)
+        b = torch.zeros(F, device=dev)
+        x = torch.zeros(d, dtype=torch.float16, device=dev)
+        y = torch.zeros(d, dtype=torch.float16, device=dev)
+        lay = lif.Layer(d_model=d, d_ffn=F, rank=r, window_k=1, capacity_rows=F, dtype="f16", A=A, B=B, c=c, b=b,
+                        host_bundles=host)
+        ts = []
+        for it in range(14):
+            m = np.full(F, -1.0, np.float32)
+            m[rng.choice(F, rows, replace=False)] = 1.0
+            c.copy_(torch.from_numpy(m))
+            torch.cuda.synchronize()
+            lay.profile_begin(16)
+            lay.step(x, y)
+            ts.append(lay.profile_collect()["load"][0] * 1e3)
+        t = float(np.median(ts[4:]))
+        out.append({"d_model": d, "chunk_bytes": bundle, "unbundled_chunk_bytes": bundle // 2, "rows_per_step": rows,
+                    "load_kernel_us_event_timed": t, "GBs": rows * bundle / t / 1e3})
+        lay.close()
+    print(json.dumps({"sweep": "chunk size (bundle bytes) at ~2.4 MB per step", "rows": out}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -94,11 +181,18 @@ def main():
     ap.add_argument("--pmc-dir", default=None,
                     help="directory with the rocprofv3 --pmc outputs of this script; fills roofline.traffic")
     ap.add_argument("--no-hint", action="store_true", help="do not give the library the expected number of cached rows")
+    ap.add_argument("--sweep", default=None, choices=["k", "chunk"],
+                    help="instead of the bench line: window-size sweep or chunk-size sweep (one JSON line each)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
               file=sys.stderr)
         sys.exit(2)
+
+    if args.sweep == "k":
+        return sweep_window(args)
+    if args.sweep == "chunk":
+        return sweep_chunk(args)
 
     import torch
     import workloads as wl

@@ -218,11 +218,12 @@ void launch_load_up(lif_layer* L, const void* x, const int32_t* added, hipStream
     const int spec = L->expected_rows > 0 ? 1 : 0;
     const int up_blocks = spec ? std::max(1, std::min(L->expected_rows, c.capacity_rows) / 4)
                                : std::min((c.capacity_rows + 3) / 4, 512);
+    const int load_wgs = (int)std::min<size_t>(64, std::max<size_t>(10, kStepInflightBytes / L->row_bytes));
 #define LIF_LU(NI)                                                                                            \
-    hipLaunchKernelGGL((k_load_up<T, NI, GLU>), dim3(kStepLoadWgs + up_blocks), dim3(256), 0, s,                  \
+    hipLaunchKernelGGL((k_load_up<T, NI, GLU>), dim3(load_wgs + up_blocks), dim3(256), 0, s,                      \
                        (T*)L->buf.matrix, L->buf.pointers, L->buf.bias, (const T*)L->host_alias, L->buf.b, added, \
                        L->move_dst, L->row_elems, c.d_ffn, c.d_model, c.capacity_rows, (const T*)x, L->h,         \
-                       L->h_new, L->stamp, spec, L->st)
+                       L->h_new, L->stamp, spec, load_wgs, L->st)
     if (ni <= 1) LIF_LU(1);
     else if (ni <= 2) LIF_LU(2);
     else if (ni <= 4) LIF_LU(4);

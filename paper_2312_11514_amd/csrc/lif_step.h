@@ -4,10 +4,10 @@
 // workgroups busy for tens of microseconds (Section 3.3 item 2), while the activation stage of
 // the FFN (Section 3.3 item 3) streams the rows that are already resident.  Both only need the
 // token's x and the deletion plan, so one launch runs them side by side:
-//   workgroups [0, kStepLoadWgs)   loader role: row moves + pinned-host appends with the layout of
+//   workgroups [0, load_wgs)       loader role: row moves + pinned-host appends with the layout of
 //                                  k_load, and - since every bundle passes through their registers -
 //                                  the activation of each row they write (h_new, stamped with the step);
-//   workgroups [kStepLoadWgs, ...) activation role over the rows kept by the deletion (slots < n').
+//   workgroups [load_wgs, ...)     activation role over the rows kept by the deletion (slots < n').
 // The activation role may read a hole while a loader overwrites it; that value is never used,
 // because the loader's stamped activation takes precedence in the down-projection kernel.
 #pragma once
@@ -17,14 +17,16 @@
 
 namespace lif {
 
-#ifndef LIF_STEP_LOAD_WGS
-#define LIF_STEP_LOAD_WGS 32
+#ifndef LIF_STEP_INFLIGHT_BYTES
+#define LIF_STEP_INFLIGHT_BYTES (256 * 1024)
 #endif
-#ifndef LIF_STEP_LOAD_WAVES
-#define LIF_STEP_LOAD_WAVES 1
-#endif
-constexpr int kStepLoadWgs = LIF_STEP_LOAD_WGS;       // workgroups in the loader role
-constexpr int kStepLoadWaves = LIF_STEP_LOAD_WAVES;   // waves of each that load (the others exit at once)
+// The host link runs best with a few hundred KiB of reads outstanding: measured 51 GB/s with 128 KiB in
+// flight (32 waves x 4 KiB bundles), 46 GB/s with 512 KiB (32 x 16 KiB), 44 GB/s with 1 MiB (32 x 32 KiB).
+// The number of loader waves (one bundle in flight each, one per workgroup so that they spread over
+// compute units) is therefore chosen from the bundle size: kStepInflightBytes / bundle bytes, within 10..64
+// (8 waves were measured 15 % slower than 16 at 16 KiB bundles).
+constexpr int kStepInflightBytes = LIF_STEP_INFLIGHT_BYTES;
+constexpr int kStepLoadWaves = 1;                     // waves of a loader workgroup that load (the others exit at once)
 
 // Loader role, one wave per work item.  Work item q covers tail slot s = n' + q (see k_load):
 // the wave requests the whole host bundle of added[q] first (the long latency), moves the live
@@ -204,7 +206,7 @@ __device__ __forceinline__ void load_role(T* __restrict__ matrix, int32_t* __res
     }
 }
 
-// grid = kStepLoadWgs + up_blocks, block = 256.  Batch 1 only.
+// grid = load_wgs + up_blocks, block = 256.  Batch 1 only.
 template <typename T, int NI, bool GLU>
 __global__ __launch_bounds__(256) void k_load_up(T* __restrict__ matrix, int32_t* __restrict__ pointers,
                                                  float* __restrict__ bias, const T* __restrict__ host,
@@ -212,18 +214,18 @@ __global__ __launch_bounds__(256) void k_load_up(T* __restrict__ matrix, int32_t
                                                  const int32_t* __restrict__ move_dst, size_t row_elems, int F, int d,
                                                  int capacity, const T* __restrict__ x, float* __restrict__ h,
                                                  float* __restrict__ h_new, int32_t* __restrict__ stamp, int spec,
-                                                 DevState* st) {
-    if (blockIdx.x < kStepLoadWgs) {
+                                                 int load_wgs, DevState* st) {
+    if ((int)blockIdx.x < load_wgs) {
         const int w = threadIdx.x >> 6;
         if (w >= kStepLoadWaves) return;
         load_role<T, NI, GLU>(matrix, pointers, bias, host, b, added, move_dst, row_elems, F, d, capacity, x, h_new, stamp,
-                              blockIdx.x * kStepLoadWaves + w, kStepLoadWgs * kStepLoadWaves, st);
+                              blockIdx.x * kStepLoadWaves + w, load_wgs * kStepLoadWaves, st);
     } else {
 #ifdef LIF_EXPERIMENT_NO_UP
         return;
 #endif
-        ffn_up_role<T, NI, GLU, true>(matrix, bias, x, h, d, 1, capacity, row_elems, spec, blockIdx.x - kStepLoadWgs,
-                                      gridDim.x - kStepLoadWgs, &st->n_base, st);
+        ffn_up_role<T, NI, GLU, true>(matrix, bias, x, h, d, 1, capacity, row_elems, spec, blockIdx.x - load_wgs,
+                                      gridDim.x - load_wgs, &st->n_base, st);
     }
 }
 
