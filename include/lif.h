@@ -179,6 +179,24 @@ int lif_update_window(lif_layer* layer, const uint8_t* step_mask_dev,
                       int32_t* removed_dev, int32_t* n_removed_dev, void* stream);
 
 /*
+ * Step 2 for a verification pass of speculative decoding (Section 4.3 "Speculative Decoding";
+ * Appendix, related work: "the window ... is updated with multiple tokens rather than one").
+ *   masks_dev  [n_tokens x d_ffn/8] bytes, device, 8-byte aligned: the per-token masks of the
+ *              pass (as written by lif_predict with batch = n_tokens); d_ffn % 64 == 0
+ *   keep       0..n_tokens: the first `keep` tokens (those expected to be accepted; the paper's
+ *              choice is about alpha * (lambda + 1) for acceptance ratio alpha) enter the window,
+ *              one entry per token, exactly as if pushed one after the other; the masks of the
+ *              remaining tokens are needed for this pass only and leave with the next update.
+ * The cache must hold, for this pass, the union of the last window_k kept token masks and of
+ * the transient masks: added / removed are the difference to what it holds now.  Capacity
+ * overflow is a LIF_CAPACITY error (no dynamic shrink on this path).  Alternates with
+ * lif_load_bundles like lif_update_window; follow with lif_sparse_ffn(batch = n_tokens).
+ */
+int lif_update_window_tokens(lif_layer* layer, const uint8_t* masks_dev, int32_t n_tokens, int32_t keep,
+                             int32_t* added_dev, int32_t* n_added_dev, int32_t* removed_dev,
+                             int32_t* n_removed_dev, void* stream);
+
+/*
  * Step 3, cache update (Section 3.3 items 1 and 2, Fig. 6; bundles per Section 3.2).
  * Deletion: with c = *n_removed_dev and n' = num_used - c, the rows whose neuron left
  * the window are overwritten by the last rows: the j-th lowest dead slot below n'

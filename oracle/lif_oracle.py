@@ -10,7 +10,8 @@ Every function restates one passage of the paper:
   predictor_logits / predict_mask   Section 3.1 "Anticipating ReLU Sparsity", Fig. 3b;
                                     "active neuron" = positive predictor output (Section 3.1,
                                     "The Sliding Window Technique")
-  SlidingWindow                     Section 3.1 "The Sliding Window Technique", Fig. 4b
+  SlidingWindow                     Section 3.1 "The Sliding Window Technique", Fig. 4b;
+                                    push_tokens: Section 4.3 "Speculative Decoding"
   bundle_bytes                      Section 3.2 "Bundling Columns and Rows", Fig. 5
   delete_neurons / insert_neurons   Section 3.3 items 1 and 2, Fig. 6
   sparse_ffn                        Section 3.3 item 3
@@ -86,12 +87,37 @@ class SlidingWindow:
         assert k >= 1
         self.F, self.k = d_ffn, k
         self.masks: list[np.ndarray] = []
+        self.transient = np.zeros(d_ffn, dtype=bool)     # masks needed by the last step only (push_tokens)
 
     def active_set(self) -> np.ndarray:
-        s = np.zeros(self.F, dtype=bool)
+        s = self.transient.copy()
         for m in self.masks:
             s |= m
         return s
+
+    def push_tokens(self, masks, keep, capacity=None):
+        """One verification pass of speculative decoding (Section 4.3): `masks` [n_tokens, F] are the
+        per-token masks of the pass; the first `keep` tokens enter the window one by one; every
+        mask of the pass is held for this pass (all its tokens are computed), those that are not
+        in the window afterwards leave with the next update.  Returns (added, removed) against what was held before."""
+        masks = np.asarray(masks, dtype=bool)
+        before = self.active_set()
+        new_masks = list(self.masks)
+        for i in range(keep):
+            new_masks.append(masks[i].copy())
+            new_masks = new_masks[-self.k:]
+        transient = np.zeros(self.F, dtype=bool)       # every token of the pass is computed in this pass,
+        for i in range(len(masks)):                    # also one that enters and leaves the window at once
+            transient |= masks[i]
+        after = transient.copy()
+        for m in new_masks:
+            after |= m
+        if capacity is not None and int(after.sum()) > capacity:
+            raise OverflowError("active set exceeds the neuron cache capacity")
+        self.masks, self.transient = new_masks, transient
+        added = np.flatnonzero(after & ~before).astype(np.int32)
+        removed = np.flatnonzero(before & ~after).astype(np.int32)
+        return added, removed
 
     def push(self, mask, capacity=None, shrink=False):
         """Slide by one step.  Returns (added ids, removed ids), ascending int32.
@@ -122,6 +148,7 @@ class SlidingWindow:
             if int(after.sum()) > capacity:
                 raise OverflowError("the step mask alone exceeds the neuron cache capacity")
         self.masks = new_masks
+        self.transient = np.zeros(self.F, dtype=bool)
         added = np.flatnonzero(after & ~before).astype(np.int32)
         removed = np.flatnonzero(before & ~after).astype(np.int32)
         return added, removed
@@ -279,6 +306,15 @@ class OracleLayer:
 
     def sparse_ffn(self, x, acc=np.float64):
         return sparse_ffn(self.cache, x, self.d, self.glu, acc)
+
+    def step_tokens(self, x, keep):
+        """One speculative verification pass: x [n_tokens, d]; the first `keep` tokens enter the window."""
+        masks = self.predict(x)
+        added, removed = self.window.push_tokens(masks, keep, self.cache.capacity)
+        loaded = self.load_bundles(added, removed)
+        y = self.sparse_ffn(x)
+        return dict(masks=masks, added=added, removed=removed, loaded=loaded, y=y,
+                    num_used=self.cache.num_used)
 
     def step(self, x):
         """One token (or one batch of tokens).  Returns a dict with every intermediate."""

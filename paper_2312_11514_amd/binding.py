@@ -50,6 +50,7 @@ EXPORTS = {
     "lif_reset": (C.c_int, [C.c_void_p, C.c_void_p]),
     "lif_predict": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]),
     "lif_update_window": (C.c_int, [C.c_void_p] + [C.c_void_p] * 5 + [C.c_void_p]),
+    "lif_update_window_tokens": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32] + [C.c_void_p] * 4 + [C.c_void_p]),
     "lif_load_bundles": (C.c_int, [C.c_void_p] + [C.c_void_p] * 4 + [C.c_void_p]),
     "lif_sparse_ffn": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]),
     "lif_step": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p] + [C.c_void_p] * 6 + [C.c_void_p]),
@@ -167,6 +168,12 @@ class Layer:
         step_mask = self.step_mask if step_mask is None else step_mask
         _check(self.lib.lif_update_window(self.handle, _ptr(step_mask), _ptr(self.added), _ptr(self.n_added),
                                           _ptr(self.removed), _ptr(self.n_removed), _stream()))
+
+    def update_window_tokens(self, n_tokens, keep, masks=None):
+        masks = self.masks if masks is None else masks
+        _check(self.lib.lif_update_window_tokens(self.handle, _ptr(masks), n_tokens, keep, _ptr(self.added),
+                                                 _ptr(self.n_added), _ptr(self.removed), _ptr(self.n_removed),
+                                                 _stream()))
 
     def load_bundles(self):
         _check(self.lib.lif_load_bundles(self.handle, _ptr(self.added), _ptr(self.n_added),

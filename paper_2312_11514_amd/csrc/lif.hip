@@ -69,7 +69,8 @@ Layout make_layout(const lif_config& c) {
     L.state = off;
     off = align_up(off + sizeof(DevState), 256);
     L.ring = off;                      // window_k step masks, each padded to whole 64-bit words
-    off = align_up(off + (size_t)c.window_k * ring_words(c) * 8, 256);
+    off = off + (size_t)c.window_k * ring_words(c) * 8;     // ... directly followed by the bitmap of the cached set
+    off = align_up(off + (size_t)ring_words(c) * 8, 256);
     L.tpart = off;
     off = align_up(off + sizeof(double) * c.max_batch * xa_chunks(c) * c.rank, 256);
     L.move_dst = off;
@@ -311,7 +312,7 @@ int lif_destroy(lif_layer* layer) {
 int lif_reset(lif_layer* L, void* stream) {
     if (!L) return fail(LIF_INVALID_ARG, "layer is null");
     hipStream_t s = (hipStream_t)stream;
-    const int total_words = L->cfg.window_k * ring_words(L->cfg);
+    const int total_words = (L->cfg.window_k + 1) * ring_words(L->cfg);      // ring + cached-set bitmap
     const int grid = std::min((total_words + 255) / 256, 256);
     hipLaunchKernelGGL(k_reset, dim3(grid), dim3(256), 0, s, L->ring, total_words, L->stamp, L->cfg.capacity_rows,
                        L->st);
@@ -331,23 +332,41 @@ int lif_predict(lif_layer* L, const void* x_dev, int32_t batch, uint8_t* masks_d
     return check_launch();
 }
 
-int lif_update_window(lif_layer* L, const uint8_t* step_mask_dev, int32_t* added_dev, int32_t* n_added_dev,
-                      int32_t* removed_dev, int32_t* n_removed_dev, void* stream) {
-    if (!L || !step_mask_dev || !added_dev || !n_added_dev || !removed_dev || !n_removed_dev)
+static int update_window_impl(lif_layer* L, const uint8_t* masks_dev, int ntok, int keep, int32_t* added_dev,
+                              int32_t* n_added_dev, int32_t* removed_dev, int32_t* n_removed_dev, void* stream) {
+    if (!L || !masks_dev || !added_dev || !n_added_dev || !removed_dev || !n_removed_dev)
         return fail(LIF_INVALID_ARG, "null argument");
-    if ((uintptr_t)step_mask_dev % 8) return fail(LIF_INVALID_ARG, "step mask must be 8-byte aligned");
+    if ((uintptr_t)masks_dev % 8) return fail(LIF_INVALID_ARG, "step mask must be 8-byte aligned");
     if (L->window_pending) return fail(LIF_BAD_STATE, "lif_update_window called twice without lif_load_bundles");
     hipStream_t s = (hipStream_t)stream;
     const lif_config& c = L->cfg;
     {
         Timed t(L, LIF_K_WINDOW, s);
-        hipLaunchKernelGGL(k_window_plan, dim3(1), dim3(kScanThreads), 0, s, step_mask_dev, L->ring, ring_words(c),
-                           L->buf.pointers, c.d_ffn, c.window_k, c.capacity_rows, c.shrink_window, added_dev, n_added_dev,
-                           removed_dev,
+        hipLaunchKernelGGL(k_window_plan, dim3(1), dim3(kScanThreads), 0, s, masks_dev, ntok, keep, L->ring,
+                           L->ring + (size_t)c.window_k * ring_words(c), ring_words(c), L->buf.pointers, c.d_ffn,
+                           c.window_k, c.capacity_rows, c.shrink_window, added_dev, n_added_dev, removed_dev,
                            n_removed_dev, L->move_dst, L->hole_list, L->st);
     }
     L->window_pending = true;
     return check_launch();
+}
+
+int lif_update_window(lif_layer* L, const uint8_t* step_mask_dev, int32_t* added_dev, int32_t* n_added_dev,
+                      int32_t* removed_dev, int32_t* n_removed_dev, void* stream) {
+    return update_window_impl(L, step_mask_dev, 1, 1, added_dev, n_added_dev, removed_dev, n_removed_dev, stream);
+}
+
+int lif_update_window_tokens(lif_layer* L, const uint8_t* masks_dev, int32_t n_tokens, int32_t keep,
+                             int32_t* added_dev, int32_t* n_added_dev, int32_t* removed_dev, int32_t* n_removed_dev,
+                             void* stream) {
+    if (!L) return fail(LIF_INVALID_ARG, "layer is null");
+    if (n_tokens < 1 || n_tokens > L->cfg.max_batch) return fail(LIF_INVALID_ARG, "n_tokens out of range");
+    if (keep < 0 || keep > n_tokens) return fail(LIF_INVALID_ARG, "keep must be in 0..n_tokens");
+    if (L->cfg.d_ffn % 64) return fail(LIF_INVALID_ARG, "token-granular window updates need d_ffn % 64 == 0");
+    if (L->cfg.shrink_window) return fail(LIF_INVALID_ARG, "token-granular window updates do not combine with shrink_window");
+    if (n_tokens == 1 && keep == 1)
+        return update_window_impl(L, masks_dev, 1, 1, added_dev, n_added_dev, removed_dev, n_removed_dev, stream);
+    return update_window_impl(L, masks_dev, n_tokens, keep, added_dev, n_added_dev, removed_dev, n_removed_dev, stream);
 }
 
 int lif_load_bundles(lif_layer* L, const int32_t* added_dev, const int32_t* n_added_dev, const int32_t* removed_dev,

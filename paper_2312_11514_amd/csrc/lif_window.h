@@ -75,8 +75,9 @@ __device__ __forceinline__ void block_exclusive_scan2(int va, int vb, unsigned l
 // The loads that do not depend on the state (mask word, ring words, first block of pointers)
 // are issued together with the state itself.
 __global__ __launch_bounds__(kScanThreads) void k_window_plan(
-    const uint8_t* __restrict__ step_mask, unsigned long long* __restrict__ ring, int ring_words,
-    const int32_t* __restrict__ pointers, int F, int k, int capacity, int shrink, int32_t* __restrict__ added,
+    const uint8_t* __restrict__ step_mask, int ntok, int keep_tok, unsigned long long* __restrict__ ring,
+    unsigned long long* __restrict__ cur_set, int ring_words, const int32_t* __restrict__ pointers, int F, int k,
+    int capacity, int shrink, int32_t* __restrict__ added,
     int32_t* __restrict__ n_added, int32_t* __restrict__ removed, int32_t* __restrict__ n_removed,
     int32_t* __restrict__ move_dst, int32_t* __restrict__ hole_list, DevState* st) {
     constexpr int NW = kScanThreads / kWave;
@@ -91,7 +92,8 @@ __global__ __launch_bounds__(kScanThreads) void k_window_plan(
     const bool have = tid < nwords;
 
     // ---- issue the state-independent loads ----
-    const unsigned long long m = have ? load_mask_word(step_mask, tid, nbytes) : 0ull;
+    unsigned long long m = have ? load_mask_word(step_mask, tid, nbytes) : 0ull;   // first (or only) mask of the step
+    const unsigned long long cur = have ? cur_set[tid] : 0ull;                       // what the cache holds now
     unsigned long long rv[kRingRegs];
 #pragma unroll
     for (int j = 0; j < kRingRegs; ++j) rv[j] = (have && j < k) ? ring[(size_t)j * ring_words + tid] : 0ull;
@@ -100,6 +102,7 @@ __global__ __launch_bounds__(kScanThreads) void k_window_plan(
     const int t = st->step;
     const int n = st->num_used;
     const int wl_prev = st->window_len;
+    const int pos = st->ring_pos;
 
     if (err) {
         if (tid == 0) {
@@ -112,23 +115,37 @@ __global__ __launch_bounds__(kScanThreads) void k_window_plan(
     }
 
     // ---- window ----
-    const int slot = t % k;
-    unsigned long long prev = 0, keep = 0;
+    const int slot = pos % k;                            // ring entry that this step's (first) mask replaces
+    const unsigned long long prev = cur;
+    unsigned long long keep = 0;
 #pragma unroll
-    for (int j = 0; j < kRingRegs; ++j) {
-        prev |= rv[j];
+    for (int j = 0; j < kRingRegs; ++j)
         if (j != slot) keep |= rv[j];
-    }
     if (have) {
         for (int j = kRingRegs; j < k; ++j) {                 // only for windows longer than kRingRegs steps
             const unsigned long long v = ring[(size_t)j * ring_words + tid];
-            prev |= v;
             if (j != slot) keep |= v;
         }
     }
     unsigned long long now = keep | m;                   // S_t with the full window
     int k_eff = k;
-    if (shrink) {
+    const bool multi = ntok != 1 || keep_tok != 1;
+    if (multi) {
+        // Several tokens in one step (speculative verification, Section 4.3 "Speculative Decoding" and the
+        // related-work note that the window is then updated with several tokens at once): all ntok masks
+        // are needed for this step's FFN, but only the first keep_tok of them enter the window (one ring
+        // entry per token, as if pushed one after the other); the others are transient.
+        const size_t row_bytes = (size_t)nbytes;           // the host checks F % 64 == 0 for this path
+        now = 0ull;
+        if (have) {
+            for (int i = 0; i < ntok; ++i) now |= load_mask_word(step_mask + (size_t)i * row_bytes, tid, nbytes);
+            for (int j = 0; j < k; ++j) {
+                const int since = ((j - pos) % k + k) % k;   // this entry is overwritten by kept token `since`
+                if (since >= keep_tok) now |= ring[(size_t)j * ring_words + tid];
+            }
+        }
+    }
+    if (shrink && !multi) {
         // Dynamic window (Appendix, Persimmon / Phi-2: the window is reduced whenever the cache would
         // pass its memory limit): keep the newest k_eff <= k masks, k_eff the largest count whose
         // union fits the capacity.  U_a = union of the newest a masks (a = 1: this step's mask).
@@ -212,9 +229,16 @@ __global__ __launch_bounds__(kScanThreads) void k_window_plan(
     }
     rem64[tid] = rbits;
     if (have) {
-        ring[(size_t)slot * ring_words + tid] = m;
-        for (int a = k_eff + 1; a <= k; ++a)                 // masks dropped by the dynamic window leave it for good
-            ring[(size_t)((slot - (a - 1) + k) % k) * ring_words + tid] = 0ull;
+        cur_set[tid] = now;
+        if (!multi) {
+            ring[(size_t)slot * ring_words + tid] = m;
+            for (int a = k_eff + 1; a <= k; ++a)             // masks dropped by the dynamic window leave it for good
+                ring[(size_t)((slot - (a - 1) + k) % k) * ring_words + tid] = 0ull;
+        } else {
+            for (int i = max(0, keep_tok - k); i < keep_tok; ++i)
+                ring[(size_t)((pos + i) % k) * ring_words + tid] =
+                    load_mask_word(step_mask + (size_t)i * nbytes, tid, nbytes);
+        }
     }
     while (abits) {
         added[off_a++] = tid * 64 + __ffsll((long long)abits) - 1;
@@ -287,7 +311,8 @@ __global__ __launch_bounds__(kScanThreads) void k_window_plan(
         st->n_removed = tot_r;
         st->n_base = n2;
         st->n_moved = H;
-        st->window_len = min(min(wl_prev + 1, k), k_eff);
+        st->window_len = multi ? min(wl_prev + keep_tok, k) : min(min(wl_prev + 1, k), k_eff);
+        st->ring_pos = (pos + (multi ? keep_tok : 1)) % k;
         st->step = t + 1;
         st->c_steps += 1;
         st->c_added += (unsigned long long)tot_a;
@@ -372,6 +397,7 @@ __global__ __launch_bounds__(256) void k_load(char* __restrict__ matrix, int32_t
 }
 
 // Empty cache: no mask in the window, state and counters zero.
+// (ring_total_words covers the ring and the current-set bitmap that follows it)
 __global__ void k_reset(unsigned long long* __restrict__ ring, int ring_total_words, int32_t* __restrict__ stamp,
                         int capacity, DevState* st) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;

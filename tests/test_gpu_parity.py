@@ -387,3 +387,47 @@ def test_n1_dynamic_window_at_opt_shape():
         lens.append(gpu.layer.state()["window_len"])
         assert lens[-1] == len(ora.window.masks)
     assert min(lens[8:]) < w.window_k
+
+
+@pytest.mark.parametrize("glu,dtype,d_model", [(False, "f16", 256), (True, "f16", 608), (False, "f32", 256)])
+def test_speculative_verify_passes_token_granular_window(glu, dtype, d_model):
+    """Passes of lambda + 1 = 5 consecutive tokens with a varying number of kept tokens (Section 4.3): per-token
+    masks, window entries per token, transient masks leaving with the next pass, FFN for all five tokens."""
+    from tests.harness import GpuLayer, rel_l2, REL_L2_TOL
+    w = wl.scaled(wl.WORKLOADS["C1"], name="spec", d_model=d_model, d_ffn=1024, rank=32, window_k=4, dtype=dtype,
+                  glu=glu, tokens=60, batch=5, capacity_rows=1024)
+    L = wl.make_layer(w)
+    X = wl.make_inputs(w)                                           # one stream; a pass takes 5 consecutive tokens
+    gpu = GpuLayer(w, L, max_batch=5)
+    lay = gpu.layer
+    ora = make_oracle(w, L)
+    keeps = [5, 3, 0, 1, 5, 2, 4, 5, 0, 0, 3, 5]
+    for p, keep in enumerate(keeps):
+        xb = X[5 * p:5 * p + 5]
+        ref = ora.step_tokens(xb, keep)
+        xd = gpu.upload_x(xb)
+        lay.predict(xd, 5)
+        lay.update_window_tokens(5, keep)
+        na, nr = int(lay.n_added.item()), int(lay.n_removed.item())
+        assert lay.added[:na].cpu().numpy().tolist() == ref["added"].tolist(), f"pass {p}"
+        assert lay.removed[:nr].cpu().numpy().tolist() == ref["removed"].tolist(), f"pass {p}"
+        lay.load_bundles()
+        lay.sparse_ffn(xd, gpu.y, 5)
+        st = lay.state()
+        n = ref["num_used"]
+        assert st["error"] == 0 and st["num_used"] == n and st["window_len"] == len(ora.window.masks)
+        assert (lay.masks[:5].cpu().numpy() == O.pack_mask(ref["masks"])).all()
+        assert (lay.pointers[:n].cpu().numpy() == ora.cache.pointers[:n]).all()
+        assert lay.matrix[:n].cpu().numpy().tobytes() == ora.cache.matrix[:n].tobytes()
+        assert rel_l2(gpu.y[:5].cpu().numpy(), ref["y"]) <= REL_L2_TOL
+    assert lay.counters()["h2d_bytes"] == ora.bytes_loaded
+    # mixing with ordinary single-token steps on the same layer
+    from tests.harness import compare_step
+    w1 = wl.scaled(w, batch=1)
+    for t in range(4):
+        x = X[55 + t]
+        ref = ora.step(x)
+        xd = gpu.upload_x(x)
+        lay.step(xd, gpu.y, 1)
+        assert lay.state()["num_used"] == ref["num_used"]
+        assert rel_l2(gpu.y[0].cpu().numpy(), ref["y"]) <= REL_L2_TOL

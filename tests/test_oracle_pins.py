@@ -432,3 +432,45 @@ def test_dynamic_window_is_the_largest_suffix_that_fits():
         assert list(added) == sorted(cur - prev) and list(removed) == sorted(prev - cur)
         a2, r2 = fixed.push(m, capacity=F, shrink=True)       # never shrinks
         assert len(fixed.masks) == min(k, t + 1)
+
+
+# ----------------------------------------------------------------------------- several tokens per step
+def test_window_tokens_hand_worked():
+    g = golden("window_tokens.json")
+    F = g["d_ffn"]
+    win = O.SlidingWindow(F, g["k"])
+    for p in g["passes"]:
+        M = np.zeros((len(p["masks"]), F), bool)
+        for i, ids in enumerate(p["masks"]):
+            M[i, ids] = True
+        added, removed = win.push_tokens(M, p["keep"])
+        assert list(added) == p["added"] and list(removed) == p["removed"]
+        assert list(np.flatnonzero(win.active_set())) == p["active"]
+        assert len(win.masks) == p["window_len"]
+
+
+def test_window_tokens_reduces_to_single_pushes():
+    """keep = all tokens: the set held after the pass is the one that single pushes end with (union of the
+    last k token masks); one token with keep = 1 is the ordinary push; keep = 0 leaves the window alone."""
+    rng = np.random.default_rng(5)
+    F, k = 64, 4
+    a, b = O.SlidingWindow(F, k), O.SlidingWindow(F, k)
+    for p in range(12):
+        M = rng.random((3, F)) < 0.1
+        a.push_tokens(M, 3)
+        for m in M:
+            b.push(m)
+        assert (a.active_set() == b.active_set()).all()
+    c, d = O.SlidingWindow(F, k), O.SlidingWindow(F, k)
+    for p in range(12):
+        m = rng.random(F) < 0.1
+        r1 = c.push_tokens(m[None, :], 1)
+        r2 = d.push(m)
+        assert list(r1[0]) == list(r2[0]) and list(r1[1]) == list(r2[1])
+    held = [x.copy() for x in c.masks]
+    M = rng.random((2, F)) < 0.2
+    c.push_tokens(M, 0)
+    assert all((x == y).all() for x, y in zip(held, c.masks))
+    assert (c.active_set() == (np.logical_or.reduce(held) | M[0] | M[1])).all()
+    c.push_tokens(np.zeros((1, F), bool), 0)                       # the transient masks are gone again
+    assert (c.active_set() == np.logical_or.reduce(held)).all()
