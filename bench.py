@@ -6,7 +6,7 @@ sparse_ffn for every token and every layer) over the workload's token stream, st
 empty neuron caches.  Inputs, weights and the pinned bundle store are resident before the
 timed region starts.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C2|C3|C4|C4b8|C5|N1] [--ffn-mode skip|full]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C2|C3|C4|C4b8|C5|N1|N2] [--ffn-mode skip|full]
 """
 from __future__ import annotations
 
@@ -42,13 +42,16 @@ def cpu_baseline(w, L, X, budget_s=20.0):
     t0 = time.perf_counter()
     done = 0
     for t in range(len(X)):
-        ora.step(X[t])
+        if w.spec_keep > 0:
+            ora.step_tokens(X[t], w.spec_keep)
+        else:
+            ora.step(X[t])
         done += 1
         if time.perf_counter() - t0 > budget_s:
             break
     dt = time.perf_counter() - t0
     return {"value": dt / done * 1e6, "unit": "us/token/layer", "cores": int(cores), "kind": "oracle",
-            "sample": f"first {done} tokens of the same stream on layer 0, whole path "
+            "sample": f"first {done} steps of the same stream on layer 0, whole path "
                       f"(predict, window, delete, insert, FFN)"}
 
 
@@ -215,7 +218,13 @@ def main():
     reads_all = args.ffn_mode == "full"
 
     base = wl.make_layer(w)
-    X = wl.make_batch_inputs(w) if w.batch > 1 else wl.make_inputs(w)
+    spec = w.spec_keep > 0
+    X = wl.make_inputs(w) if (w.batch == 1 or spec) else wl.make_batch_inputs(w)
+    if spec:
+        # pass p verifies tokens [p * keep, p * keep + batch): the next pass starts after the accepted ones
+        import numpy as np
+        n_pass = (len(X) - w.batch) // w.spec_keep + 1
+        X = np.stack([X[p * w.spec_keep:p * w.spec_keep + w.batch] for p in range(n_pass)])
     T = len(X)
     gpus = []
     for l in range(NL):
@@ -229,9 +238,16 @@ def main():
     if NL == 1:
         # whole token stream of the layer in one HIP graph
         def run_stream():
-            layers[0].reset()
+            lay0 = layers[0]
+            lay0.reset()
             for t in range(T):
-                layers[0].step(xd[t], yd[0, t], w.batch)
+                if spec:
+                    lay0.predict(xd[t], w.batch)
+                    lay0.update_window_tokens(w.batch, w.spec_keep)
+                    lay0.load_bundles()
+                    lay0.sparse_ffn(xd[t], yd[0, t], w.batch)
+                else:
+                    lay0.step(xd[t], yd[0, t], w.batch)
         graph = None
         run_stream()                                      # eager pass: validates the chain, fills counters
         torch.cuda.synchronize()
@@ -372,6 +388,8 @@ def main():
                                 "rows_added": added_per_call, "h2d_bytes": added_per_call * w.bundle_bytes,
                                 "nominal_bundle_bytes": nominal},
         "window_len_at_end": window_len_end,
+        "speculative": ({"tokens_per_pass": w.batch, "kept_per_pass": w.spec_keep, "passes": T,
+                         "us_per_accepted_token": us_per_token_layer / w.spec_keep} if spec else None),
         "end_to_end_us_per_token": us_per_token_layer * NL,
         "h2d_bytes_per_token": added_per_call * w.bundle_bytes * NL,
     }

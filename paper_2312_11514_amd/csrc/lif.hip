@@ -144,15 +144,15 @@ int launch_predict(lif_layer* L, const void* x, int batch, uint8_t* masks, uint8
     }
     const int grid = (c.d_ffn + kMaskCols * 8 - 1) / (kMaskCols * 8);
     Timed t(L, LIF_K_PREDICT_MASK, s);
-    if (batch == 1 || c.rank > 1024) {
-        hipLaunchKernelGGL((k_predict_mask<T, 1>), dim3(grid), dim3(256), sizeof(double) * c.rank, s,
-                           (const T*)L->buf.B, L->buf.c, L->tpart, nch, c.rank, c.d_ffn, batch, c.threshold, masks,
-                           step_mask, L->st);
-    } else {
-        hipLaunchKernelGGL((k_predict_mask<T, 4>), dim3(grid), dim3(256), sizeof(double) * 4 * c.rank, s,
-                           (const T*)L->buf.B, L->buf.c, L->tpart, nch, c.rank, c.d_ffn, batch, c.threshold, masks,
-                           step_mask, L->st);
-    }
+#define LIF_MASK(BT)                                                                                        \
+    hipLaunchKernelGGL((k_predict_mask<T, BT>), dim3(grid), dim3(256), sizeof(double) * BT * c.rank, s,          \
+                       (const T*)L->buf.B, L->buf.c, L->tpart, nch, c.rank, c.d_ffn, batch, c.threshold, masks,    \
+                       step_mask, L->st)
+    // tokens per pass over B: all of them when the partial sums fit LDS (BT * rank doubles <= 48 KiB)
+    if (batch == 1 || c.rank > 1536) LIF_MASK(1);
+    else if (batch <= 4 || c.rank > 768) LIF_MASK(4);
+    else LIF_MASK(8);
+#undef LIF_MASK
     return LIF_OK;
 }
 

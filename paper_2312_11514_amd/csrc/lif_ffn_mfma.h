@@ -104,6 +104,10 @@ constexpr int kDownBLanes = LIF_DOWNB_LANES;     // lanes per row piece: 16 x 16
 constexpr int kDownChunks = LIF_DOWNB_CHUNKS;    // row chunks of the batched down projection (partial outputs per chunk)
 constexpr int kDownBTile = 512;                  // cached rows whose activations sit in LDS per pass
 
+// Row chunks actually used for n rows in use: about 256 rows per chunk, at most kDownChunks (the finish
+// kernel applies the same rule, so unused chunks are neither written nor read).
+__device__ __forceinline__ int down_chunks_in_use(int n) { return min(kDownChunks, max(1, (n + 255) / 256)); }
+
 // Down projection for a batch of tokens: Y[t][j] = sum_s H[t][s] * D[s][j] over the rows in use.
 // grid = (ceil(d / (kDownBLanes * VE)), kDownChunks), block = 256 = row groups x kDownBLanes lanes.
 // Workgroup (slice, chunk) owns 256 contiguous bytes of every down column of the rows of its
@@ -134,7 +138,9 @@ __global__ __launch_bounds__(256) void k_ffn_down_batched(const T* __restrict__ 
     const int err = st->error;
     const int n = st->num_used;
     if (err) return;
-    const int per_chunk = (n + kDownChunks - 1) / kDownChunks;
+    const int eff = down_chunks_in_use(n);
+    if ((int)blockIdx.y >= eff) return;              // uniform: fewer, fatter chunks when few rows are in use
+    const int per_chunk = (n + eff - 1) / eff;
     const int r0 = blockIdx.y * per_chunk, r1 = min(n, r0 + per_chunk);
 
     float acc[BT][VE];
@@ -221,9 +227,9 @@ __global__ __launch_bounds__(256) void k_ffn_down_finish(const float* __restrict
     if (st->error) return;
     const int i = blockIdx.x * 256 + threadIdx.x;
     if (i < batch * d) {
+        const int eff = down_chunks_in_use(st->num_used);
         float s = 0.f;
-#pragma unroll
-        for (int c = 0; c < kDownChunks; ++c) s += ypart[(size_t)c * batch * d + i];
+        for (int c = 0; c < eff; ++c) s += ypart[(size_t)c * batch * d + i];
         y[i] = (T)s;
     }
     if (i == 0) {

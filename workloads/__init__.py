@@ -39,6 +39,7 @@ class Workload:
     capacity_rows: int   # rows preallocated in the HBM neuron cache
     layers: int = 1
     shrink: bool = False # dynamic window: drop the oldest masks instead of overflowing
+    spec_keep: int = 0   # > 0: speculative verification passes of `batch` consecutive tokens, the first spec_keep kept
 
     @property
     def np_dtype(self):
@@ -76,6 +77,9 @@ WORKLOADS = {
     # dynamic-window case: OPT shape at 10 % activity, k = 8, cache capped at 25 % of the FFN rows
     # (the appendix's Persimmon setting: window reduced whenever the cache would pass 25 % of the FFN)
     "N1": Workload("N1", 4096, 16384, 128, 8, 0.10, 0.9, "f16", False, 256, 1, 4096, shrink=True),
+    # speculative verification (Section 4.3): passes of lambda + 1 = 5 consecutive tokens of one stream, 4 of
+    # them accepted (acceptance ratio 0.8), window of the last 5 kept tokens; the next pass starts after them
+    "N2": Workload("N2", 4096, 16384, 128, 5, 0.03, 0.9, "f16", False, 256, 5, 8192, spec_keep=4),
 }
 
 
