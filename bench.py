@@ -37,8 +37,9 @@ def cpu_baseline(w, L, X, budget_s=20.0):
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         cores = os.cpu_count() or 1
-    ora = O.OracleLayer(w.d_model, w.d_ffn, w.window_k, w.capacity_rows, w.glu, L.A, L.B, L.c, L.theta,
-                        L.b, L.bundles, shrink=w.shrink)
+    gate = w.gate_resident
+    ora = O.OracleLayer(w.d_model, w.d_ffn, w.window_k, w.capacity_rows, w.glu and not gate, L.A, L.B, L.c,
+                        L.theta, L.b, L.bundles, shrink=w.shrink, w_gate=L.w_gate if gate else None)
     t0 = time.perf_counter()
     done = 0
     for t in range(len(X)):

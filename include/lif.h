@@ -55,6 +55,14 @@ enum lif_ffn_mode {
     LIF_FFN_FULL_BUNDLE = 1 /* read every cached bundle completely */
 };
 
+/* What decides which neurons are predicted active (step 1). */
+enum lif_predictor {
+    LIF_PRED_LOWRANK = 0,  /* low-rank predictor (x A) B + c > theta (Section 3.1, Fig. 3b)               */
+    LIF_PRED_GATE = 1      /* the resident gate projection itself (Appendix, Llama 2, "Alternative         */
+                           /* approaches"): mask_i = gate_i . x + b_i > theta, exact; bundles = up | down; */
+                           /* y = sum_s relu(gate . x + b)_s * (up_s . x) * down_s; batch 1, glu = 0        */
+};
+
 typedef struct lif_config {
     int32_t d_model;        /* d: length of the up row and of the down column              */
     int32_t d_ffn;          /* F: number of intermediate neurons of the layer              */
@@ -68,6 +76,7 @@ typedef struct lif_config {
     int32_t shrink_window;  /* 1: dynamic window (Appendix, Persimmon / Phi-2): when the active  */
                             /* set would exceed capacity_rows the oldest masks leave the window  */
                             /* until it fits; 0: such a step is a LIF_CAPACITY error             */
+    int32_t predictor;      /* enum lif_predictor                                          */
     float threshold;        /* theta: neuron i is predicted active iff logit_i > theta     */
 } lif_config;
 

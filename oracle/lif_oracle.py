@@ -247,6 +247,26 @@ def sparse_ffn_loops(cache: NeuronCache, x, d_model: int, glu: bool = False):
     return y
 
 
+def gate_predict_mask(x, w_gate, b, theta):
+    """Appendix (Llama 2, alternative approaches): with the gate projection resident, the gate
+    pre-activations a_i = gate_i . x + b_i are known before anything is loaded and a_i > theta names
+    exactly the neurons that fire.  Returns (mask, margin, relu(a)) in fp64."""
+    a = np.asarray(x, np.float64) @ np.asarray(w_gate, np.float64).T + np.asarray(b, np.float64)
+    margin = float(np.min(np.abs(a - theta))) if a.size else float("inf")
+    return a > theta, margin, np.maximum(a, 0.0)
+
+
+def sparse_ffn_resident_gate(cache: NeuronCache, gate_act, x, d_model: int):
+    """FFN over the cached rows when bundles hold up row | down column and the gate activation
+    relu(gate_i . x + b_i) comes from the resident gate projection (indexed by original neuron id):
+    y = sum_s gate_act[pointers[s]] * (up_s . x) * down_s."""
+    n = cache.num_used
+    m = cache.matrix[:n].astype(np.float64)
+    up, down = m[:, :d_model], m[:, d_model:2 * d_model]
+    h = np.asarray(gate_act, np.float64)[cache.pointers[:n]] * (up @ np.asarray(x, np.float64))
+    return h @ down
+
+
 def preactivations(w_act, b, x):
     return np.asarray(w_act, dtype=np.float64) @ np.asarray(x, dtype=np.float64) + \
         np.asarray(b, dtype=np.float64)
@@ -279,8 +299,12 @@ class OracleLayer:
     """One FFN layer driven token by token: predict -> window -> delete -> insert -> FFN."""
 
     def __init__(self, d_model, d_ffn, window_k, capacity_rows, glu, A, B, c, theta, b,
-                 host_bundles, shrink=False):
+                 host_bundles, shrink=False, w_gate=None):
+        """w_gate given: the resident gate projection is the predictor (A, B, c unused, glu False,
+        bundles = up | down)."""
         self.shrink = shrink
+        self.w_gate = w_gate
+        self.gate_act = None
         self.d, self.F, self.k, self.glu = d_model, d_ffn, window_k, glu
         self.A, self.B, self.c, self.theta, self.b = A, B, c, theta, b
         self.host = host_bundles
@@ -291,7 +315,10 @@ class OracleLayer:
         self.min_margin = float("inf")
 
     def predict(self, x):
-        mask, margin = predict_mask(x, self.A, self.B, self.c, self.theta)
+        if self.w_gate is not None:
+            mask, margin, self.gate_act = gate_predict_mask(x, self.w_gate, self.b, self.theta)
+        else:
+            mask, margin = predict_mask(x, self.A, self.B, self.c, self.theta)
         self.min_margin = min(self.min_margin, margin)
         return mask
 
@@ -305,6 +332,8 @@ class OracleLayer:
         return loaded
 
     def sparse_ffn(self, x, acc=np.float64):
+        if self.w_gate is not None:
+            return sparse_ffn_resident_gate(self.cache, self.gate_act, x, self.d)
         return sparse_ffn(self.cache, x, self.d, self.glu, acc)
 
     def step_tokens(self, x, keep):

@@ -14,13 +14,15 @@ LIB_PATH = os.environ.get("LIF_LIBRARY", os.path.join(HERE, "liblif.so"))   # ov
 LIF_OK, LIF_INVALID_ARG, LIF_BAD_STATE, LIF_CAPACITY, LIF_HIP_ERROR = 0, 1, 2, 3, 4
 LIF_F32, LIF_F16 = 0, 1
 FFN_SKIP_DEAD, FFN_FULL_BUNDLE = 0, 1
+PRED_LOWRANK, PRED_GATE = 0, 1
 KERNEL_NAMES = ("predict_xa", "predict_mask", "window", "load", "ffn_up", "ffn_down")
 STATUS_NAMES = {0: "OK", 1: "INVALID_ARG", 2: "BAD_STATE", 3: "CAPACITY", 4: "HIP_ERROR"}
 
 
 class LifConfig(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("d_model", "d_ffn", "rank", "window_k", "capacity_rows",
-                                         "max_batch", "glu", "dtype", "ffn_mode", "shrink_window")] + \
+                                         "max_batch", "glu", "dtype", "ffn_mode", "shrink_window",
+                                         "predictor")] + \
         [("threshold", C.c_float)]
 
 
@@ -108,12 +110,14 @@ class Layer:
     """
 
     def __init__(self, *, d_model, d_ffn, rank, window_k, capacity_rows, max_batch=1, glu=False,
-                 dtype="f16", ffn_mode=FFN_SKIP_DEAD, shrink_window=False, threshold=0.0, A, B, c, b, host_bundles):
+                 dtype="f16", ffn_mode=FFN_SKIP_DEAD, shrink_window=False, predictor=PRED_LOWRANK, threshold=0.0, A, B, c, b,
+                 host_bundles):
         import torch
         self.lib = load_library()
         self.torch = torch
         self.cfg = LifConfig(d_model, d_ffn, rank, window_k, capacity_rows, max_batch, int(glu),
-                             LIF_F32 if dtype == "f32" else LIF_F16, ffn_mode, int(shrink_window), threshold)
+                             LIF_F32 if dtype == "f32" else LIF_F16, ffn_mode, int(shrink_window), predictor,
+                             threshold)
         self.tdtype = torch.float32 if dtype == "f32" else torch.float16
         dev = A.device
         G = 3 if glu else 2
@@ -133,7 +137,8 @@ class Layer:
         self.removed = torch.empty(d_ffn, dtype=torch.int32, device=dev)
         self.n_added = torch.empty(1, dtype=torch.int32, device=dev)
         self.n_removed = torch.empty(1, dtype=torch.int32, device=dev)
-        self.buf = LifBuffers(A.data_ptr(), B.data_ptr(), c.data_ptr() if c is not None else None,
+        self.buf = LifBuffers(A.data_ptr(), B.data_ptr() if B is not None else None,
+                              c.data_ptr() if c is not None else None,
                               b.data_ptr(), host_bundles.data_ptr(), self.matrix.data_ptr(),
                               self.pointers.data_ptr(), self.bias.data_ptr(),
                               self.workspace.data_ptr(), ws_bytes)

@@ -36,7 +36,7 @@ int fail(int code, const char* fmt, const char* detail = "") {
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 struct Layout {
-    size_t state, ring, tpart, move_dst, hole_list, h, ypart, h_new, stamp, total;
+    size_t state, ring, tpart, move_dst, hole_list, h, ypart, h_new, stamp, gact, total;
 };
 
 int elem_bytes(const lif_config& c) { return c.dtype == LIF_F32 ? 4 : 2; }
@@ -52,12 +52,16 @@ bool config_ok(const lif_config* c, const char** why) {
     if (c->d_model <= 0 || c->d_model % ve) return (*why = "d_model must be a positive multiple of 16 bytes", false);
     if ((c->d_model / ve + 63) / 64 > 16) return (*why = "d_model too large (at most 1024 16-byte vectors)", false);
     if (c->d_ffn <= 0 || c->d_ffn % 8 || c->d_ffn > kScanThreads * kMaxSpan) return (*why = "d_ffn must be a multiple of 8, at most 65536", false);
-    if (c->rank <= 0 || c->rank % ve || c->rank / ve > 256 || c->rank > 2048) return (*why = "rank", false);
+    if (c->predictor != LIF_PRED_GATE &&
+        (c->rank <= 0 || c->rank % ve || c->rank / ve > 256 || c->rank > 2048)) return (*why = "rank", false);
     if (c->window_k < 1 || c->window_k > 256) return (*why = "window_k must be in 1..256", false);
     if (c->capacity_rows < 1 || c->capacity_rows > kScanThreads * kMaxSpan) return (*why = "capacity_rows must be in 1..65536", false);
     if (c->max_batch < 1 || c->max_batch > 8) return (*why = "max_batch must be in 1..8", false);
     if (c->glu != 0 && c->glu != 1) return (*why = "glu", false);
     if (c->shrink_window != 0 && c->shrink_window != 1) return (*why = "shrink_window", false);
+    if (c->predictor != LIF_PRED_LOWRANK && c->predictor != LIF_PRED_GATE) return (*why = "predictor", false);
+    if (c->predictor == LIF_PRED_GATE && (c->glu || c->max_batch != 1))
+        return (*why = "the gate predictor takes plain (up | down) bundles and batch 1", false);
     if (c->ffn_mode != LIF_FFN_SKIP_DEAD && c->ffn_mode != LIF_FFN_FULL_BUNDLE) return (*why = "ffn_mode", false);
     if ((size_t)c->max_batch * c->d_model * elem_bytes(*c) > 64 * 1024) return (*why = "max_batch * d_model exceeds the 64 KiB LDS staging area", false);
     return true;
@@ -72,7 +76,7 @@ Layout make_layout(const lif_config& c) {
     off = off + (size_t)c.window_k * ring_words(c) * 8;     // ... directly followed by the bitmap of the cached set
     off = align_up(off + (size_t)ring_words(c) * 8, 256);
     L.tpart = off;
-    off = align_up(off + sizeof(double) * c.max_batch * xa_chunks(c) * c.rank, 256);
+    off = align_up(off + sizeof(double) * c.max_batch * xa_chunks(c) * std::max(c.rank, 0), 256);
     L.move_dst = off;
     off = align_up(off + sizeof(int32_t) * c.capacity_rows, 256);
     L.hole_list = off;
@@ -85,6 +89,8 @@ Layout make_layout(const lif_config& c) {
     off = align_up(off + sizeof(float) * c.capacity_rows, 256);
     L.stamp = off;                     // step number at which h_new[slot] was written
     off = align_up(off + sizeof(int32_t) * c.capacity_rows, 256);
+    L.gact = off;                      // gate predictor: relu(gate_i . x + b_i) per original neuron
+    off = align_up(off + (c.predictor == LIF_PRED_GATE ? sizeof(float) * c.d_ffn : 0), 256);
     L.total = off;
     return L;
 }
@@ -105,6 +111,7 @@ struct lif_layer {
     float* ypart;
     float* h_new;
     int32_t* stamp;
+    float* gact;                // null unless the gate projection is the predictor
     size_t row_elems, row_bytes;
     bool window_pending;
     int expected_rows;          // hint, 0 = none
@@ -156,6 +163,30 @@ int launch_predict(lif_layer* L, const void* x, int batch, uint8_t* masks, uint8
     return LIF_OK;
 }
 
+template <typename T>
+void launch_predict_gate(lif_layer* L, const void* x, uint8_t* masks, uint8_t* step_mask, hipStream_t s) {
+    const lif_config& c = L->cfg;
+    const int nvec = c.d_model / Vec<T>::N;
+    const int ni = (nvec + 63) / 64;
+    const int grid = std::min((c.d_ffn / 8 + 3) / 4, 2048);
+    Timed t(L, LIF_K_PREDICT_MASK, s);
+#define LIF_PG(NI)                                                                                           \
+    do {                                                                                                     \
+        hipLaunchKernelGGL((k_predict_gate<T, NI>), dim3(grid), dim3(256), 0, s, (const T*)L->buf.A, L->buf.b,   \
+                           (const T*)x, c.d_model, c.d_ffn, c.threshold, masks, L->gact, L->st);                 \
+        if (step_mask != masks)                                                                              \
+            hipMemcpyAsync(step_mask, masks, c.d_ffn / 8, hipMemcpyDeviceToDevice, s);                        \
+    } while (0)
+    if (ni <= 1) LIF_PG(1);
+    else if (ni <= 2) LIF_PG(2);
+    else if (ni <= 4) LIF_PG(4);
+    else if (ni <= 8) LIF_PG(8);
+    else if (ni <= 9) LIF_PG(9);
+    else if (ni <= 12) LIF_PG(12);
+    else LIF_PG(16);
+#undef LIF_PG
+}
+
 template <typename T, bool GLU>
 void launch_ffn_up(lif_layer* L, const void* x, int batch, hipStream_t s) {
     const lif_config& c = L->cfg;
@@ -168,7 +199,8 @@ void launch_ffn_up(lif_layer* L, const void* x, int batch, hipStream_t s) {
     const size_t shm = batch == 1 ? 0 : (size_t)batch * c.d_model * sizeof(T);
 #define LIF_UP_X(NI, XREG)                                                                                   \
     hipLaunchKernelGGL((k_ffn_up<T, NI, GLU, XREG>), dim3(grid), dim3(256), shm, s, (const T*)L->buf.matrix,    \
-                       L->buf.bias, (const T*)x, L->h, c.d_model, batch, c.capacity_rows, L->row_elems, spec, L->st)
+                       L->buf.bias, (const T*)x, L->h, c.d_model, batch, c.capacity_rows, L->row_elems, spec,     \
+                       L->buf.pointers, L->gact, c.d_ffn, L->st)
 #define LIF_UP(NI) do { if (batch == 1) LIF_UP_X(NI, true); else LIF_UP_X(NI, false); } while (0)
     if (ni <= 1) LIF_UP(1);
     else if (ni <= 2) LIF_UP(2);
@@ -224,7 +256,7 @@ void launch_load_up(lif_layer* L, const void* x, const int32_t* added, hipStream
     hipLaunchKernelGGL((k_load_up<T, NI, GLU>), dim3(load_wgs + up_blocks), dim3(256), 0, s,                      \
                        (T*)L->buf.matrix, L->buf.pointers, L->buf.bias, (const T*)L->host_alias, L->buf.b, added, \
                        L->move_dst, L->row_elems, c.d_ffn, c.d_model, c.capacity_rows, (const T*)x, L->h,         \
-                       L->h_new, L->stamp, spec, load_wgs, L->st)
+                       L->h_new, L->stamp, spec, load_wgs, L->gact, L->st)
     if (ni <= 1) LIF_LU(1);
     else if (ni <= 2) LIF_LU(2);
     else if (ni <= 4) LIF_LU(4);
@@ -262,10 +294,10 @@ int lif_create(const lif_config* cfg, const lif_buffers* buf, lif_layer** out) {
     *out = nullptr;
     if (!config_ok(cfg, &why)) return fail(LIF_INVALID_ARG, "invalid config: %s", why);
     if (!buf) return fail(LIF_INVALID_ARG, "buffers are null");
-    if (!buf->A || !buf->B || !buf->b || !buf->host_bundles || !buf->matrix || !buf->pointers || !buf->bias ||
+    if (!buf->A || (!buf->B && cfg->predictor != LIF_PRED_GATE) || !buf->b || !buf->host_bundles || !buf->matrix || !buf->pointers || !buf->bias ||
         !buf->workspace)
         return fail(LIF_INVALID_ARG, "a required buffer is null");
-    const void* ptrs[] = {buf->A, buf->B, buf->host_bundles, buf->matrix};
+    const void* ptrs[] = {buf->A, buf->B ? buf->B : buf->A, buf->host_bundles, buf->matrix};
     for (const void* p : ptrs)
         if ((uintptr_t)p % 16) return fail(LIF_INVALID_ARG, "A, B, host_bundles and matrix must be 16-byte aligned");
     if ((uintptr_t)buf->workspace % 256) return fail(LIF_INVALID_ARG, "workspace must be 256-byte aligned");
@@ -292,6 +324,7 @@ int lif_create(const lif_config* cfg, const lif_buffers* buf, lif_layer** out) {
     L->ypart = (float*)(ws + lay.ypart);
     L->h_new = (float*)(ws + lay.h_new);
     L->stamp = (int32_t*)(ws + lay.stamp);
+    L->gact = cfg->predictor == LIF_PRED_GATE ? (float*)(ws + lay.gact) : nullptr;
     L->row_elems = (size_t)(cfg->glu ? 3 : 2) * cfg->d_model;
     L->row_bytes = L->row_elems * elem_bytes(*cfg);
     L->window_pending = false;
@@ -327,8 +360,14 @@ int lif_predict(lif_layer* L, const void* x_dev, int32_t batch, uint8_t* masks_d
     if ((uintptr_t)x_dev % 16) return fail(LIF_INVALID_ARG, "x must be 16-byte aligned");
     if (batch > 1 && masks_dev == step_mask_dev) return fail(LIF_INVALID_ARG, "step mask must not alias the masks when batch > 1");
     hipStream_t s = (hipStream_t)stream;
-    if (L->cfg.dtype == LIF_F32) launch_predict<float>(L, x_dev, batch, masks_dev, step_mask_dev, s);
-    else launch_predict<_Float16>(L, x_dev, batch, masks_dev, step_mask_dev, s);
+    if (L->cfg.predictor == LIF_PRED_GATE) {
+        if (L->cfg.dtype == LIF_F32) launch_predict_gate<float>(L, x_dev, masks_dev, step_mask_dev, s);
+        else launch_predict_gate<_Float16>(L, x_dev, masks_dev, step_mask_dev, s);
+    } else if (L->cfg.dtype == LIF_F32) {
+        launch_predict<float>(L, x_dev, batch, masks_dev, step_mask_dev, s);
+    } else {
+        launch_predict<_Float16>(L, x_dev, batch, masks_dev, step_mask_dev, s);
+    }
     return check_launch();
 }
 

@@ -29,11 +29,16 @@ namespace lif {
 // was told how many rows to expect and has sized the grid to that many waves.
 // `block` / `nblocks`: index and count of the workgroups that share this role; `n_ptr`: device
 // address of the number of rows to cover (num_used, or the rows kept by a pending deletion).
+// `gact` (may be null, plain bundles only): per-neuron gate activations relu(gate_i . x + b_i) written by the
+// gate predictor (Appendix, Llama 2, "Alternative approaches": the resident gate projection is the predictor);
+// the activation of slot s is then gact[pointers[s]] * (up_s . x).  gact_n = d_ffn bounds the lookup.
 template <typename T, int NI, bool GLU, bool XREG>
 __device__ __forceinline__ void ffn_up_role(const T* __restrict__ matrix, const float* __restrict__ bias,
                                             const T* __restrict__ x, float* __restrict__ h, int d, int batch,
                                             int capacity, size_t row_elems, int spec, int block, int nblocks,
-                                            const int32_t* __restrict__ n_ptr, const DevState* __restrict__ st) {
+                                            const int32_t* __restrict__ n_ptr, const int32_t* __restrict__ pointers,
+                                            const float* __restrict__ gact, int gact_n,
+                                            const DevState* __restrict__ st) {
     using V = typename Vec<T>::type;
     constexpr int VE = Vec<T>::N;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
@@ -68,7 +73,7 @@ __device__ __forceinline__ void ffn_up_role(const T* __restrict__ matrix, const 
                 u[it] = in ? row[idx] : V(0);
             }
         }
-        if (ok) bs = bias[gw];
+        if (ok) bs = gact ? gact[min(max(pointers[gw], 0), gact_n - 1)] : bias[gw];
     }
     const int err = st->error;
     const int n = *n_ptr;
@@ -93,7 +98,7 @@ __device__ __forceinline__ void ffn_up_role(const T* __restrict__ matrix, const 
                     u[it] = in ? row[idx] : V(0);
                 }
             }
-            bs = bias[s];
+            bs = gact ? gact[min(max(pointers[s], 0), gact_n - 1)] : bias[s];
         }
         for (int b = 0; b < (XREG ? 1 : batch); ++b) {
             float du = 0.f, dg = 0.f;
@@ -114,6 +119,8 @@ __device__ __forceinline__ void ffn_up_role(const T* __restrict__ matrix, const 
             if (GLU) {
                 dg = wave_sum(dg);
                 act = fmaxf(dg + bs, 0.f) * du;
+            } else if (gact) {
+                act = bs * du;                        // resident gate: bs = relu(gate . x + bias) from the predictor
             } else {
                 act = fmaxf(du + bs, 0.f);
             }
@@ -126,9 +133,10 @@ template <typename T, int NI, bool GLU, bool XREG>
 __global__ __launch_bounds__(256) void k_ffn_up(const T* __restrict__ matrix, const float* __restrict__ bias,
                                                 const T* __restrict__ x, float* __restrict__ h, int d, int batch,
                                                 int capacity, size_t row_elems, int spec,
-                                                const DevState* __restrict__ st) {
+                                                const int32_t* __restrict__ pointers, const float* __restrict__ gact,
+                                                int gact_n, const DevState* __restrict__ st) {
     ffn_up_role<T, NI, GLU, XREG>(matrix, bias, x, h, d, batch, capacity, row_elems, spec, blockIdx.x, gridDim.x,
-                                  &st->num_used, st);
+                                  &st->num_used, pointers, gact, gact_n, st);
 }
 
 constexpr int kXcds = 8;            // accelerator complex dies of an MI355X, each with a private L2

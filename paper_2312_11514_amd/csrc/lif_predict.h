@@ -213,4 +213,57 @@ __global__ __launch_bounds__(256) void k_predict_mask(const T* __restrict__ B, c
     if (tid < kMaskCols && n0 < F && !err) step_mask[n0 >> 3] = or_byte;
 }
 
+// Gate projection as the predictor (Appendix, Llama 2, "Alternative approaches"): the gate matrix stays
+// resident and  a_i = gate_i . x + b_i  decides exactly which neurons fire (mask bit = a_i > theta); the same
+// pass leaves relu(a_i) per neuron for the FFN, so bundles hold only up row | down column.
+// One wave per group of 8 neurons (one mask byte): 16-byte loads along the row, fp64 accumulation (bit-exact
+// decision), wave reduction.  grid-stride over F / 8 groups, block = 256.  NI as in the FFN kernels.
+template <typename T, int NI>
+__global__ __launch_bounds__(256) void k_predict_gate(const T* __restrict__ Wg, const float* __restrict__ b,
+                                                      const T* __restrict__ x, int d, int F, float theta,
+                                                      uint8_t* __restrict__ mask, float* __restrict__ gact,
+                                                      const DevState* __restrict__ st) {
+    using V = typename Vec<T>::type;
+    constexpr int VE = Vec<T>::N;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int nvec = d / VE;
+    const int gw = blockIdx.x * 4 + (tid >> 6), nw = gridDim.x * 4;
+    const V* xv = reinterpret_cast<const V*>(x);
+    V xr[NI];
+#pragma unroll
+    for (int it = 0; it < NI; ++it) {
+        const int idx = it * 64 + lane;
+        xr[it] = (idx < nvec) ? xv[idx] : V(0);
+    }
+    if (st->error) return;
+    const double th = (double)theta;
+    for (int grp = gw; grp * 8 < F; grp += nw) {
+        unsigned byte = 0;
+        float keep_act = 0.f;
+#pragma unroll 2
+        for (int e = 0; e < 8; ++e) {
+            const int i = grp * 8 + e;
+            const V* row = reinterpret_cast<const V*>(Wg + (size_t)i * d);
+            V g[NI];
+#pragma unroll
+            for (int it = 0; it < NI; ++it) {
+                const int idx = it * 64 + lane;
+                g[it] = (idx < nvec) ? row[idx] : V(0);
+            }
+            double acc = 0.0;
+#pragma unroll
+            for (int it = 0; it < NI; ++it)
+#pragma unroll
+                for (int q = 0; q < VE; ++q) acc = __builtin_fma((double)g[it][q], (double)xr[it][q], acc);
+#pragma unroll
+            for (int msk = 32; msk >= 1; msk >>= 1) acc += __shfl_xor(acc, msk, kWave);
+            const double a = acc + (double)b[i];
+            if (a > th) byte |= 1u << e;
+            if (lane == e) keep_act = (float)(a > 0.0 ? a : 0.0);
+        }
+        if (lane == 0) mask[grp] = (uint8_t)byte;
+        if (lane < 8) gact[grp * 8 + lane] = keep_act;
+    }
+}
+
 }  // namespace lif

@@ -41,7 +41,8 @@ __device__ __forceinline__ void load_role(T* __restrict__ matrix, int32_t* __res
                                           const float* __restrict__ b, const int32_t* __restrict__ added,
                                           const int32_t* __restrict__ move_dst, size_t row_elems, int F, int d,
                                           int capacity, const T* __restrict__ x, float* __restrict__ h_new,
-                                          int32_t* __restrict__ stamp, int wave_id, int nwaves, DevState* st) {
+                                          int32_t* __restrict__ stamp, const float* __restrict__ gact, int wave_id,
+                                          int nwaves, DevState* st) {
     using V = typename Vec<T>::type;
     constexpr int VE = Vec<T>::N;
     constexpr int G = GLU ? 3 : 2;
@@ -76,10 +77,15 @@ __device__ __forceinline__ void load_role(T* __restrict__ matrix, int32_t* __res
       if (ql >= a || nid_l >= F) nid_l = -1;
       int optr_l = -1;
       float obias_l = 0.f, nbias_l = 0.f;
+      float ogate_l = 0.f, ngate_l = 0.f;                // resident-gate activations of the moved / new neuron
       if (ql < items) {
           optr_l = pointers[n2 + ql];
           obias_l = bias[n2 + ql];
           if (nid_l >= 0) nbias_l = b[nid_l];
+          if (gact) {
+              if (nid_l >= 0) ngate_l = gact[nid_l];
+              if (optr_l >= 0 && optr_l < F) ogate_l = gact[optr_l];
+          }
       }
       const int nitems = min(kWave, (items - q0 + nwaves - 1) / nwaves);
       // Software pipeline over the items of this wave: the reads of item j+1 are requested as soon
@@ -113,6 +119,7 @@ __device__ __forceinline__ void load_role(T* __restrict__ matrix, int32_t* __res
         const int32_t old_ptr = __shfl(optr_l, j, kWave);
         const float old_bias = __shfl(obias_l, j, kWave);
         const float new_bias = __shfl(nbias_l, j, kWave);
+        const float old_gate = __shfl(ogate_l, j, kWave), new_gate = __shfl(ngate_l, j, kWave);
         float mdu = 0.f, mdg = 0.f, hdu = 0.f, hdg = 0.f;
         if (dst >= 0) {                                   // wave-uniform
 #pragma unroll
@@ -170,6 +177,8 @@ __device__ __forceinline__ void load_role(T* __restrict__ matrix, int32_t* __res
             if (GLU) {
                 const float dg = wave_sum(mdg);
                 act = fmaxf(dg + old_bias, 0.f) * du;
+            } else if (gact) {
+                act = old_gate * du;
             } else {
                 act = fmaxf(du + old_bias, 0.f);
             }
@@ -186,6 +195,8 @@ __device__ __forceinline__ void load_role(T* __restrict__ matrix, int32_t* __res
             if (GLU) {
                 const float dg = wave_sum(hdg);
                 act = fmaxf(dg + new_bias, 0.f) * du;
+            } else if (gact) {
+                act = new_gate * du;
             } else {
                 act = fmaxf(du + new_bias, 0.f);
             }
@@ -214,18 +225,18 @@ __global__ __launch_bounds__(256) void k_load_up(T* __restrict__ matrix, int32_t
                                                  const int32_t* __restrict__ move_dst, size_t row_elems, int F, int d,
                                                  int capacity, const T* __restrict__ x, float* __restrict__ h,
                                                  float* __restrict__ h_new, int32_t* __restrict__ stamp, int spec,
-                                                 int load_wgs, DevState* st) {
+                                                 int load_wgs, const float* __restrict__ gact, DevState* st) {
     if ((int)blockIdx.x < load_wgs) {
         const int w = threadIdx.x >> 6;
         if (w >= kStepLoadWaves) return;
         load_role<T, NI, GLU>(matrix, pointers, bias, host, b, added, move_dst, row_elems, F, d, capacity, x, h_new, stamp,
-                              blockIdx.x * kStepLoadWaves + w, load_wgs * kStepLoadWaves, st);
+                              gact, blockIdx.x * kStepLoadWaves + w, load_wgs * kStepLoadWaves, st);
     } else {
 #ifdef LIF_EXPERIMENT_NO_UP
         return;
 #endif
         ffn_up_role<T, NI, GLU, true>(matrix, bias, x, h, d, 1, capacity, row_elems, spec, blockIdx.x - load_wgs,
-                                      gridDim.x - load_wgs, &st->n_base, st);
+                                      gridDim.x - load_wgs, &st->n_base, pointers, gact, F, st);
     }
 }
 

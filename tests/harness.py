@@ -24,11 +24,14 @@ class GpuLayer:
         self.tdtype = torch.float32 if w.dtype == "f32" else torch.float16
         up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
         self.host = torch.from_numpy(L.bundles).pin_memory()
+        gate = w.gate_resident
         self.layer = lif.Layer(
             d_model=w.d_model, d_ffn=w.d_ffn, rank=w.rank, window_k=w.window_k,
-            capacity_rows=capacity or w.capacity_rows, max_batch=max_batch or w.batch, glu=w.glu,
-            dtype=w.dtype, ffn_mode=ffn_mode, shrink_window=(shrink or w.shrink), threshold=L.theta,
-            A=up(L.A), B=up(L.B), c=up(L.c) if use_c else None, b=up(L.b), host_bundles=self.host)
+            capacity_rows=capacity or w.capacity_rows, max_batch=max_batch or w.batch,
+            glu=(w.glu and not gate), dtype=w.dtype, ffn_mode=ffn_mode, shrink_window=(shrink or w.shrink),
+            predictor=lif.PRED_GATE if gate else lif.PRED_LOWRANK, threshold=L.theta,
+            A=up(L.w_gate if gate else L.A), B=None if gate else up(L.B),
+            c=up(L.c) if (use_c and not gate) else None, b=up(L.b), host_bundles=self.host)
         self.y = torch.zeros((max_batch or w.batch, w.d_model), dtype=self.tdtype, device=dev)
 
     def upload_x(self, x):

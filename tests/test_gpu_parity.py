@@ -14,8 +14,9 @@ pytestmark = pytest.mark.gpu
 
 
 def make_oracle(w, L, capacity=None, k=None):
-    return O.OracleLayer(w.d_model, w.d_ffn, k or w.window_k, capacity or w.capacity_rows, w.glu,
-                         L.A, L.B, L.c, L.theta, L.b, L.bundles)
+    gate = w.gate_resident
+    return O.OracleLayer(w.d_model, w.d_ffn, k or w.window_k, capacity or w.capacity_rows, w.glu and not gate,
+                         L.A, L.B, L.c, L.theta, L.b, L.bundles, w_gate=L.w_gate if gate else None)
 
 
 def run_stream(w, L, X, ffn_mode=0, check_every=1, api="calls"):
@@ -431,3 +432,46 @@ def test_speculative_verify_passes_token_granular_window(glu, dtype, d_model):
         lay.step(xd, gpu.y, 1)
         assert lay.state()["num_used"] == ref["num_used"]
         assert rel_l2(gpu.y[0].cpu().numpy(), ref["y"]) <= REL_L2_TOL
+
+
+# ----------------------------------------------------------------------------- resident gate as predictor
+@pytest.mark.parametrize("api", ["calls", "step"])
+@pytest.mark.parametrize("ffn_mode", [0, 1])
+@pytest.mark.parametrize("dtype,d_model", [("f16", 568), ("f16", 256), ("f32", 256)])
+def test_gate_predictor_small_shapes(dtype, d_model, ffn_mode, api):
+    """Gate projection resident in HBM as the predictor; bundles = up | down (two vectors)."""
+    w = wl.scaled(wl.WORKLOADS["C1"], name="gate", d_model=d_model, d_ffn=1096, rank=8, window_k=3,
+                  p_active=0.08, dtype=dtype, glu=True, gate_resident=True, tokens=24, capacity_rows=700)
+    L = wl.make_layer(w)
+    X = wl.make_inputs(w)
+    stats = run_stream(w, L, X, ffn_mode, api=api)
+    assert any(s["moved"] > 0 for s in stats) and any(s["removed"] > 0 for s in stats)
+    # exact predictor: the sparse output is the dense gated FFN
+    from tests.harness import GpuLayer, rel_l2
+    gpu = GpuLayer(w, L, ffn_mode=ffn_mode)
+    for x in X[:6]:
+        gpu.layer.step(gpu.upload_x(x), gpu.y, 1)
+        dense = O.dense_ffn(L.w_up, L.w_down, L.b, x, w_gate=L.w_gate)
+        assert rel_l2(gpu.y[0].cpu().numpy(), dense) <= 1e-3
+
+
+def test_n4_llama_shape_gate_predictor():
+    """Llama-2-7B FFN shape with the gate resident, the launch configuration bench.py times for N4."""
+    w = wl.WORKLOADS["N4"]
+    L = wl.cached_layer("N4")
+    X = wl.make_inputs(w, tokens=32)
+    stats = run_stream(w, L, X, check_every=8, api="step")
+    print("N4 max rel-L2 %.2e, rows %.0f" % (max(s["err"] for s in stats), np.mean([s["n"] for s in stats[10:]])))
+
+
+def test_gate_predictor_rejects_batches_and_gated_bundles():
+    import paper_2312_11514_amd as lif
+    from tests.harness import GpuLayer
+    w = wl.scaled(wl.WORKLOADS["C1"], name="gate", glu=True, gate_resident=True, tokens=2)
+    L = wl.make_layer(w)
+    with pytest.raises(Exception):
+        GpuLayer(w, L, max_batch=2)
+    gpu = GpuLayer(w, L)
+    x2 = gpu.upload_x(np.stack([wl.make_inputs(w)[0]] * 2))
+    with pytest.raises(Exception):
+        gpu.layer.predict(x2, 2)

@@ -43,7 +43,7 @@ def test_bundle_size_matches_paper_constants():
     assert O.bundle_bytes(4096, 2) == 2 * (4096 * 2)
     assert O.bundle_bytes(4096, 2, glu=True) == 3 * (4096 * 2)
     for name, w in wl.WORKLOADS.items():
-        assert w.bundle_bytes == O.bundle_bytes(w.d_model, w.elem_bytes, w.glu)
+        assert w.bundle_bytes == O.bundle_bytes(w.d_model, w.elem_bytes, w.glu and not w.gate_resident)
 
 
 # ----------------------------------------------------------------------------- FFN
@@ -474,3 +474,51 @@ def test_window_tokens_reduces_to_single_pushes():
     assert (c.active_set() == (np.logical_or.reduce(held) | M[0] | M[1])).all()
     c.push_tokens(np.zeros((1, F), bool), 0)                       # the transient masks are gone again
     assert (c.active_set() == np.logical_or.reduce(held)).all()
+
+
+# ----------------------------------------------------------------------------- resident gate as predictor
+def _gate_layer(g, theta, k=2):
+    gate, up, down = (np.array(g[n], np.float32) for n in ("gate", "up", "down"))
+    b = np.array(g["b"], np.float32)
+    bundles = np.concatenate([up, down], axis=1)
+    return O.OracleLayer(2, 3, k, 3, False, None, None, None, theta, b, bundles, w_gate=gate)
+
+
+def test_gate_predictor_hand_worked():
+    """Appendix (Llama 2, alternative approaches): mask from the resident gate, bundles = up | down."""
+    g = golden("gate_tiny.json")
+    x = np.array(g["x"])
+    for case in g["cases"]:
+        lay = _gate_layer(g, case["theta"])
+        r = lay.step(x)
+        assert r["masks"].astype(int).tolist() == case["mask"]
+        assert r["added"].tolist() == [i for i, m in enumerate(case["mask"]) if m]
+        assert r["loaded"] == sum(case["mask"]) * 2 * 2 * 4           # up | down of d = 2 fp32 values
+        np.testing.assert_allclose(r["y"], case["y"], rtol=0, atol=1e-12)
+    # second token at theta = 0: neurons 0 and 1 fire (a = 2.5, 2.0); neuron 0 stays cached, 1 is loaded
+    lay = _gate_layer(g, 0.0)
+    lay.step(x)
+    r = lay.step(np.array(g["second_x"]))
+    assert r["added"].tolist() == [1] and r["removed"].tolist() == []
+    np.testing.assert_allclose(lay.gate_act, np.maximum(g["second_a"], 0), rtol=0, atol=1e-12)
+    np.testing.assert_allclose(r["y"], g["second_y_theta0"], rtol=0, atol=1e-12)
+
+
+def test_gate_predictor_reproduces_the_dense_gated_ffn():
+    """The gate decides exactly which neurons fire, so at theta = 0 the windowed sparse path equals the
+    dense gated FFN on every token (cached neurons that do not fire contribute exactly zero), and the
+    bytes moved per new neuron are two thirds of the gate | up | down bundle."""
+    w = wl.scaled(wl.WORKLOADS["C1"], name="gate", d_model=64, d_ffn=192, rank=8, window_k=3, p_active=0.1,
+                  glu=True, gate_resident=True, tokens=12, capacity_rows=192)
+    wfull = wl.scaled(w, gate_resident=False)
+    L = wl.make_layer(w)
+    assert L.bundles.shape[1] == 2 * w.d_model and w.bundle_bytes * 3 == wfull.bundle_bytes * 2
+    assert (L.bundles[:, :w.d_model] == L.w_up).all() and (L.bundles[:, w.d_model:] == L.w_down).all()
+    lay = O.OracleLayer(w.d_model, w.d_ffn, w.window_k, w.capacity_rows, False, None, None, None, 0.0, L.b,
+                        L.bundles, w_gate=L.w_gate)
+    for x in wl.make_inputs(w):
+        r = lay.step(x)
+        assert (r["masks"] == O.true_mask(L.w_gate, L.b, x)).all()
+        dense = O.dense_ffn(L.w_up, L.w_down, L.b, x, w_gate=L.w_gate)
+        np.testing.assert_allclose(r["y"], dense, rtol=1e-11, atol=1e-13)
+        assert r["loaded"] == len(r["added"]) * w.bundle_bytes

@@ -40,6 +40,8 @@ class Workload:
     layers: int = 1
     shrink: bool = False # dynamic window: drop the oldest masks instead of overflowing
     spec_keep: int = 0   # > 0: speculative verification passes of `batch` consecutive tokens, the first spec_keep kept
+    gate_resident: bool = False  # gated FFN whose gate projection stays in HBM and serves as the predictor;
+                                 # bundle = up row | down column
 
     @property
     def np_dtype(self):
@@ -51,7 +53,7 @@ class Workload:
 
     @property
     def vectors_per_bundle(self) -> int:
-        return 3 if self.glu else 2
+        return 3 if (self.glu and not self.gate_resident) else 2
 
     @property
     def bundle_elems(self) -> int:
@@ -79,6 +81,9 @@ WORKLOADS = {
     "N1": Workload("N1", 4096, 16384, 128, 8, 0.10, 0.9, "f16", False, 256, 1, 4096, shrink=True),
     # speculative verification (Section 4.3): passes of lambda + 1 = 5 consecutive tokens of one stream, 4 of
     # them accepted (acceptance ratio 0.8), window of the last 5 kept tokens; the next pass starts after them
+    # Llama-2-7B-shaped gated layer with the gate projection resident as the (exact) predictor (appendix on
+    # Llama 2, alternative approaches): only up | down bundles move
+    "N4": Workload("N4", 4096, 11008, 256, 4, 0.10, 0.9, "f16", True, 256, 1, 11008, gate_resident=True),
     "N2": Workload("N2", 4096, 16384, 128, 5, 0.03, 0.9, "f16", False, 256, 5, 8192, spec_keep=4),
 }
 
@@ -166,7 +171,7 @@ def make_layer(w: Workload, layer: int = 0, structured: bool = False,
     zq_pred = norm.ppf(1.0 - min(w.p_active * overpredict, 0.999))
     c = (-zq_pred * colnorm).astype(np.float32)
 
-    parts = ([w_gate] if w.glu else []) + [w_up, w_down]
+    parts = ([w_gate] if (w.glu and not w.gate_resident) else []) + [w_up, w_down]
     bundles = np.ascontiguousarray(np.concatenate(parts, axis=1))
     return LayerData(w_up, w_down, w_gate, b, A, B, c, 0.0, bundles)
 
@@ -191,7 +196,7 @@ def make_layer_variant(base: LayerData, w: Workload, layer: int) -> LayerData:
     w_gate = None if base.w_gate is None else base.w_gate[pi] * sgn
     A = base.A * sgn[:, None]
     B = np.ascontiguousarray(base.B[:, pi])
-    parts = ([w_gate] if w.glu else []) + [w_up, w_down]
+    parts = ([w_gate] if (w.glu and not w.gate_resident) else []) + [w_up, w_down]
     bundles = np.ascontiguousarray(np.concatenate(parts, axis=1))
     return LayerData(w_up, w_down, w_gate, base.b[pi].copy(), A, B, base.c[pi].copy(), base.theta, bundles)
 
