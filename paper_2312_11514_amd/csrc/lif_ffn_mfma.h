@@ -124,7 +124,6 @@ __global__ __launch_bounds__(256) void k_ffn_down_batched(const T* __restrict__ 
     constexpr int VE = Vec<T>::N;
     constexpr int PER = kDownBTile / 256;
     constexpr int RG = 256 / kDownBLanes;            // row groups per workgroup
-    constexpr int RGW = 64 / kDownBLanes;            // row groups per wave
     __shared__ int list[kDownBTile];
     __shared__ float hv[BT][kDownBTile];
     __shared__ int wave_tot[4];
@@ -217,7 +216,6 @@ __global__ __launch_bounds__(256) void k_ffn_down_batched(const T* __restrict__ 
                 out[e] = ((red[0][l2][b][e] + red[1][l2][b][e]) + red[2][l2][b][e]) + red[3][l2][b][e];
         }
     }
-    (void)RGW;
 }
 
 // y[t][j] = sum over the chunks, in chunk order, rounded once to the element type.

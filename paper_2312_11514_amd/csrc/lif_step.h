@@ -232,9 +232,6 @@ __global__ __launch_bounds__(256) void k_load_up(T* __restrict__ matrix, int32_t
         load_role<T, NI, GLU>(matrix, pointers, bias, host, b, added, move_dst, row_elems, F, d, capacity, x, h_new, stamp,
                               gact, blockIdx.x * kStepLoadWaves + w, load_wgs * kStepLoadWaves, st);
     } else {
-#ifdef LIF_EXPERIMENT_NO_UP
-        return;
-#endif
         ffn_up_role<T, NI, GLU, true>(matrix, bias, x, h, d, 1, capacity, row_elems, spec, blockIdx.x - load_wgs,
                                       gridDim.x - load_wgs, &st->n_base, pointers, gact, F, st);
     }
