@@ -145,7 +145,7 @@ def sweep_chunk(args):
         bundle = 2 * d * 2
         rows = max(1, int(round(2.4e6 / bundle)))
         host = torch.from_numpy(rng.standard_normal((F, 2 * d), dtype=np.float32).astype(np.float16)).pin_memory()
-        A = torch.zeros((d, r), dtype=torch.float16, device=dev)
+        A = torch.zeros((r, d), dtype=torch.float16, device=dev)
         B = torch.zeros((r, F), dtype=torch.float16, device=dev)
         c = torch.zeros(F, device=dev)
         b = torch.zeros(F, device=dev)
@@ -169,6 +169,60 @@ def sweep_chunk(args):
     print(json.dumps({"sweep": "chunk size (bundle bytes) at ~2.4 MB per step", "rows": out}))
 
 
+def sweep_rows(args):
+    """Bandwidth of one lif_sparse_ffn call against the number of cached rows n (full-bundle mode reads n bundles,
+    skip mode reads the activation vector of every row and the down column of the rows that fire).  Shows where the
+    two FFN kernels leave the launch/latency regime: bytes grow with n, the fixed cost does not."""
+    import numpy as np
+    import torch
+    import workloads as wl
+    import paper_2312_11514_amd as lif
+    from tests.harness import GpuLayer
+    w0 = wl.WORKLOADS[args.workload]
+    w = wl.scaled(w0, capacity_rows=w0.d_ffn)
+    L = wl.make_layer(w)
+    X = wl.make_inputs(w) if w.batch == 1 else wl.make_batch_inputs(w)
+    rng = np.random.default_rng(1)
+    E, d, G = w.elem_bytes, w.d_model, w.vectors_per_bundle
+    out = []
+    for mode_name, mode in (("full", lif.FFN_FULL_BUNDLE), ("skip", lif.FFN_SKIP_DEAD)):
+        gpu = GpuLayer(w, L, ffn_mode=mode)
+        lay = gpu.layer
+        xd = gpu.upload_x(X[0])
+        n = 256
+        while n <= w.d_ffn:
+            ids = np.sort(rng.choice(w.d_ffn, n, replace=False))
+            lay.reset()
+            gpu.fill_cache(ids, L)
+            lay.set_expected_rows(n)
+            calls = 50
+            g = torch.cuda.CUDAGraph()
+            lay.sparse_ffn(xd, gpu.y, w.batch)
+            torch.cuda.synchronize()
+            with torch.cuda.graph(g):
+                for _ in range(calls):
+                    lay.sparse_ffn(xd, gpu.y, w.batch)
+            g.replay()
+            torch.cuda.synchronize()
+            c0 = lay.counters()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(4):
+                g.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            c1 = lay.counters()
+            us = e0.elapsed_time(e1) * 1e3 / (4 * calls)
+            active = (c1["ffn_active"] - c0["ffn_active"]) / (c1["ffn_calls"] - c0["ffn_calls"])
+            req = n * (G - 1) * d * E + (n if mode_name == "full" else active) * d * E
+            out.append({"mode": mode_name, "rows": n, "rows_active": active, "us_per_call": us,
+                        "requested_bytes": req, "GBs": req / us / 1e3, "frac_of_8TBs": req / us / 1e3 / 8000.0})
+            n *= 2
+        lay.close()
+        del gpu, lay
+    print(json.dumps({"sweep": "cached rows per lif_sparse_ffn call", "workload": describe(w), "rows": out}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -185,7 +239,7 @@ def main():
     ap.add_argument("--pmc-dir", default=None,
                     help="directory with the rocprofv3 --pmc outputs of this script; fills roofline.traffic")
     ap.add_argument("--no-hint", action="store_true", help="do not give the library the expected number of cached rows")
-    ap.add_argument("--sweep", default=None, choices=["k", "chunk"],
+    ap.add_argument("--sweep", default=None, choices=["k", "chunk", "rows"],
                     help="instead of the bench line: window-size sweep or chunk-size sweep (one JSON line each)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -197,6 +251,8 @@ def main():
         return sweep_window(args)
     if args.sweep == "chunk":
         return sweep_chunk(args)
+    if args.sweep == "rows":
+        return sweep_rows(args)
 
     import torch
     import workloads as wl

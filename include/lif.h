@@ -82,8 +82,13 @@ typedef struct lif_config {
 
 typedef struct lif_buffers {
     /* predictor (device, read-only): logits = (x A) B + c                               */
-    const void* A;          /* [d_model x rank] row-major, E                              */
-    const void* B;          /* [rank x d_ffn]  row-major, E                               */
+    const void* A;          /* LIF_PRED_LOWRANK: the first predictor matrix stored with the */
+                            /* contraction dimension contiguous, [rank x d_model] row-major, E */
+                            /* (row j = column j of the paper's d_model x rank matrix);     */
+                            /* LIF_PRED_GATE: the gate projection [d_ffn x d_model]         */
+                            /* row-major, E (row i = gate weights of neuron i)              */
+    const void* B;          /* [rank x d_ffn] row-major, E; unused (may be NULL) with       */
+                            /* LIF_PRED_GATE                                                */
     const float* c;         /* [d_ffn] per-neuron offset, fp32; may be NULL (= 0)         */
     /* bias of the ReLU'd projection per original neuron (device, read-only)             */
     const float* b;         /* [d_ffn] fp32                                               */

@@ -105,7 +105,8 @@ def _stream():
 class Layer:
     """One FFN layer behind the C ABI.  Owns (through torch) every array the library uses.
 
-    A, B, c, b: device tensors; host_bundles: pinned CPU tensor [F, G*d].  The four hot
+    A [rank, d_model] (or the gate projection [d_ffn, d_model]), B [rank, d_ffn], c, b: device tensors;
+    host_bundles: pinned CPU tensor [F, G*d].  The four hot
     calls enqueue on torch's current stream and return immediately.
     """
 

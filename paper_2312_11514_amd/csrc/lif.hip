@@ -41,7 +41,6 @@ struct Layout {
 
 int elem_bytes(const lif_config& c) { return c.dtype == LIF_F32 ? 4 : 2; }
 int vec_elems(const lif_config& c) { return 16 / elem_bytes(c); }
-int xa_chunks(const lif_config& c) { return (c.d_model + kXaRows - 1) / kXaRows; }
 int ring_words(const lif_config& c) { return (c.d_ffn + 63) / 64; }
 
 bool config_ok(const lif_config* c, const char** why) {
@@ -53,7 +52,7 @@ bool config_ok(const lif_config* c, const char** why) {
     if ((c->d_model / ve + 63) / 64 > 16) return (*why = "d_model too large (at most 1024 16-byte vectors)", false);
     if (c->d_ffn <= 0 || c->d_ffn % 8 || c->d_ffn > kScanThreads * kMaxSpan) return (*why = "d_ffn must be a multiple of 8, at most 65536", false);
     if (c->predictor != LIF_PRED_GATE &&
-        (c->rank <= 0 || c->rank % ve || c->rank / ve > 256 || c->rank > 2048)) return (*why = "rank", false);
+        (c->rank <= 0 || c->rank % ve || c->rank > 2048)) return (*why = "rank", false);
     if (c->window_k < 1 || c->window_k > 256) return (*why = "window_k must be in 1..256", false);
     if (c->capacity_rows < 1 || c->capacity_rows > kScanThreads * kMaxSpan) return (*why = "capacity_rows must be in 1..65536", false);
     if (c->max_batch < 1 || c->max_batch > 8) return (*why = "max_batch must be in 1..8", false);
@@ -76,15 +75,15 @@ Layout make_layout(const lif_config& c) {
     off = off + (size_t)c.window_k * ring_words(c) * 8;     // ... directly followed by the bitmap of the cached set
     off = align_up(off + (size_t)ring_words(c) * 8, 256);
     L.tpart = off;
-    off = align_up(off + sizeof(double) * c.max_batch * xa_chunks(c) * std::max(c.rank, 0), 256);
+    off = align_up(off + sizeof(double) * c.max_batch * std::max(c.rank, 0), 256);
     L.move_dst = off;
     off = align_up(off + sizeof(int32_t) * c.capacity_rows, 256);
     L.hole_list = off;
     off = align_up(off + sizeof(int32_t) * c.capacity_rows, 256);
     L.h = off;
     off = align_up(off + sizeof(float) * c.max_batch * c.capacity_rows, 256);
-    L.ypart = off;                     // per-chunk partial outputs of the batched down projection
-    off = align_up(off + (c.max_batch > 1 ? sizeof(float) * kDownChunks * c.max_batch * c.d_model : 0), 256);
+    L.ypart = off;                     // per-chunk partial outputs of the down projection
+    off = align_up(off + sizeof(float) * kDownChunksMax * c.max_batch * c.d_model, 256);
     L.h_new = off;                     // activations written by the fused load kernel (single-token steps)
     off = align_up(off + sizeof(float) * c.capacity_rows, 256);
     L.stamp = off;                     // step number at which h_new[slot] was written
@@ -143,17 +142,26 @@ struct Timed {
 template <typename T>
 int launch_predict(lif_layer* L, const void* x, int batch, uint8_t* masks, uint8_t* step_mask, hipStream_t s) {
     const lif_config& c = L->cfg;
-    const int nch = xa_chunks(c);
     {
         Timed t(L, LIF_K_PREDICT_XA, s);
-        hipLaunchKernelGGL((k_predict_xa<T>), dim3(nch, batch), dim3(256), 0, s, (const T*)x, (const T*)L->buf.A,
-                           L->tpart, c.d_model, c.rank, L->st);
+        const int ni = (c.d_model / Vec<T>::N + 63) / 64;
+#define LIF_XA(NI)                                                                                          \
+    hipLaunchKernelGGL((k_predict_xa<T, NI>), dim3((c.rank + 3) / 4, batch), dim3(256), 0, s, (const T*)x,       \
+                       (const T*)L->buf.A, L->tpart, c.d_model, c.rank, L->st)
+        if (ni <= 1) LIF_XA(1);
+        else if (ni <= 2) LIF_XA(2);
+        else if (ni <= 4) LIF_XA(4);
+        else if (ni <= 8) LIF_XA(8);
+        else if (ni <= 9) LIF_XA(9);
+        else if (ni <= 12) LIF_XA(12);
+        else LIF_XA(16);
+#undef LIF_XA
     }
     const int grid = (c.d_ffn + kMaskCols * 8 - 1) / (kMaskCols * 8);
     Timed t(L, LIF_K_PREDICT_MASK, s);
 #define LIF_MASK(BT)                                                                                        \
     hipLaunchKernelGGL((k_predict_mask<T, BT>), dim3(grid), dim3(256), sizeof(double) * BT * c.rank, s,          \
-                       (const T*)L->buf.B, L->buf.c, L->tpart, nch, c.rank, c.d_ffn, batch, c.threshold, masks,    \
+                       (const T*)L->buf.B, L->buf.c, L->tpart, c.rank, c.d_ffn, batch, c.threshold, masks,         \
                        step_mask, L->st)
     // tokens per pass over B: all of them when the partial sums fit LDS (BT * rank doubles <= 48 KiB)
     if (batch == 1 || c.rank > 1536) LIF_MASK(1);
@@ -194,7 +202,7 @@ void launch_ffn_up(lif_layer* L, const void* x, int batch, hipStream_t s) {
     const int ni = (nvec + 63) / 64;
     // one wave per row; with a row-count hint the grid is sized to it and the first pass is speculative
     const int spec = L->expected_rows > 0 ? 1 : 0;
-    const int grid = spec ? std::max(1, std::min(L->expected_rows, c.capacity_rows) / 4)
+    const int grid = spec ? std::min(kUpMaxWgs, std::max(1, std::min(L->expected_rows, c.capacity_rows) / 4))
                           : std::min((c.capacity_rows + 3) / 4, 512);
     const size_t shm = batch == 1 ? 0 : (size_t)batch * c.d_model * sizeof(T);
 #define LIF_UP_X(NI, XREG)                                                                                   \
@@ -214,33 +222,39 @@ void launch_ffn_up(lif_layer* L, const void* x, int batch, hipStream_t s) {
 #undef LIF_UP_X
 }
 
+template <typename T, int BT, bool SKIP, int LANES>
+void launch_ffn_down_as(lif_layer* L, int batch, void* y, hipStream_t s, bool use_new) {
+    const lif_config& c = L->cfg;
+    const int cols = LANES * Vec<T>::N;
+    int slices = (c.d_model + cols - 1) / cols;
+    if (LANES * 16 < 128) slices = (slices + kXcds - 1) / kXcds * kXcds;      // whole runs of slices per XCD
+    // workgroup rows: enough for the chunks of the expected number of rows (with some slack), else of the
+    // capacity; fewer than the chunks in use is still correct (a workgroup row then takes several chunks)
+    const int rows_hint = L->expected_rows > 0 ? std::min(c.capacity_rows, L->expected_rows + L->expected_rows / 8)
+                                               : c.capacity_rows;
+    const int wg_rows = down_chunks<BT, SKIP>(rows_hint);
+    const int down_off = (c.glu ? 2 : 1) * c.d_model;
+    hipLaunchKernelGGL((k_ffn_down<T, BT, SKIP, LANES>), dim3(slices, wg_rows), dim3(256), 0, s,
+                       (const T*)L->buf.matrix, L->h, use_new ? L->h_new : nullptr, use_new ? L->stamp : nullptr,
+                       (T*)y, L->ypart, c.d_model, batch, c.capacity_rows, L->row_elems, down_off, L->st);
+    if (wg_rows > 1)
+        hipLaunchKernelGGL((k_ffn_down_finish<T, BT, SKIP>), dim3((batch * c.d_model + 255) / 256), dim3(256), 0, s,
+                           L->ypart, (T*)y, c.d_model, batch, L->st);
+}
+
 template <typename T>
 void launch_ffn_down(lif_layer* L, int batch, void* y, hipStream_t s, bool use_new = false) {
-    const float* h_new = use_new ? L->h_new : nullptr;
-    const int32_t* stamp = use_new ? L->stamp : nullptr;
-    const lif_config& c = L->cfg;
-    const int cols = kDownLanes * Vec<T>::N;
-    const int grid = ((c.d_model + cols - 1) / cols + kXcds - 1) / kXcds * kXcds;   // whole runs of slices per XCD
-    const int colsb = kDownBLanes * Vec<T>::N;
-    const int gridb = (c.d_model + colsb - 1) / colsb;
-    const int down_off = (c.glu ? 2 : 1) * c.d_model;
-    const bool skip = c.ffn_mode == LIF_FFN_SKIP_DEAD;
-#define LIF_DOWN(BT, SKIP)                                                                                  \
-    hipLaunchKernelGGL((k_ffn_down<T, BT, SKIP>), dim3(grid), dim3(256), 0, s, (const T*)L->buf.matrix, L->h,  \
-                       h_new, stamp, (T*)y, c.d_model, batch, c.capacity_rows, L->row_elems, down_off, L->st)
-#define LIF_DOWNB(BT, SKIP)                                                                                 \
-    hipLaunchKernelGGL((k_ffn_down_batched<T, BT, SKIP>), dim3(gridb, kDownChunks), dim3(256), 0, s,           \
-                       (const T*)L->buf.matrix, L->h, L->ypart, c.d_model, batch, c.capacity_rows, L->row_elems, \
-                       down_off, L->st)
-    if (batch == 1) { if (skip) LIF_DOWN(1, true); else LIF_DOWN(1, false); }
-    else {
-        if (batch <= 4) { if (skip) LIF_DOWNB(4, true); else LIF_DOWNB(4, false); }
-        else { if (skip) LIF_DOWNB(8, true); else LIF_DOWNB(8, false); }
-        hipLaunchKernelGGL((k_ffn_down_finish<T>), dim3((batch * c.d_model + 255) / 256), dim3(256), 0, s, L->ypart,
-                           (T*)y, c.d_model, batch, L->st);
+    const bool skip = L->cfg.ffn_mode == LIF_FFN_SKIP_DEAD;
+    if (batch == 1) {
+        if (skip) launch_ffn_down_as<T, 1, true, kDownLanes1>(L, batch, y, s, use_new);
+        else launch_ffn_down_as<T, 1, false, kDownLanesN>(L, batch, y, s, use_new);
+    } else if (batch <= 4) {
+        if (skip) launch_ffn_down_as<T, 4, true, kDownLanesN>(L, batch, y, s, use_new);
+        else launch_ffn_down_as<T, 4, false, kDownLanesN>(L, batch, y, s, use_new);
+    } else {
+        if (skip) launch_ffn_down_as<T, 8, true, kDownLanesN>(L, batch, y, s, use_new);
+        else launch_ffn_down_as<T, 8, false, kDownLanesN>(L, batch, y, s, use_new);
     }
-#undef LIF_DOWNB
-#undef LIF_DOWN
 }
 
 template <typename T, bool GLU>
@@ -249,7 +263,7 @@ void launch_load_up(lif_layer* L, const void* x, const int32_t* added, hipStream
     const int nvec = c.d_model / Vec<T>::N;
     const int ni = (nvec + 63) / 64;
     const int spec = L->expected_rows > 0 ? 1 : 0;
-    const int up_blocks = spec ? std::max(1, std::min(L->expected_rows, c.capacity_rows) / 4)
+    const int up_blocks = spec ? std::min(kUpMaxWgs, std::max(1, std::min(L->expected_rows, c.capacity_rows) / 4))
                                : std::min((c.capacity_rows + 3) / 4, 512);
     const int load_wgs = (int)std::min<size_t>(64, std::max<size_t>(10, kStepInflightBytes / L->row_bytes));
 #define LIF_LU(NI)                                                                                            \

@@ -84,21 +84,41 @@ __device__ __forceinline__ void ffn_up_role(const T* __restrict__ matrix, const 
         __syncthreads();
     }
 
+    if (!spec && gw < n) {                            // not requested yet: load now that the count is known
+        const V* row = reinterpret_cast<const V*>(matrix + (size_t)gw * row_elems);
+#pragma unroll
+        for (int it = 0; it < NI; ++it) {
+            const int idx = it * 64 + lane;
+            const bool in = idx < nvec;
+            if (GLU) {
+                g[it] = in ? row[idx] : V(0);
+                u[it] = in ? row[nvec + idx] : V(0);
+            } else {
+                u[it] = in ? row[idx] : V(0);
+            }
+        }
+        bs = gact ? gact[min(max(pointers[gw], 0), gact_n - 1)] : bias[gw];
+    }
     for (int s = gw; s < n; s += nw) {
-        if (s != gw || !spec) {                       // not requested yet: load now that the count is known
-            const V* row = reinterpret_cast<const V*>(matrix + (size_t)s * row_elems);
+        // the next row of this wave is requested before the current one is reduced (when the grid is
+        // smaller than the row count, every wave keeps two rows in flight)
+        const int sn = s + nw;
+        V un[NI], gn[GLU ? NI : 1];
+        float bsn = 0.f;
+        if (sn < n) {
+            const V* row = reinterpret_cast<const V*>(matrix + (size_t)sn * row_elems);
 #pragma unroll
             for (int it = 0; it < NI; ++it) {
                 const int idx = it * 64 + lane;
                 const bool in = idx < nvec;
                 if (GLU) {
-                    g[it] = in ? row[idx] : V(0);
-                    u[it] = in ? row[nvec + idx] : V(0);
+                    gn[it] = in ? row[idx] : V(0);
+                    un[it] = in ? row[nvec + idx] : V(0);
                 } else {
-                    u[it] = in ? row[idx] : V(0);
+                    un[it] = in ? row[idx] : V(0);
                 }
             }
-            bs = gact ? gact[min(max(pointers[s], 0), gact_n - 1)] : bias[s];
+            bsn = gact ? gact[min(max(pointers[sn], 0), gact_n - 1)] : bias[sn];
         }
         for (int b = 0; b < (XREG ? 1 : batch); ++b) {
             float du = 0.f, dg = 0.f;
@@ -126,6 +146,14 @@ __device__ __forceinline__ void ffn_up_role(const T* __restrict__ matrix, const 
             }
             if (lane == 0) h[(size_t)b * capacity + s] = act;
         }
+        if (sn < n) {
+#pragma unroll
+            for (int it = 0; it < NI; ++it) {
+                u[it] = un[it];
+                if (GLU) g[it] = gn[it];
+            }
+            bs = bsn;
+        }
     }
 }
 
@@ -139,68 +167,110 @@ __global__ __launch_bounds__(256) void k_ffn_up(const T* __restrict__ matrix, co
                                   &st->num_used, pointers, gact, gact_n, st);
 }
 
-constexpr int kXcds = 8;            // accelerator complex dies of an MI355X, each with a private L2
-constexpr int kDownLanes = 4;       // lanes per column slice (4 x 16 B = 64 B of every down column)
-constexpr int kDownRg = 64;         // row groups per workgroup
-constexpr int kDownTile = 2048;     // cached rows compacted per pass
+#ifndef LIF_UP_MAX_WGS
+#define LIF_UP_MAX_WGS 1024
+#endif
+constexpr int kUpMaxWgs = LIF_UP_MAX_WGS;   // workgroups of the activation stage: beyond this, waves loop over rows (x stays in registers)
 
-// grid = ceil(d / (4 * VE)), block = 256 = 64 row groups x 4 lanes.
-// SKIP: rows whose activation is zero for every token of the batch are not read.
+constexpr int kXcds = 8;            // accelerator complex dies of an MI355X, each with a private L2
+constexpr int kDownTile = 2048;     // activations (rows x tokens) compacted per pass
+constexpr int kDownChunksMax = 32;  // row chunks of the down projection (partial outputs per chunk)
+#ifndef LIF_DOWN_LANES_1
+#define LIF_DOWN_LANES_1 4
+#endif
+#ifndef LIF_DOWN_LANES_N
+#define LIF_DOWN_LANES_N 8
+#endif
+constexpr int kDownLanes1 = LIF_DOWN_LANES_1;   // lanes per column slice, single token skipping dead rows (latency bound)
+constexpr int kDownLanesN = LIF_DOWN_LANES_N;   // ... when most rows are read: 8 x 16 B = one 128-byte line per row
+#ifndef LIF_DOWN_ROWS_SPARSE
+#define LIF_DOWN_ROWS_SPARSE 2048
+#endif
+#ifndef LIF_DOWN_ROWS_DENSE
+#define LIF_DOWN_ROWS_DENSE 512
+#endif
+
+// Row chunks in use for n cached rows.  For a single token and up to 2048 rows (1024 in full-bundle mode), one
+// chunk (one workgroup per column slice, no partial sums) is the shortest path: the kernel is latency bound
+// there.  Beyond that, the single-token
+// case that skips rows without activation keeps chunks of 2048 rows (one compaction pass each; few rows
+// contribute); when most rows are read (full-bundle mode, or several tokens whose active sets add up) a
+// chunk is 512 rows so that several hundred workgroups stream at once: column slices alone (d / 64
+// workgroups) reach only about 3 TB/s.  The host sizes the grid with the same rule.
+template <int BT, bool SKIP>
+__host__ __device__ __forceinline__ int down_chunks(int n) {
+    constexpr int per = (BT == 1 && SKIP) ? LIF_DOWN_ROWS_SPARSE : LIF_DOWN_ROWS_DENSE;
+    if (BT == 1 && n <= (SKIP ? LIF_DOWN_ROWS_SPARSE : 2 * LIF_DOWN_ROWS_DENSE)) return 1;
+    const int c = (n + per - 1) / per;
+    return c < 1 ? 1 : (c > kDownChunksMax ? kDownChunksMax : c);
+}
+
+// Down projection  y[t][j] = sum_s H[t][s] * D[s][j]  over the rows in use, for 1..BT tokens.
+// grid = (column slices, row-chunk workgroups), block = 256 = (256 / LANES) row groups x LANES lanes; a
+// lane owns 16 bytes of every down column it reads, a workgroup LANES * 16 contiguous bytes.
+// SKIP: rows whose activation is zero for every token of the batch are not read (they are compacted
+// away with a prefix sum in LDS, in a fixed order).
 // h_new / stamp (may be null): activations of the rows that the fused load kernel wrote during the
 // step whose number equals stamp[s]; they override h for those rows.
-template <typename T, int BT, bool SKIP>
+// The rows are cut into down_chunks(n) chunks - a function of n alone, so the arithmetic does not
+// depend on the launch geometry - and workgroup row y takes the chunks y, y + gridDim.y, ...  Every
+// chunk is summed from zero.  With one chunk in use the workgroup writes its columns of y.  With more,
+// a grid of one workgroup row adds its chunk sums in chunk order and writes y; a taller grid writes
+// them to ypart[chunk][token][d] (fp32) and k_ffn_down_finish adds them in the same order.  No atomics.
+template <typename T, int BT, bool SKIP, int LANES>
 __global__ __launch_bounds__(256) void k_ffn_down(const T* __restrict__ matrix, const float* __restrict__ h,
                                                   const float* __restrict__ h_new, const int32_t* __restrict__ stamp,
-                                                  T* __restrict__ y, int d, int batch, int capacity,
-                                                  size_t row_elems, int down_off, DevState* __restrict__ st) {
+                                                  T* __restrict__ y, float* __restrict__ ypart, int d, int batch,
+                                                  int capacity, size_t row_elems, int down_off,
+                                                  DevState* __restrict__ st) {
     using V = typename Vec<T>::type;
     constexpr int VE = Vec<T>::N;
-    constexpr int TS = kDownTile / BT;
+    constexpr int RG = 256 / LANES;                  // row groups per workgroup
+    constexpr int TS = kDownTile / BT;               // rows per compaction pass
     constexpr int PER = TS / 256;                    // slots per thread in the compaction
     __shared__ int list[TS];
     __shared__ float hv[BT][TS];
     __shared__ int wave_tot[4];
-    __shared__ float red[4][kDownLanes][BT][VE];
+    __shared__ float red[4][LANES][BT][VE];
     __shared__ int n_active;
 
-    const int tid = threadIdx.x, l = tid & (kDownLanes - 1), rg = tid >> 2;
-    // XCD-aware slice order: workgroups are dealt round-robin to the 8 XCDs, each with its own L2.
-    // A slice is 64 bytes wide, an L2 line 128: giving every XCD a contiguous run of slices makes
-    // the two halves of a line meet in one L2 instead of being fetched by two.
-    const int per_xcd = gridDim.x / kXcds;                   // the host rounds the grid up to a multiple of 8
-    const int slice = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
-    const int col = slice * (kDownLanes * VE) + l * VE;
+    const int tid = threadIdx.x, l = tid & (LANES - 1), rg = tid / LANES;
+    // XCD-aware slice order when a slice is narrower than a 128-byte L2 line: workgroups are dealt
+    // round-robin to the 8 XCDs, each with its own L2; giving every XCD a contiguous run of slices makes
+    // the parts of a line meet in one L2 instead of being fetched by several (the host rounds the
+    // grid up to a multiple of 8 in that case).
+    int slice = blockIdx.x;
+    if (LANES * 16 < 128) {
+        const int per_xcd = gridDim.x / kXcds;
+        slice = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
+    }
+    const int col = slice * (LANES * VE) + l * VE;
     const bool col_ok = col < d;
-    const T* base = matrix + down_off + col;
-
-    float acc[BT][VE];
-#pragma unroll
-    for (int b = 0; b < BT; ++b)
-#pragma unroll
-        for (int e = 0; e < VE; ++e) acc[b][e] = 0.f;
+    const T* base = matrix + down_off + (col_ok ? col : 0);
 
     if (tid == 0) n_active = 0;
-    // the activations of the first tile are requested before the row count is known (the
-    // activation array spans the whole capacity, so the addresses are valid; values past
+    // the first workgroup row requests the activations of its first pass before the row count is known
+    // (the activation array spans the whole capacity, so the addresses are valid; values past
     // num_used are masked below): one memory round trip less on the critical path
+    const bool first_row = blockIdx.y == 0;
     float hfirst[PER][BT];
-#pragma unroll
-    for (int q = 0; q < PER; ++q)
-#pragma unroll
-        for (int b = 0; b < BT; ++b) {
-            const int s = q * 256 + tid;
-            hfirst[q][b] = (s < capacity && b < batch) ? h[(size_t)b * capacity + s] : 0.f;
-        }
     int sfirst[PER];
 #pragma unroll
     for (int q = 0; q < PER; ++q) {
         const int s = q * 256 + tid;
-        sfirst[q] = (stamp && s < capacity) ? stamp[s] : -1;
+#pragma unroll
+        for (int b = 0; b < BT; ++b)
+            hfirst[q][b] = (first_row && s < capacity && b < batch) ? h[(size_t)b * capacity + s] : 0.f;
+        sfirst[q] = (first_row && stamp && s < capacity) ? stamp[s] : -1;
     }
     const int err = st->error;
     const int n = err ? 0 : st->num_used;
     const int cur_step = st->step;
-    if (stamp) {
+    if (err) return;
+    const int chunks = down_chunks<BT, SKIP>(n);
+    if ((int)blockIdx.y >= chunks) return;           // uniform
+    const int per_chunk = (n + chunks - 1) / chunks;
+    if (first_row && stamp) {
 #pragma unroll
         for (int q = 0; q < PER; ++q)
             if (sfirst[q] == cur_step) {
@@ -209,88 +279,134 @@ __global__ __launch_bounds__(256) void k_ffn_down(const T* __restrict__ matrix, 
                     if (b < batch) hfirst[q][b] = h_new[(size_t)b * capacity + q * 256 + tid];
             }
     }
-    __syncthreads();
-    if (err) return;
-    for (int s_base = 0; s_base < n; s_base += TS) {
-        // compaction of the rows that contribute, in a fixed order (thread-major over slots q * 256 + tid)
-        float hloc[PER][BT];
-        unsigned flags = 0, nonzero = 0;
+    const int ob = tid / LANES, ol = tid - ob * LANES;            // (token, lane) whose 16-byte piece this thread writes
+    const int ocol = slice * (LANES * VE) + ol * VE;
+    const bool writer = tid < LANES * BT && ocol < d && ob < batch;
+    float total[VE];
 #pragma unroll
-        for (int q = 0; q < PER; ++q) {
-            const int s = s_base + q * 256 + tid;
-            bool any = false;
+    for (int e = 0; e < VE; ++e) total[e] = 0.f;
+
+    for (int chunk = blockIdx.y; chunk < chunks; chunk += gridDim.y) {
+        const int r0 = chunk * per_chunk, r1 = min(n, r0 + per_chunk);
+        float acc[BT][VE];
 #pragma unroll
-            for (int b = 0; b < BT; ++b) {
-                float v = 0.f;
-                if (s < n && b < batch) {
-                    if (s_base == 0) v = hfirst[q][b];
-                    else v = (stamp && stamp[s] == cur_step) ? h_new[(size_t)b * capacity + s]
-                                                             : h[(size_t)b * capacity + s];
-                }
-                hloc[q][b] = v;
-                any |= (v != 0.f);
-            }
-            if (any) nonzero |= 1u << q;
-            if (!SKIP) any = s < n;
-            if (any) flags |= 1u << q;
-        }
-        if (slice == 0 && nonzero) atomicAdd(&n_active, __popc(nonzero));   // statistics only
-        int cnt;
-        int off = block_exclusive_scan(__popc(flags), wave_tot, &cnt);
+        for (int b = 0; b < BT; ++b)
 #pragma unroll
-        for (int q = 0; q < PER; ++q) {
-            if (flags & (1u << q)) {
-                list[off] = s_base + q * 256 + tid;
-#pragma unroll
-                for (int b = 0; b < BT; ++b) hv[b][off] = hloc[q][b];
-                ++off;
-            }
-        }
+            for (int e = 0; e < VE; ++e) acc[b][e] = 0.f;
         __syncthreads();
-        if (col_ok) {
-#pragma unroll 4
-            for (int i = rg; i < cnt; i += kDownRg) {
-                const int s = list[i];
-                const V v = *reinterpret_cast<const V*>(base + (size_t)s * row_elems);
+        for (int s_base = r0; s_base < r1; s_base += TS) {
+            // compaction of the rows that contribute, in a fixed order (thread-major over slots q * 256 + tid)
+            float hloc[PER][BT];
+            unsigned flags = 0, nonzero = 0;
+#pragma unroll
+            for (int q = 0; q < PER; ++q) {
+                const int s = s_base + q * 256 + tid;
+                bool any = false;
 #pragma unroll
                 for (int b = 0; b < BT; ++b) {
-                    const float hb = hv[b][i];
+                    float v = 0.f;
+                    if (s < r1 && b < batch) {
+                        if (s_base == 0) v = hfirst[q][b];       // only chunk 0 (first workgroup row) starts at row 0
+                        else v = (stamp && stamp[s] == cur_step) ? h_new[(size_t)b * capacity + s]
+                                                                 : h[(size_t)b * capacity + s];
+                    }
+                    hloc[q][b] = v;
+                    any |= (v != 0.f);
+                }
+                if (any) nonzero |= 1u << q;
+                if (!SKIP) any = s < r1;
+                if (any) flags |= 1u << q;
+            }
+            if (slice == 0 && nonzero) atomicAdd(&n_active, __popc(nonzero));   // statistics only
+            int cnt;
+            int off = block_exclusive_scan(__popc(flags), wave_tot, &cnt);
 #pragma unroll
-                    for (int e = 0; e < VE; ++e) acc[b][e] = __builtin_fmaf(hb, (float)v[e], acc[b][e]);
+            for (int q = 0; q < PER; ++q) {
+                if (flags & (1u << q)) {
+                    list[off] = s_base + q * 256 + tid;
+#pragma unroll
+                    for (int b = 0; b < BT; ++b) hv[b][off] = hloc[q][b];
+                    ++off;
                 }
             }
+            __syncthreads();
+            if (col_ok) {
+#pragma unroll 4
+                for (int i = rg; i < cnt; i += RG) {
+                    const int s = list[i];
+                    const V v = *reinterpret_cast<const V*>(base + (size_t)s * row_elems);
+#pragma unroll
+                    for (int b = 0; b < BT; ++b) {
+                        const float hb = hv[b][i];
+#pragma unroll
+                        for (int e = 0; e < VE; ++e) acc[b][e] = __builtin_fmaf(hb, (float)v[e], acc[b][e]);
+                    }
+                }
+            }
+            __syncthreads();
         }
+        // the row groups of one wave sit LANES lanes apart: butterfly over the upper lane bits, then LDS over waves
+#pragma unroll
+        for (int b = 0; b < BT; ++b)
+#pragma unroll
+            for (int e = 0; e < VE; ++e) {
+                float v = acc[b][e];
+#pragma unroll
+                for (int m = LANES; m < kWave; m <<= 1) v += __shfl_xor(v, m, kWave);
+                if ((tid & 63) < LANES) red[tid >> 6][l][b][e] = v;
+            }
         __syncthreads();
-    }
-    // row groups of one wave sit 4 lanes apart: butterfly over lane bits 2..5, then LDS over waves
-#pragma unroll
-    for (int b = 0; b < BT; ++b)
-#pragma unroll
-        for (int e = 0; e < VE; ++e) {
-            float v = acc[b][e];
-            v += __shfl_xor(v, 4, kWave);
-            v += __shfl_xor(v, 8, kWave);
-            v += __shfl_xor(v, 16, kWave);
-            v += __shfl_xor(v, 32, kWave);
-            if ((tid & 63) < kDownLanes) red[tid >> 6][l][b][e] = v;
-        }
-    __syncthreads();
-    if (slice == 0 && tid == 0) {
-        st->c_ffn_calls += 1;
-        st->c_ffn_rows += (unsigned long long)n;
-        st->c_ffn_active += (unsigned long long)n_active;
-    }
-    if (tid < kDownLanes * BT) {
-        const int b = tid / kDownLanes, l2 = tid - b * kDownLanes;
-        const int col2 = slice * (kDownLanes * VE) + l2 * VE;
-        if (col2 < d && b < batch) {
-            V out;
+        if (writer) {
+            float sum[VE];
 #pragma unroll
             for (int e = 0; e < VE; ++e)
-                out[e] = (T)(((red[0][l2][b][e] + red[1][l2][b][e]) + red[2][l2][b][e]) + red[3][l2][b][e]);
-            *reinterpret_cast<V*>(y + (size_t)b * d + col2) = out;
+                sum[e] = ((red[0][ol][ob][e] + red[1][ol][ob][e]) + red[2][ol][ob][e]) + red[3][ol][ob][e];
+            if (chunks > 1 && gridDim.y > 1) {
+                float* out = ypart + ((size_t)chunk * batch + ob) * d + ocol;
+#pragma unroll
+                for (int e = 0; e < VE; ++e) out[e] = sum[e];
+            } else {
+#pragma unroll
+                for (int e = 0; e < VE; ++e) total[e] += sum[e];      // chunk order; 0 + first sum is exact
+            }
         }
     }
+    if (slice == 0 && tid == 0) {
+        if (first_row) {
+            st->c_ffn_calls += 1;
+            st->c_ffn_rows += (unsigned long long)n;
+        }
+        if (n_active) atomicAdd(&st->c_ffn_active, (unsigned long long)n_active);
+    }
+    if (writer && (chunks == 1 || gridDim.y == 1)) {
+        V out;
+#pragma unroll
+        for (int e = 0; e < VE; ++e) out[e] = (T)total[e];
+        *reinterpret_cast<V*>(y + (size_t)ob * d + ocol) = out;
+    }
+}
+
+// y = sum of the chunk partials in chunk order, rounded once to the element type.  Launched after a
+// k_ffn_down grid of more than one workgroup row; does nothing when a single chunk was in use (y is
+// written already).  grid = ceil(batch * d / 256), block = 256.
+template <typename T, int BT, bool SKIP>
+__global__ __launch_bounds__(256) void k_ffn_down_finish(const float* __restrict__ ypart, T* __restrict__ y, int d,
+                                                         int batch, const DevState* __restrict__ st) {
+    if (st->error) return;
+    const int chunks = down_chunks<BT, SKIP>(st->num_used);
+    if (chunks == 1) return;
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= batch * d) return;
+    // all partials are requested before the first add (a loop with a run-time trip count would wait for
+    // every load in turn)
+    float v[kDownChunksMax];
+#pragma unroll
+    for (int c = 0; c < kDownChunksMax; ++c) v[c] = (c < chunks) ? ypart[(size_t)c * batch * d + i] : 0.f;
+    float s = 0.f;
+#pragma unroll
+    for (int c = 0; c < kDownChunksMax; ++c)
+        if (c < chunks) s += v[c];
+    y[i] = (T)s;
 }
 
 }  // namespace lif

@@ -10,89 +10,57 @@
 // global loads (weights, partial sums, offsets, state) before the first dependent use.
 #pragma once
 
+#include <type_traits>
+
 #include "lif_common.h"
 
 namespace lif {
 
-constexpr int kXaRows = 256;       // rows of A per workgroup of predict_xa
-constexpr int kXaBatch = 16;       // rows of A a thread keeps in flight
 constexpr int kMaskCols = 8;       // mask bytes (groups of 8 neurons) per workgroup of predict_mask
 constexpr int kMaskJg = 32;        // rank groups per workgroup of predict_mask
 constexpr int kMaskRows = 8;       // rows of B a thread keeps in flight
 
-// t_partial[b][chunk][j] = sum_{i in chunk} x[b][i] * A[i][j]
-// grid = (ceil(d / kXaRows), batch), block = 256.
-// Thread (rl, cl): column lanes cl cover a row of A with 16-byte loads, rl strides rows.
-template <typename T>
-__global__ __launch_bounds__(256) void k_predict_xa(const T* __restrict__ x, const T* __restrict__ A,
-                                                    double* __restrict__ tpart, int d, int r,
+// t[b][j] = sum_i x[b][i] * At[j][i]   (At = the first predictor matrix with the contraction dimension
+// contiguous, [r x d]).  One wave per (j, b): 16-byte loads along the row, fp64 accumulation, wave
+// reduction - every t[b][j] is complete after this kernel, so the mask kernel needs no partial sums.
+// grid = (ceil(r / 4), batch), block = 256.  NI = ceil(d / (64 * VE)) loads per lane.
+template <typename T, int NI>
+__global__ __launch_bounds__(256) void k_predict_xa(const T* __restrict__ x, const T* __restrict__ At,
+                                                    double* __restrict__ t, int d, int r,
                                                     const DevState* __restrict__ st) {
     using V = typename Vec<T>::type;
     constexpr int VE = Vec<T>::N;
-    __shared__ float xs[kXaRows];
-    __shared__ double red[256 * VE];
-
-    const int tid = threadIdx.x;
-    const int lpr = r / VE;                 // lanes per row (host guarantees 1 <= lpr <= 256)
-    const int rp = 256 / lpr;               // rows per pass
-    const int rl = tid / lpr, cl = tid - rl * lpr;
-    const int chunk = blockIdx.x, b = blockIdx.y, nchunks = gridDim.x;
-    const int row0 = chunk * kXaRows;
-    const int nrows = min(kXaRows, d - row0);
-    const bool lane_ok = rl < rp;
-    const V* __restrict__ Av = reinterpret_cast<const V*>(A) + (size_t)row0 * lpr + cl;
-
-    // loads first: x, the first batch of A rows, the error flag
-    const float xreg = (tid < nrows) ? (float)x[(size_t)b * d + row0 + tid] : 0.f;
-    V a[kXaBatch];
+    const int lane = threadIdx.x & 63;
+    const int j = blockIdx.x * 4 + (threadIdx.x >> 6), b = blockIdx.y;
+    if (j >= r) return;                              // wave-uniform; the kernel has no barrier
+    const int nvec = d / VE;
+    const V* xv = reinterpret_cast<const V*>(x + (size_t)b * d);
+    const V* row = reinterpret_cast<const V*>(At + (size_t)j * d);
+    V a[NI], xr[NI];
 #pragma unroll
-    for (int u = 0; u < kXaBatch; ++u) {
-        const int i = rl + u * rp;
-        a[u] = (lane_ok && i < nrows) ? Av[(size_t)i * lpr] : V(0);
+    for (int it = 0; it < NI; ++it) {
+        const int idx = it * 64 + lane;
+        a[it] = (idx < nvec) ? row[idx] : V(0);
+        xr[it] = (idx < nvec) ? xv[idx] : V(0);
     }
     const int err = st->error;
-    xs[tid] = xreg;
-    __syncthreads();
-
-    double acc[VE];
+    double acc = 0.0;
 #pragma unroll
-    for (int e = 0; e < VE; ++e) acc[e] = 0.0;
+    for (int it = 0; it < NI; ++it)
 #pragma unroll
-    for (int u = 0; u < kXaBatch; ++u) {
-        const int i = rl + u * rp;
-        const double xv = (double)xs[min(i, kXaRows - 1)];
+        for (int q = 0; q < VE; ++q) acc = __builtin_fma((double)a[it][q], (double)xr[it][q], acc);
 #pragma unroll
-        for (int e = 0; e < VE; ++e) acc[e] = __builtin_fma(xv, (double)a[u][e], acc[e]);   // a[u] is 0 past the end
-    }
-    if (lane_ok) {
-        for (int i = rl + kXaBatch * rp; i < nrows; i += rp) {     // only when rank / VE > 16
-            const V av = Av[(size_t)i * lpr];
-            const double xv = (double)xs[i];
-#pragma unroll
-            for (int e = 0; e < VE; ++e) acc[e] = __builtin_fma(xv, (double)av[e], acc[e]);
-        }
-    }
-#pragma unroll
-    for (int e = 0; e < VE; ++e) red[tid * VE + e] = acc[e];
-    __syncthreads();
-    if (err) return;
-    // column j lives in lane cl = j / VE, element e = j % VE; rows-in-pass summed ascending
-    for (int j = tid; j < r; j += 256) {
-        const int jc = j / VE, je = j - jc * VE;
-        double s = 0.0;
-        for (int q = 0; q < rp; ++q) s += red[(q * lpr + jc) * VE + je];
-        tpart[((size_t)b * nchunks + chunk) * r + j] = s;
-    }
+    for (int msk = 32; msk >= 1; msk >>= 1) acc += __shfl_xor(acc, msk, kWave);
+    if (lane == 0 && !err) t[(size_t)b * r + j] = acc;
 }
 
 // logits = t B + c, threshold, pack 8 neurons per byte; step mask = OR over the batch.
 // grid = ceil(F / 64), block = 256 = 32 rank groups x 8 column lanes; each column lane owns
-// 8 consecutive neurons = one mask byte.  t = sum of the chunk partials, reduced redundantly
-// by every workgroup in a fixed order.  dynamic LDS: BT * r doubles.
+// 8 consecutive neurons = one mask byte.  dynamic LDS: BT * r doubles (t of the tokens of a pass).
 template <typename T, int BT>
 __global__ __launch_bounds__(256) void k_predict_mask(const T* __restrict__ B, const float* __restrict__ c,
-                                                      const double* __restrict__ tpart, int nchunks, int r,
-                                                      int F, int batch, float theta,
+                                                      const double* __restrict__ t, int r, int F, int batch,
+                                                      float theta,
                                                       uint8_t* __restrict__ masks, uint8_t* __restrict__ step_mask,
                                                       const DevState* __restrict__ st) {
     using V = typename Vec<T>::type;
@@ -132,21 +100,13 @@ __global__ __launch_bounds__(256) void k_predict_mask(const T* __restrict__ B, c
         __syncthreads();
         for (int idx = tid; idx < BT * r; idx += 256) {
             const int bt = idx / r, j = idx - bt * r;
-            double s = 0.0;
-            if (b0 + bt < batch) {
-                const double* p = tpart + ((size_t)(b0 + bt) * nchunks) * r + j;
-#pragma unroll 8
-                for (int ch = 0; ch < nchunks; ++ch) s += p[(size_t)ch * r];
-            }
-            tl[idx] = s;
+            tl[idx] = (b0 + bt < batch) ? t[(size_t)(b0 + bt) * r + j] : 0.0;
         }
         __syncthreads();
 
-        double acc[BT][8];
+        double v[BT * 8];                    // v[bt * 8 + e]: logit sums of token bt, neuron e of this lane's byte
 #pragma unroll
-        for (int bt = 0; bt < BT; ++bt)
-#pragma unroll
-            for (int e = 0; e < 8; ++e) acc[bt][e] = 0.0;
+        for (int i = 0; i < BT * 8; ++i) v[i] = 0.0;
 #pragma unroll
         for (int u = 0; u < kMaskRows; ++u) {
             const int j = min(jg + u * kMaskJg, r - 1);           // bv[u] is 0 past the end
@@ -157,7 +117,7 @@ __global__ __launch_bounds__(256) void k_predict_mask(const T* __restrict__ B, c
                 for (int q = 0; q < LPB; ++q)
 #pragma unroll
                     for (int e = 0; e < VE; ++e)
-                        acc[bt][q * VE + e] = __builtin_fma(tj, (double)bv[u][q][e], acc[bt][q * VE + e]);
+                        v[bt * 8 + q * VE + e] = __builtin_fma(tj, (double)bv[u][q][e], v[bt * 8 + q * VE + e]);
             }
         }
         if (col_ok) {
@@ -173,21 +133,50 @@ __global__ __launch_bounds__(256) void k_predict_mask(const T* __restrict__ B, c
                     for (int q = 0; q < LPB; ++q)
 #pragma unroll
                         for (int e = 0; e < VE; ++e)
-                            acc[bt][q * VE + e] = __builtin_fma(tj, (double)bw[q][e], acc[bt][q * VE + e]);
+                            v[bt * 8 + q * VE + e] = __builtin_fma(tj, (double)bw[q][e], v[bt * 8 + q * VE + e]);
                 }
             }
         }
-        // the eight rank groups of a wave sit 8 lanes apart: butterfly, then LDS across the 4 waves
+        // The eight rank groups of a wave sit 8 lanes apart (lane bits 3..5): butterfly over those bits, then LDS
+        // across the 4 waves.  While a lane still holds the sums of more than one token, a step halves them: the
+        // lane keeps the tokens selected by its own bit and hands the other half to its partner (56 exchanges
+        // instead of 192 for 8 tokens).  Afterwards lane (g, cl), g = lane bits 3..5, holds the 8 sums of token
+        // `owner` (all lanes for BT = 8; even g / g = 0 only for fewer tokens).
+        int owner = 0;
+        auto halve = [&](auto half_c, int m) {       // keep the half selected by this lane's bit m, add the partner's
+            constexpr int half = decltype(half_c)::value;
+            const bool up = (tid & m) != 0;
 #pragma unroll
-        for (int bt = 0; bt < BT; ++bt)
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                double v = acc[bt][e];
-                v += __shfl_xor(v, 8, kWave);
-                v += __shfl_xor(v, 16, kWave);
-                v += __shfl_xor(v, 32, kWave);
-                if ((tid & 63) < kMaskCols) red[wave][cl][bt][e] = v;
+            for (int i = 0; i < half; ++i) {
+                const double send = up ? v[i] : v[i + half], keep = up ? v[i + half] : v[i];
+                v[i] = keep + __shfl_xor(send, m, kWave);
             }
+            owner = owner * 2 + (up ? 1 : 0);
+        };
+        auto full = [&](int m) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) v[i] += __shfl_xor(v[i], m, kWave);
+        };
+        if constexpr (BT == 8) {
+            halve(std::integral_constant<int, 32>{}, 32);
+            halve(std::integral_constant<int, 16>{}, 16);
+            halve(std::integral_constant<int, 8>{}, 8);
+        } else if constexpr (BT == 4) {
+            halve(std::integral_constant<int, 16>{}, 32);
+            halve(std::integral_constant<int, 8>{}, 16);
+            full(8);
+        } else {
+            full(32);
+            full(16);
+            full(8);
+        }
+        // which lanes hold a finished token: those whose bits of the non-halving steps are zero
+        constexpr int kHalvings = (BT == 8) ? 3 : (BT == 4) ? 2 : 0;
+        const bool holder = ((tid & 63) & ((64 >> kHalvings) - 8)) == 0;
+        if (holder) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) red[wave][cl][owner][e] = v[e];
+        }
         __syncthreads();
         if (tid < kMaskCols * BT) {
             const int bt = tid / kMaskCols, c2 = tid - bt * kMaskCols;

@@ -30,7 +30,8 @@ class GpuLayer:
             capacity_rows=capacity or w.capacity_rows, max_batch=max_batch or w.batch,
             glu=(w.glu and not gate), dtype=w.dtype, ffn_mode=ffn_mode, shrink_window=(shrink or w.shrink),
             predictor=lif.PRED_GATE if gate else lif.PRED_LOWRANK, threshold=L.theta,
-            A=up(L.w_gate if gate else L.A), B=None if gate else up(L.B),
+            A=up(L.w_gate if gate else L.A.T),       # the ABI takes the contraction dimension contiguous: [rank, d_model]
+            B=None if gate else up(L.B),
             c=up(L.c) if (use_c and not gate) else None, b=up(L.b), host_bundles=self.host)
         self.y = torch.zeros((max_batch or w.batch, w.d_model), dtype=self.tdtype, device=dev)
 
