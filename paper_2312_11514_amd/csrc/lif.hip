@@ -18,6 +18,10 @@
 
 using namespace lif;
 
+#ifndef LIF_NO_MFMA
+#define LIF_NO_MFMA 0
+#endif
+
 namespace {
 
 thread_local char g_err[512] = "";
@@ -249,11 +253,11 @@ void launch_ffn_down(lif_layer* L, int batch, void* y, hipStream_t s, bool use_n
         if (skip) launch_ffn_down_as<T, 1, true, kDownLanes1>(L, batch, y, s, use_new);
         else launch_ffn_down_as<T, 1, false, kDownLanesN>(L, batch, y, s, use_new);
     } else if (batch <= 4) {
-        if (skip) launch_ffn_down_as<T, 4, true, kDownLanesN>(L, batch, y, s, use_new);
-        else launch_ffn_down_as<T, 4, false, kDownLanesN>(L, batch, y, s, use_new);
+        if (skip) launch_ffn_down_as<T, 4, true, kDownLanesB>(L, batch, y, s, use_new);
+        else launch_ffn_down_as<T, 4, false, kDownLanesB>(L, batch, y, s, use_new);
     } else {
-        if (skip) launch_ffn_down_as<T, 8, true, kDownLanesN>(L, batch, y, s, use_new);
-        else launch_ffn_down_as<T, 8, false, kDownLanesN>(L, batch, y, s, use_new);
+        if (skip) launch_ffn_down_as<T, 8, true, kDownLanesB>(L, batch, y, s, use_new);
+        else launch_ffn_down_as<T, 8, false, kDownLanesB>(L, batch, y, s, use_new);
     }
 }
 
@@ -280,6 +284,42 @@ void launch_load_up(lif_layer* L, const void* x, const int32_t* added, hipStream
     else if (ni <= 12) LIF_LU(12);
     else LIF_LU(16);
 #undef LIF_LU
+}
+
+bool mfma_path(const lif_config& c, int batch) {
+    return !LIF_NO_MFMA && c.dtype == LIF_F16 && batch > 1 && c.d_model % 32 == 0;
+}
+
+template <int MODE>
+void launch_ffn_up_mfma(lif_layer* L, const void* x, int batch, hipStream_t s) {
+    const lif_config& c = L->cfg;
+    constexpr int W = (MODE == kRowsChanged) ? kMfmaWavesFix : kMfmaWaves;
+    // the rows a load wrote are few: a small grid strides over their tiles
+    const int tiles = (c.capacity_rows + 15) / 16;
+    const int grid = (MODE == kRowsChanged) ? std::min(tiles, 64) : tiles;
+    if (c.glu)
+        hipLaunchKernelGGL((k_ffn_up_mfma<true, MODE, W>), dim3(grid), dim3(W * 64), 0, s,
+                           (const _Float16*)L->buf.matrix, L->buf.bias, (const _Float16*)x, L->h, c.d_model, batch,
+                           c.capacity_rows, L->row_elems, L->move_dst, L->st);
+    else
+        hipLaunchKernelGGL((k_ffn_up_mfma<false, MODE, W>), dim3(grid), dim3(W * 64), 0, s,
+                           (const _Float16*)L->buf.matrix, L->buf.bias, (const _Float16*)x, L->h, c.d_model, batch,
+                           c.capacity_rows, L->row_elems, L->move_dst, L->st);
+}
+
+// batch > 1, fp16: bundle load next to the activation stage of the surviving rows, then the rows the load wrote
+void launch_load_up_mfma(lif_layer* L, const void* x, int batch, const int32_t* added, hipStream_t s) {
+    const lif_config& c = L->cfg;
+    const int tiles = (c.capacity_rows + 15) / 16;
+    static_assert(kMfmaWaves == 4, "the fused kernel runs both roles with 256 threads");
+    if (c.glu)
+        hipLaunchKernelGGL((k_load_up_mfma<true>), dim3(kLoadGrid + tiles), dim3(256), 0, s, (_Float16*)L->buf.matrix,
+                           L->buf.pointers, L->buf.bias, L->host_alias, L->buf.b, added, L->move_dst, L->row_bytes,
+                           c.d_ffn, (const _Float16*)x, L->h, c.d_model, batch, c.capacity_rows, kLoadGrid, L->st);
+    else
+        hipLaunchKernelGGL((k_load_up_mfma<false>), dim3(kLoadGrid + tiles), dim3(256), 0, s, (_Float16*)L->buf.matrix,
+                           L->buf.pointers, L->buf.bias, L->host_alias, L->buf.b, added, L->move_dst, L->row_bytes,
+                           c.d_ffn, (const _Float16*)x, L->h, c.d_model, batch, c.capacity_rows, kLoadGrid, L->st);
 }
 
 int check_launch() {
@@ -447,18 +487,10 @@ int lif_sparse_ffn(lif_layer* L, const void* x_dev, int32_t batch, void* y_dev, 
     if ((uintptr_t)x_dev % 16 || (uintptr_t)y_dev % 16) return fail(LIF_INVALID_ARG, "x and y must be 16-byte aligned");
     hipStream_t s = (hipStream_t)stream;
     const lif_config& c = L->cfg;
-    if (c.dtype == LIF_F16 && batch > 1 && c.d_model % 32 == 0) {
+    if (mfma_path(c, batch)) {
         // batched tokens: the activation stage is a dense contraction -> matrix cores
         Timed t(L, LIF_K_FFN_UP, s);
-        const int grid = (c.capacity_rows + 15) / 16;
-        if (c.glu)
-            hipLaunchKernelGGL((k_ffn_up_mfma<true>), dim3(grid), dim3(256), 0, s, (const _Float16*)L->buf.matrix,
-                               L->buf.bias, (const _Float16*)x_dev, L->h, c.d_model, batch, c.capacity_rows,
-                               L->row_elems, L->st);
-        else
-            hipLaunchKernelGGL((k_ffn_up_mfma<false>), dim3(grid), dim3(256), 0, s, (const _Float16*)L->buf.matrix,
-                               L->buf.bias, (const _Float16*)x_dev, L->h, c.d_model, batch, c.capacity_rows,
-                               L->row_elems, L->st);
+        launch_ffn_up_mfma<kRowsAll>(L, x_dev, batch, s);
     } else {
         Timed t(L, LIF_K_FFN_UP, s);
         if (c.dtype == LIF_F32) {
@@ -485,13 +517,27 @@ int lif_step(lif_layer* L, const void* x_dev, int32_t batch, void* y_dev, uint8_
     if (!y_dev || (uintptr_t)y_dev % 16) return fail(LIF_INVALID_ARG, "y must be a 16-byte aligned device pointer");
     rc = lif_update_window(L, step_mask_dev, added_dev, n_added_dev, removed_dev, n_removed_dev, stream);
     if (rc) return rc;
-    if (batch > 1) {
+    hipStream_t s = (hipStream_t)stream;
+    const lif_config& c = L->cfg;
+    if (batch > 1 && !mfma_path(c, batch)) {
         rc = lif_load_bundles(L, added_dev, n_added_dev, removed_dev, n_removed_dev, stream);
         if (rc) return rc;
         return lif_sparse_ffn(L, x_dev, batch, y_dev, stream);
     }
-    hipStream_t s = (hipStream_t)stream;
-    const lif_config& c = L->cfg;
+    if (batch > 1) {
+        {
+            Timed t(L, LIF_K_LOAD, s);
+            launch_load_up_mfma(L, x_dev, batch, added_dev, s);
+        }
+        L->window_pending = false;
+        {
+            Timed t(L, LIF_K_FFN_UP, s);
+            launch_ffn_up_mfma<kRowsChanged>(L, x_dev, batch, s);
+        }
+        Timed t(L, LIF_K_FFN_DOWN, s);
+        launch_ffn_down<_Float16>(L, batch, y_dev, s);
+        return check_launch();
+    }
     {
         Timed t(L, LIF_K_LOAD, s);
         if (c.dtype == LIF_F32) {

@@ -97,4 +97,54 @@ __device__ __forceinline__ int block_exclusive_scan(int v, int* wave_tot, int* t
     return before + inc - v;
 }
 
+
+// Sum of v[0..N) over the lanes that differ in the lane bits M, 2M, ..., 32 (groups of lanes M apart).
+// While a lane holds more than one value, a step halves them: the lane keeps the half selected by its own
+// bit and hands the other half to its partner, so N - N / 2^steps (+ the remaining full steps) exchanges
+// replace steps * N.  Returns through `first` the index of the first value this lane ends up with; it then
+// holds wave_fold_held<N, M>() finished sums in v[0..held).  Lanes whose bits of the steps taken after a
+// single value was left are not all zero hold a duplicate (wave_fold_dup_mask gives those bits).
+template <int N, int M>
+constexpr int wave_fold_held() {
+    int held = N;
+    for (int m = M; m < kWave; m <<= 1)
+        if (held > 1) held >>= 1;
+    return held;
+}
+template <int N, int M>
+constexpr int wave_fold_dup_mask() {
+    int held = N, mask = 0;
+    for (int m = M; m < kWave; m <<= 1) {
+        if (held > 1) held >>= 1;
+        else mask |= m;
+    }
+    return mask;
+}
+template <int HELD, int M, int N>
+__device__ __forceinline__ void wave_fold_step(float (&v)[N], int& first, int lane) {
+    if constexpr (M < kWave) {
+        if constexpr (HELD > 1) {
+            constexpr int half = HELD / 2;
+            const bool up = (lane & M) != 0;
+#pragma unroll
+            for (int i = 0; i < half; ++i) {
+                const float send = up ? v[i] : v[i + half], keep = up ? v[i + half] : v[i];
+                v[i] = keep + __shfl_xor(send, M, kWave);
+            }
+            first += up ? half : 0;
+            wave_fold_step<half, M * 2, N>(v, first, lane);
+        } else {
+            v[0] += __shfl_xor(v[0], M, kWave);
+            wave_fold_step<1, M * 2, N>(v, first, lane);
+        }
+    }
+}
+template <int N, int M>
+__device__ __forceinline__ int wave_fold(float (&v)[N], int lane) {
+    static_assert((N & (N - 1)) == 0, "power of two");
+    int first = 0;
+    wave_fold_step<N, M, N>(v, first, lane);
+    return first;
+}
+
 }  // namespace lif

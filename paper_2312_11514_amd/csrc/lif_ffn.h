@@ -173,7 +173,7 @@ __global__ __launch_bounds__(256) void k_ffn_up(const T* __restrict__ matrix, co
 constexpr int kUpMaxWgs = LIF_UP_MAX_WGS;   // workgroups of the activation stage: beyond this, waves loop over rows (x stays in registers)
 
 constexpr int kXcds = 8;            // accelerator complex dies of an MI355X, each with a private L2
-constexpr int kDownTile = 2048;     // activations (rows x tokens) compacted per pass
+constexpr int kDownTile = 2048;     // activations (rows x tokens) compacted per pass (at least 512 rows)
 constexpr int kDownChunksMax = 32;  // row chunks of the down projection (partial outputs per chunk)
 #ifndef LIF_DOWN_LANES_1
 #define LIF_DOWN_LANES_1 4
@@ -181,6 +181,13 @@ constexpr int kDownChunksMax = 32;  // row chunks of the down projection (partia
 #ifndef LIF_DOWN_LANES_N
 #define LIF_DOWN_LANES_N 8
 #endif
+#ifndef LIF_DOWN_LANES_B
+#define LIF_DOWN_LANES_B 16
+#endif
+#ifndef LIF_DOWN_ROWS_BATCH
+#define LIF_DOWN_ROWS_BATCH 512
+#endif
+constexpr int kDownLanesB = LIF_DOWN_LANES_B;   // ... for several tokens
 constexpr int kDownLanes1 = LIF_DOWN_LANES_1;   // lanes per column slice, single token skipping dead rows (latency bound)
 constexpr int kDownLanesN = LIF_DOWN_LANES_N;   // ... when most rows are read: 8 x 16 B = one 128-byte line per row
 #ifndef LIF_DOWN_ROWS_SPARSE
@@ -199,7 +206,7 @@ constexpr int kDownLanesN = LIF_DOWN_LANES_N;   // ... when most rows are read: 
 // workgroups) reach only about 3 TB/s.  The host sizes the grid with the same rule.
 template <int BT, bool SKIP>
 __host__ __device__ __forceinline__ int down_chunks(int n) {
-    constexpr int per = (BT == 1 && SKIP) ? LIF_DOWN_ROWS_SPARSE : LIF_DOWN_ROWS_DENSE;
+    constexpr int per = (BT == 1 && SKIP) ? LIF_DOWN_ROWS_SPARSE : (BT == 1 ? LIF_DOWN_ROWS_DENSE : LIF_DOWN_ROWS_BATCH);
     if (BT == 1 && n <= (SKIP ? LIF_DOWN_ROWS_SPARSE : 2 * LIF_DOWN_ROWS_DENSE)) return 1;
     const int c = (n + per - 1) / per;
     return c < 1 ? 1 : (c > kDownChunksMax ? kDownChunksMax : c);
@@ -226,12 +233,12 @@ __global__ __launch_bounds__(256) void k_ffn_down(const T* __restrict__ matrix, 
     using V = typename Vec<T>::type;
     constexpr int VE = Vec<T>::N;
     constexpr int RG = 256 / LANES;                  // row groups per workgroup
-    constexpr int TS = kDownTile / BT;               // rows per compaction pass
+    constexpr int TS = (kDownTile / BT < 512) ? 512 : kDownTile / BT;   // rows per compaction pass
     constexpr int PER = TS / 256;                    // slots per thread in the compaction
     __shared__ int list[TS];
     __shared__ float hv[BT][TS];
     __shared__ int wave_tot[4];
-    __shared__ float red[4][LANES][BT][VE];
+    __shared__ float red[4][LANES][BT * VE];
     __shared__ int n_active;
 
     const int tid = threadIdx.x, l = tid & (LANES - 1), rg = tid / LANES;
@@ -288,11 +295,9 @@ __global__ __launch_bounds__(256) void k_ffn_down(const T* __restrict__ matrix, 
 
     for (int chunk = blockIdx.y; chunk < chunks; chunk += gridDim.y) {
         const int r0 = chunk * per_chunk, r1 = min(n, r0 + per_chunk);
-        float acc[BT][VE];
+        float acc[BT * VE];                          // acc[b * VE + e]: token b, element e of this lane's 16 bytes
 #pragma unroll
-        for (int b = 0; b < BT; ++b)
-#pragma unroll
-            for (int e = 0; e < VE; ++e) acc[b][e] = 0.f;
+        for (int i = 0; i < BT * VE; ++i) acc[i] = 0.f;
         __syncthreads();
         for (int s_base = r0; s_base < r1; s_base += TS) {
             // compaction of the rows that contribute, in a fixed order (thread-major over slots q * 256 + tid)
@@ -339,28 +344,30 @@ __global__ __launch_bounds__(256) void k_ffn_down(const T* __restrict__ matrix, 
                     for (int b = 0; b < BT; ++b) {
                         const float hb = hv[b][i];
 #pragma unroll
-                        for (int e = 0; e < VE; ++e) acc[b][e] = __builtin_fmaf(hb, (float)v[e], acc[b][e]);
+                        for (int e = 0; e < VE; ++e) acc[b * VE + e] = __builtin_fmaf(hb, (float)v[e], acc[b * VE + e]);
                     }
                 }
             }
             __syncthreads();
         }
-        // the row groups of one wave sit LANES lanes apart: butterfly over the upper lane bits, then LDS over waves
+        // the row groups of one wave sit LANES lanes apart: halving butterfly over the upper lane bits (a lane
+        // ends with a few finished sums), then LDS over waves
+        {
+            constexpr int held = wave_fold_held<BT * VE, LANES>();
+            constexpr int dup = wave_fold_dup_mask<BT * VE, LANES>();
+            const int first = wave_fold<BT * VE, LANES>(acc, tid & 63);
+            if (((tid & 63) & dup) == 0) {
 #pragma unroll
-        for (int b = 0; b < BT; ++b)
-#pragma unroll
-            for (int e = 0; e < VE; ++e) {
-                float v = acc[b][e];
-#pragma unroll
-                for (int m = LANES; m < kWave; m <<= 1) v += __shfl_xor(v, m, kWave);
-                if ((tid & 63) < LANES) red[tid >> 6][l][b][e] = v;
+                for (int i = 0; i < held; ++i) red[tid >> 6][l][first + i] = acc[i];
             }
+        }
         __syncthreads();
         if (writer) {
             float sum[VE];
 #pragma unroll
             for (int e = 0; e < VE; ++e)
-                sum[e] = ((red[0][ol][ob][e] + red[1][ol][ob][e]) + red[2][ol][ob][e]) + red[3][ol][ob][e];
+                sum[e] = ((red[0][ol][ob * VE + e] + red[1][ol][ob * VE + e]) + red[2][ol][ob * VE + e]) +
+                         red[3][ol][ob * VE + e];
             if (chunks > 1 && gridDim.y > 1) {
                 float* out = ypart + ((size_t)chunk * batch + ob) * d + ocol;
 #pragma unroll

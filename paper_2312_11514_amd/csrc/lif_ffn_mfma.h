@@ -16,73 +16,116 @@ namespace lif {
 #endif
 constexpr int kMfmaUnroll = LIF_MFMA_UNROLL;     // k-steps (32 elements each) a wave keeps in flight
 
-// grid = ceil(capacity / 16) workgroups of 256 threads; workgroup b owns cached rows 16b .. 16b+15
-// and exits at once if they are not in use.  Each of its four waves takes a contiguous quarter of the
-// k-steps (a wave instruction reads 64 bytes of 16 rows; consecutive instructions of one wave then
-// complete whole 128-byte lines: measured 6.5 TB/s against 4.6 TB/s when the waves interleave
-// k-steps) and the partial tiles are added in wave order through LDS.
+// grid = ceil(capacity / 16) workgroups of 4 (or 16) waves; workgroup b owns 16 rows and exits at once if
+// they are not in use.  Each wave takes contiguous k-steps (a wave instruction reads 64 bytes of 16 rows;
+// consecutive instructions of one wave then complete whole 128-byte lines: measured 6.5 TB/s against
+// 4.6 TB/s when the waves interleave k-steps); the partial tiles are added in k order through LDS.
 // Fragment layout of the 16x16x32 MFMA: lane l supplies row (l mod 16) of A and column (l mod 16)
 // of B for the k sub-block (l div 16); it receives D[4 * (l div 16) + r][l mod 16], r = 0..3.
 // Here A = rows of the cache, B = tokens (columns >= batch are zero).
 // Requires d % 32 == 0.
-template <bool GLU>
-__global__ __launch_bounds__(256) void k_ffn_up_mfma(const _Float16* __restrict__ matrix,
-                                                     const float* __restrict__ bias,
-                                                     const _Float16* __restrict__ x, float* __restrict__ h, int d,
-                                                     int batch, int capacity, size_t row_elems,
-                                                     const DevState* __restrict__ st) {
-    __shared__ float red[GLU ? 2 : 1][4][64][4];
+#ifndef LIF_MFMA_WAVES
+#define LIF_MFMA_WAVES 4
+#endif
+constexpr int kMfmaParts = 16;                   // parts of the k range, each summed from zero (see ffn_up_mfma_tile)
+constexpr int kMfmaWaves = LIF_MFMA_WAVES;       // waves per 16-row tile (each takes a contiguous part of the k-steps)
+#ifndef LIF_MFMA_WAVES_FIX
+#define LIF_MFMA_WAVES_FIX 16
+#endif
+constexpr int kMfmaWavesFix = LIF_MFMA_WAVES_FIX; // ... for the short pass over the rows a load wrote: few tiles, so a
+                                                  // tile is spread over 16 waves (one round of loads each)
+
+// Which rows a launch of the MFMA activation stage covers.
+enum MfmaRows {
+    kRowsAll = 0,     // slots [0, num_used)
+    kRowsKept = 1,    // slots [0, n_base): the rows that survive a pending deletion, while the loader role of the
+                      // same launch moves rows into holes and appends new ones (values of holes are recomputed later)
+    kRowsChanged = 2  // the slots the last load wrote: holes filled by a move, then the appended rows
+};
+
+// One 16-row tile.  `tile` indexes the list of rows of the given mode; entry e of the list is slot e for
+// kRowsAll / kRowsKept; for kRowsChanged it is move_dst[e] for e < n_removed (-1 = tail slot that was not
+// moved: skipped) and slot n_base + (e - n_removed) for the n_added entries after that.
+// Returns false (for the whole workgroup) when the tile lies past the end of the list.
+template <bool GLU, int MODE, int WAVES>
+__device__ __forceinline__ bool ffn_up_mfma_tile(const _Float16* __restrict__ matrix, const float* __restrict__ bias,
+                                                 const _Float16* __restrict__ x, float* __restrict__ h, int d,
+                                                 int batch, int capacity, size_t row_elems,
+                                                 const int32_t* __restrict__ move_dst, int tile,
+                                                 const DevState* __restrict__ st) {
+    __shared__ float red[GLU ? 2 : 1][kMfmaParts][64][4];
+    __shared__ int rows_lds[16];
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int i = lane & 15, q = lane >> 4;
     const int err = st->error;
-    const int n = st->num_used;
-    const int s0 = blockIdx.x * 16;
-    if (err || s0 >= n) return;                                   // uniform
+    const int n_removed = st->n_removed, n_base = st->n_base;
+    const int n = (MODE == kRowsAll) ? st->num_used : (MODE == kRowsKept) ? n_base : n_removed + st->n_added;
+    const int s0 = tile * 16;
+    if (err || s0 >= n) return false;                             // uniform
 
-    const int srow = min(s0 + i, capacity - 1);                   // rows past the cache end repeat the last one; masked below
-    const _Float16* grow = matrix + (size_t)srow * row_elems;
+    int srow = s0 + i;                                            // slot of list entry s0 + i (-1: none)
+    if (MODE == kRowsChanged) {
+        const int e = s0 + i;
+        srow = (e >= n) ? -1 : (e < n_removed ? move_dst[e] : n_base + (e - n_removed));
+        if (w == 0 && q == 0) rows_lds[i] = srow;
+    } else if (srow >= n) {
+        srow = -1;
+    }
+    const _Float16* grow = matrix + (size_t)min(max(srow, 0), capacity - 1) * row_elems;   // masked rows read slot 0
     const _Float16* urow = grow + (GLU ? d : 0);
     const bool xok = i < batch;
     const _Float16* xrow = x + (size_t)(xok ? i : 0) * d;
     const int nks = d >> 5;
 
-    f32x4 cu = {0.f, 0.f, 0.f, 0.f}, cg = {0.f, 0.f, 0.f, 0.f};
-    const int per = (nks + 3) >> 2;                               // k-steps per wave: a contiguous quarter of the row
-    const int ks_begin = w * per, ks_end = min(nks, ks_begin + per);
-    for (int ks0 = ks_begin; ks0 < ks_end; ks0 += kMfmaUnroll) {
-        f16x8 uf[kMfmaUnroll], gf[GLU ? kMfmaUnroll : 1], xf[kMfmaUnroll];
+    // The k-steps are cut into kMfmaParts contiguous parts, each accumulated from zero; wave w takes the parts
+    // w * PPW .. w * PPW + PPW - 1.  The parts are added in order below, so the result does not depend on
+    // how many waves share a tile.
+    constexpr int PPW = kMfmaParts / WAVES;
+    const int per = (nks + kMfmaParts - 1) / kMfmaParts;
 #pragma unroll
-        for (int u = 0; u < kMfmaUnroll; ++u) {
-            const int ks = ks0 + u;
-            const int off = (ks << 5) + (q << 3);
-            const bool in = ks < ks_end;
-            uf[u] = in ? *reinterpret_cast<const f16x8*>(urow + off) : f16x8(0);
-            if (GLU) gf[u] = in ? *reinterpret_cast<const f16x8*>(grow + off) : f16x8(0);
-            xf[u] = (in && xok) ? *reinterpret_cast<const f16x8*>(xrow + off) : f16x8(0);
+    for (int pp = 0; pp < PPW; ++pp) {
+        const int part = w * PPW + pp;
+        const int ks_begin = part * per, ks_end = min(nks, ks_begin + per);
+        f32x4 cu = {0.f, 0.f, 0.f, 0.f}, cg = {0.f, 0.f, 0.f, 0.f};
+        for (int ks0 = ks_begin; ks0 < ks_end; ks0 += kMfmaUnroll) {
+            f16x8 uf[kMfmaUnroll], gf[GLU ? kMfmaUnroll : 1], xf[kMfmaUnroll];
+#pragma unroll
+            for (int u = 0; u < kMfmaUnroll; ++u) {
+                const int ks = ks0 + u;
+                const int off = (ks << 5) + (q << 3);
+                const bool in = ks < ks_end;
+                uf[u] = in ? *reinterpret_cast<const f16x8*>(urow + off) : f16x8(0);
+                if (GLU) gf[u] = in ? *reinterpret_cast<const f16x8*>(grow + off) : f16x8(0);
+                xf[u] = (in && xok) ? *reinterpret_cast<const f16x8*>(xrow + off) : f16x8(0);
+            }
+#pragma unroll
+            for (int u = 0; u < kMfmaUnroll; ++u) {
+                cu = __builtin_amdgcn_mfma_f32_16x16x32_f16(uf[u], xf[u], cu, 0, 0, 0);
+                if (GLU) cg = __builtin_amdgcn_mfma_f32_16x16x32_f16(gf[u], xf[u], cg, 0, 0, 0);
+            }
         }
 #pragma unroll
-        for (int u = 0; u < kMfmaUnroll; ++u) {
-            cu = __builtin_amdgcn_mfma_f32_16x16x32_f16(uf[u], xf[u], cu, 0, 0, 0);
-            if (GLU) cg = __builtin_amdgcn_mfma_f32_16x16x32_f16(gf[u], xf[u], cg, 0, 0, 0);
+        for (int r = 0; r < 4; ++r) {
+            red[0][part][lane][r] = cu[r];
+            if (GLU) red[GLU ? 1 : 0][part][lane][r] = cg[r];
         }
-    }
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        red[0][w][lane][r] = cu[r];
-        if (GLU) red[GLU ? 1 : 0][w][lane][r] = cg[r];
     }
     __syncthreads();
     if (w == 0 && xok) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            const int row = s0 + 4 * q + r;
-            if (row < n) {
-                const float su = ((red[0][0][lane][r] + red[0][1][lane][r]) + red[0][2][lane][r]) + red[0][3][lane][r];
+            const int e = s0 + 4 * q + r;                         // list entry of D row 4q + r
+            const int row = (MODE == kRowsChanged) ? rows_lds[4 * q + r] : (e < n ? e : -1);
+            if (row >= 0) {
+                float su = 0.f;
+#pragma unroll
+                for (int ww = 0; ww < kMfmaParts; ++ww) su += red[0][ww][lane][r];
                 const float bs = bias[row];
                 float act;
                 if (GLU) {
-                    const float sg = ((red[GLU ? 1 : 0][0][lane][r] + red[GLU ? 1 : 0][1][lane][r]) +
-                                      red[GLU ? 1 : 0][2][lane][r]) + red[GLU ? 1 : 0][3][lane][r];
+                    float sg = 0.f;
+#pragma unroll
+                    for (int ww = 0; ww < kMfmaParts; ++ww) sg += red[GLU ? 1 : 0][ww][lane][r];
                     act = fmaxf(sg + bs, 0.f) * su;
                 } else {
                     act = fmaxf(su + bs, 0.f);
@@ -90,6 +133,22 @@ __global__ __launch_bounds__(256) void k_ffn_up_mfma(const _Float16* __restrict_
                 h[(size_t)i * capacity + row] = act;
             }
         }
+    }
+    return true;
+}
+
+template <bool GLU, int MODE, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void k_ffn_up_mfma(const _Float16* __restrict__ matrix,
+                                                                 const float* __restrict__ bias,
+                                                                 const _Float16* __restrict__ x, float* __restrict__ h,
+                                                                 int d, int batch, int capacity, size_t row_elems,
+                                                                 const int32_t* __restrict__ move_dst,
+                                                                 const DevState* __restrict__ st) {
+    // grid-stride over tiles (the grid may be smaller than the tile count; LDS is reused between tiles)
+    for (int tile = blockIdx.x;; tile += gridDim.x) {
+        if (!ffn_up_mfma_tile<GLU, MODE, WAVES>(matrix, bias, x, h, d, batch, capacity, row_elems, move_dst, tile, st))
+            break;
+        __syncthreads();
     }
 }
 

@@ -13,6 +13,7 @@
 #pragma once
 
 #include "lif_ffn.h"
+#include "lif_ffn_mfma.h"
 #include "lif_window.h"
 
 namespace lif {
@@ -235,6 +236,25 @@ __global__ __launch_bounds__(256) void k_load_up(T* __restrict__ matrix, int32_t
         ffn_up_role<T, NI, GLU, true>(matrix, bias, x, h, d, 1, capacity, row_elems, spec, blockIdx.x - load_wgs,
                                       gridDim.x - load_wgs, &st->n_base, pointers, gact, F, st);
     }
+}
+
+// The same overlap for a batch of tokens (fp16): loader workgroups (layout of k_load) next to the MFMA activation
+// stage over the rows that survive the deletion.  The slots the loaders write (filled holes, appended rows) get
+// their activations from a second, short launch of k_ffn_up_mfma<GLU, kRowsChanged> once the load is complete.
+// grid = load_wgs + ceil(capacity / 16), block = 256.
+template <bool GLU>
+__global__ __launch_bounds__(256) void k_load_up_mfma(_Float16* __restrict__ matrix, int32_t* __restrict__ pointers,
+                                                      float* __restrict__ bias, const char* __restrict__ host,
+                                                      const float* __restrict__ b, const int32_t* __restrict__ added,
+                                                      const int32_t* __restrict__ move_dst, size_t row_bytes, int F,
+                                                      const _Float16* __restrict__ x, float* __restrict__ h, int d,
+                                                      int batch, int capacity, int load_wgs, DevState* st) {
+    if ((int)blockIdx.x < load_wgs)
+        load_rows_role(reinterpret_cast<char*>(matrix), pointers, bias, host, b, added, move_dst, row_bytes, F,
+                       blockIdx.x, load_wgs, st);
+    else
+        ffn_up_mfma_tile<GLU, kRowsKept, 4>(matrix, bias, x, h, d, batch, capacity, row_bytes / sizeof(_Float16), move_dst,
+                                         blockIdx.x - load_wgs, st);
 }
 
 }  // namespace lif

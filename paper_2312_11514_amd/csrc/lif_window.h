@@ -335,18 +335,19 @@ constexpr int kLoadPer = 4;
 constexpr size_t kLoadChunk = 256 * 16 * kLoadPer;
 constexpr int kLoadGrid = 32;
 
-__global__ __launch_bounds__(256) void k_load(char* __restrict__ matrix, int32_t* __restrict__ pointers,
-                                              float* __restrict__ bias, const char* __restrict__ host,
-                                              const float* __restrict__ b, const int32_t* __restrict__ added,
-                                              const int32_t* __restrict__ move_dst, size_t row_bytes, int F,
-                                              DevState* st) {
+// `block` / `nblocks`: index and count of the workgroups that share this role.
+__device__ __forceinline__ void load_rows_role(char* __restrict__ matrix, int32_t* __restrict__ pointers,
+                                               float* __restrict__ bias, const char* __restrict__ host,
+                                               const float* __restrict__ b, const int32_t* __restrict__ added,
+                                               const int32_t* __restrict__ move_dst, size_t row_bytes, int F,
+                                               int block, int nblocks, DevState* st) {
     if (st->error) return;
     const int n2 = st->n_base, c = st->n_removed, a = st->n_added;
     const int items = max(c, a);
     const int cpr = (int)((row_bytes + kLoadChunk - 1) / kLoadChunk);
     const long long total = (long long)items * cpr;
     const int tid = threadIdx.x;
-    for (long long it = blockIdx.x; it < total; it += gridDim.x) {
+    for (long long it = block; it < total; it += nblocks) {
         const int q = (int)(it / cpr), ch = (int)(it - (long long)q * cpr);
         const int s = n2 + q;
         const int dst = (q < c) ? move_dst[q] : -1;
@@ -390,10 +391,18 @@ __global__ __launch_bounds__(256) void k_load(char* __restrict__ matrix, int32_t
             }
         }
     }
-    if (blockIdx.x == 0 && tid == 0) {
+    if (block == 0 && tid == 0) {
         st->num_used = n2 + a;
         st->c_h2d_bytes += (unsigned long long)a * row_bytes;
     }
+}
+
+__global__ __launch_bounds__(256) void k_load(char* __restrict__ matrix, int32_t* __restrict__ pointers,
+                                              float* __restrict__ bias, const char* __restrict__ host,
+                                              const float* __restrict__ b, const int32_t* __restrict__ added,
+                                              const int32_t* __restrict__ move_dst, size_t row_bytes, int F,
+                                              DevState* st) {
+    load_rows_role(matrix, pointers, bias, host, b, added, move_dst, row_bytes, F, blockIdx.x, gridDim.x, st);
 }
 
 // Empty cache: no mask in the window, state and counters zero.

@@ -97,6 +97,7 @@ def test_c4_llama_shape_gated_batch8():
     L = wl.cached_layer("C4")            # same layer as the batch-1 run
     X = wl.make_batch_inputs(w, tokens=10)
     stats = run_stream(w, L, X, check_every=3)
+    run_stream(w, L, X, check_every=3, api="step")
     print("C4b8 max rel-L2 %.2e, rows %.0f" % (max(s["err"] for s in stats), np.mean([s["n"] for s in stats[4:]])))
 
 
@@ -298,18 +299,21 @@ def test_row_count_hint_never_changes_results(hint):
     assert ys[0] == ys[1]
 
 
+@pytest.mark.parametrize("api", ["calls", "step"])
 @pytest.mark.parametrize("batch", [2, 5, 8])
 @pytest.mark.parametrize("glu", [False, True])
 @pytest.mark.parametrize("d_model,dtype", [(608, "f16"), (128, "f16"), (568, "f16"), (256, "f32")])
-def test_batched_tokens_small_shapes(d_model, dtype, glu, batch):
+def test_batched_tokens_small_shapes(d_model, dtype, glu, batch, api):
     """Batches of 2..8 tokens sharing one cache.  fp16 with d % 32 == 0 runs the MFMA activation kernel
     (d = 608 = 19 x 32: a k-step count that does not divide by the four waves; capacity and row counts
-    not multiples of the 16-row tile); d = 568 and fp32 run the streaming kernel."""
+    not multiples of the 16-row tile); d = 568 and fp32 run the streaming kernel.  api = "step": for the MFMA
+    shapes the bundle load runs next to the activation stage of the surviving rows and the rows it wrote
+    are computed in a second pass."""
     w = wl.scaled(wl.WORKLOADS["C1"], name="batched", d_model=d_model, d_ffn=1096, rank=40, window_k=3,
                   p_active=0.06, dtype=dtype, glu=glu, tokens=10, batch=batch, capacity_rows=1003)
     L = wl.make_layer(w)
     X = wl.make_batch_inputs(w)
-    stats = run_stream(w, L, X)
+    stats = run_stream(w, L, X, api=api)
     assert np.mean([s["n"] for s in stats]) > 100
 
 
@@ -338,6 +342,29 @@ def test_fused_step_equals_four_calls_bit_for_bit():
         assert res[0][0].tobytes() == res[1][0].tobytes(), name
         ca, cb = res[0][5], res[1][5]
         assert ca["h2d_bytes"] == cb["h2d_bytes"] and ca["rows_moved"] == cb["rows_moved"]
+
+
+def test_fused_step_equals_four_calls_bit_for_bit_batched():
+    """Batch of 8 tokens (MFMA activation stage): lif_step overlaps the bundle load with the activations of the
+    surviving rows and recomputes the slots the load wrote; every output byte equals the four separate calls."""
+    from tests.harness import GpuLayer
+    w = wl.scaled(wl.WORKLOADS["C1"], name="batched", d_model=608, d_ffn=2200, rank=40, window_k=3, p_active=0.06,
+                  dtype="f16", glu=True, tokens=14, batch=8, capacity_rows=2003)
+    L = wl.make_layer(w)
+    X = wl.make_batch_inputs(w)
+    res = []
+    for api in ("calls", "step"):
+        gpu = GpuLayer(w, L)
+        lay = gpu.layer
+        xd = gpu.upload_x(X)
+        y = torch.zeros_like(xd)
+        for t in range(w.tokens):
+            (lay.step if api == "step" else lay.step_calls)(xd[t], y[t], w.batch)
+        n = lay.state()["num_used"]
+        res.append((y.cpu().numpy().tobytes(), lay.pointers[:n].cpu().numpy().tobytes(),
+                    lay.matrix[:n].cpu().numpy().tobytes(), lay.masks.cpu().numpy().tobytes()))
+        assert n > 300 and lay.counters()["rows_moved"] > 0
+    assert res[0] == res[1]
 
 
 @pytest.mark.parametrize("api", ["calls", "step"])
