@@ -51,9 +51,22 @@ def cpu_baseline(w, L, X, budget_s=20.0):
         if time.perf_counter() - t0 > budget_s:
             break
     dt = time.perf_counter() - t0
-    return {"value": dt / done * 1e6, "unit": "us/token/layer", "cores": int(cores), "kind": "oracle",
-            "sample": f"first {done} steps of the same stream on layer 0, whole path "
-                      f"(predict, window, delete, insert, FFN)"}
+    out = {"value": dt / done * 1e6, "unit": "us/token/layer", "cores": int(cores), "kind": "oracle",
+           "sample": f"first {done} steps of the same stream on layer 0, whole path "
+                     f"(predict, window, delete, insert, FFN)"}
+    # untimed: how good the synthetic predictor is on a few tokens (the oracle's mask against the sign of the
+    # true pre-activation) - describes the workload, not the kernels
+    import numpy as np
+    xs = X[:8].reshape(-1, X.shape[-1])[:8]
+    w_act = L.w_gate if L.w_gate is not None else L.w_up
+    hit = pred = true = 0
+    for x in xs:
+        m = np.asarray(ora.predict(x)).reshape(-1)
+        tm = O.true_mask(w_act, L.b, x)
+        hit += int((m & tm).sum()); pred += int(m.sum()); true += int(tm.sum())
+    out["predictor_recall"] = hit / max(true, 1)
+    out["predictor_precision"] = hit / max(pred, 1)
+    return out
 
 
 def pmc_traffic(pmc_dir):
@@ -239,6 +252,11 @@ def main():
     ap.add_argument("--pmc-dir", default=None,
                     help="directory with the rocprofv3 --pmc outputs of this script; fills roofline.traffic")
     ap.add_argument("--no-hint", action="store_true", help="do not give the library the expected number of cached rows")
+    ap.add_argument("--structured", action="store_true",
+                    help="second workload: 1/j singular spectrum of the ReLU'd projection, so that the rank-r predictor "
+                         "is accurate (labelled in the output; never mixed with the default)")
+    ap.add_argument("--overpredict", type=float, default=1.0,
+                    help="predictor calibrated to fire on overpredict * p_active of the neurons")
     ap.add_argument("--sweep", default=None, choices=["k", "chunk", "rows"],
                     help="instead of the bench line: window-size sweep or chunk-size sweep (one JSON line each)")
     args = ap.parse_args()
@@ -274,7 +292,7 @@ def main():
     mode = {"skip": lif.FFN_SKIP_DEAD, "full": lif.FFN_FULL_BUNDLE}[args.ffn_mode]
     reads_all = args.ffn_mode == "full"
 
-    base = wl.make_layer(w)
+    base = wl.make_layer(w, structured=args.structured, overpredict=args.overpredict)
     spec = w.spec_keep > 0
     X = wl.make_inputs(w) if (w.batch == 1 or spec) else wl.make_batch_inputs(w)
     if spec:
@@ -299,10 +317,7 @@ def main():
             lay0.reset()
             for t in range(T):
                 if spec:
-                    lay0.predict(xd[t], w.batch)
-                    lay0.update_window_tokens(w.batch, w.spec_keep)
-                    lay0.load_bundles()
-                    lay0.sparse_ffn(xd[t], yd[0, t], w.batch)
+                    lay0.step_tokens(xd[t], yd[0, t], w.batch, w.spec_keep)
                 else:
                     lay0.step(xd[t], yd[0, t], w.batch)
         graph = None
@@ -437,7 +452,9 @@ def main():
         "value": us_per_token_layer, "unit": "us/token/layer", "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": ms_per_step, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",
-        "config": {"workload": describe(w), "tokens_per_step": T, "layers": NL, "ffn_mode": args.ffn_mode,
+        "config": {"workload": describe(w) + (" structured-spectrum" if args.structured else "") +
+                               (f" overpredict={args.overpredict}" if args.overpredict != 1.0 else ""),
+                   "tokens_per_step": T, "layers": NL, "ffn_mode": args.ffn_mode,
                    "launch": launch,
                    "llc": ("single layer: the cache working set stays warm in the 256 MB Infinity Cache" if NL == 1 else
                            f"{NL} layers rotate {NL * nominal / 1e6:.0f} MB of cached rows per token: FFN reads come from HBM")},

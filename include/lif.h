@@ -241,15 +241,26 @@ int lif_sparse_ffn(lif_layer* layer, const void* x_dev, int32_t batch, void* y_d
 /*
  * One whole step in one call: lif_predict, lif_update_window, lif_load_bundles and
  * lif_sparse_ffn on the same x, with the same arguments, results and error behaviour as the
- * four calls in sequence.  For batch == 1 the cache update and the activation stage of the
- * FFN share one launch: the host-link gather keeps few compute units busy, the others compute
- * the activations of the resident rows meanwhile, and the loaders compute those of the rows
- * they write (Section 3.3 items 2 and 3 overlapped), with the same summation order.  y, masks,
- * ids, counts and the cache are bit-identical to the four-call sequence.
+ * four calls in sequence.  The cache update and the activation stage of the FFN share one
+ * launch: the host-link gather keeps few compute units busy, the others compute the
+ * activations of the resident rows meanwhile (Section 3.3 items 2 and 3 overlapped).  For
+ * batch == 1 the loaders compute the activations of the rows they write, with the same
+ * summation order; for fp16 batches a short second pass covers those rows.  y, masks, ids,
+ * counts and the cache are bit-identical to the four-call sequence.
  */
 int lif_step(lif_layer* layer, const void* x_dev, int32_t batch, void* y_dev, uint8_t* masks_dev,
              uint8_t* step_mask_dev, int32_t* added_dev, int32_t* n_added_dev, int32_t* removed_dev,
              int32_t* n_removed_dev, void* stream);
+
+/*
+ * One speculative verification pass in one call (Section 4.3): lif_predict on the n_tokens
+ * consecutive tokens of x, lif_update_window_tokens with keep_tokens, lif_load_bundles and
+ * lif_sparse_ffn, with the same arguments, results and error behaviour as those four calls in
+ * sequence, and the same shared launches as lif_step.
+ */
+int lif_step_tokens(lif_layer* layer, const void* x_dev, int32_t n_tokens, int32_t keep_tokens, void* y_dev,
+                    uint8_t* masks_dev, uint8_t* step_mask_dev, int32_t* added_dev, int32_t* n_added_dev,
+                    int32_t* removed_dev, int32_t* n_removed_dev, void* stream);
 
 /*
  * Performance hint: the number of rows the cache

@@ -56,6 +56,8 @@ EXPORTS = {
     "lif_load_bundles": (C.c_int, [C.c_void_p] + [C.c_void_p] * 4 + [C.c_void_p]),
     "lif_sparse_ffn": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]),
     "lif_step": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p] + [C.c_void_p] * 6 + [C.c_void_p]),
+    "lif_step_tokens": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p] + [C.c_void_p] * 6 +
+                        [C.c_void_p]),
     "lif_set_expected_rows": (C.c_int, [C.c_void_p, C.c_int32]),
     "lif_get_state": (C.c_int, [C.c_void_p, C.POINTER(LifState), C.c_void_p]),
     "lif_get_counters": (C.c_int, [C.c_void_p, C.POINTER(LifCounters), C.c_void_p]),
@@ -193,6 +195,12 @@ class Layer:
         _check(self.lib.lif_step(self.handle, _ptr(x), batch, _ptr(y), _ptr(self.masks), _ptr(self.step_mask),
                                  _ptr(self.added), _ptr(self.n_added), _ptr(self.removed), _ptr(self.n_removed),
                                  _stream()))
+
+    def step_tokens(self, x, y, n_tokens, keep_tokens):
+        """lif_step_tokens: one speculative verification pass in one call."""
+        _check(self.lib.lif_step_tokens(self.handle, _ptr(x), n_tokens, keep_tokens, _ptr(y), _ptr(self.masks),
+                                        _ptr(self.step_mask), _ptr(self.added), _ptr(self.n_added),
+                                        _ptr(self.removed), _ptr(self.n_removed), _stream()))
 
     def step_calls(self, x, y, batch=1):
         """The same step as four separate calls: predict -> update_window -> load_bundles -> sparse_ffn."""

@@ -286,6 +286,8 @@ void launch_load_up(lif_layer* L, const void* x, const int32_t* added, hipStream
 #undef LIF_LU
 }
 
+constexpr int kFuseBatchedMinRows = 2048;
+
 bool mfma_path(const lif_config& c, int batch) {
     return !LIF_NO_MFMA && c.dtype == LIF_F16 && batch > 1 && c.d_model % 32 == 0;
 }
@@ -509,17 +511,24 @@ int lif_sparse_ffn(lif_layer* L, const void* x_dev, int32_t batch, void* y_dev, 
     return check_launch();
 }
 
-int lif_step(lif_layer* L, const void* x_dev, int32_t batch, void* y_dev, uint8_t* masks_dev,
-             uint8_t* step_mask_dev, int32_t* added_dev, int32_t* n_added_dev, int32_t* removed_dev,
-             int32_t* n_removed_dev, void* stream) {
+// keep < 0: the window advances by one step whose mask is the OR over the batch (lif_update_window);
+// keep >= 0: token-granular update of a speculative pass (lif_update_window_tokens)
+static int step_impl(lif_layer* L, const void* x_dev, int32_t batch, int32_t keep, void* y_dev, uint8_t* masks_dev,
+                     uint8_t* step_mask_dev, int32_t* added_dev, int32_t* n_added_dev, int32_t* removed_dev,
+                     int32_t* n_removed_dev, void* stream) {
     int rc = lif_predict(L, x_dev, batch, masks_dev, step_mask_dev, stream);
     if (rc) return rc;
     if (!y_dev || (uintptr_t)y_dev % 16) return fail(LIF_INVALID_ARG, "y must be a 16-byte aligned device pointer");
-    rc = lif_update_window(L, step_mask_dev, added_dev, n_added_dev, removed_dev, n_removed_dev, stream);
+    rc = keep < 0 ? lif_update_window(L, step_mask_dev, added_dev, n_added_dev, removed_dev, n_removed_dev, stream)
+                  : lif_update_window_tokens(L, masks_dev, batch, keep, added_dev, n_added_dev, removed_dev,
+                                             n_removed_dev, stream);
     if (rc) return rc;
     hipStream_t s = (hipStream_t)stream;
     const lif_config& c = L->cfg;
-    if (batch > 1 && !mfma_path(c, batch)) {
+    // batch > 1: sharing a launch between the load and the activation stage pays once the activation stage over
+    // all rows takes longer than the second pass over the rows the load wrote (about 2000 rows in use)
+    const int rows_hint = L->expected_rows > 0 ? L->expected_rows : c.capacity_rows;
+    if (batch > 1 && (!mfma_path(c, batch) || rows_hint < kFuseBatchedMinRows)) {
         rc = lif_load_bundles(L, added_dev, n_added_dev, removed_dev, n_removed_dev, stream);
         if (rc) return rc;
         return lif_sparse_ffn(L, x_dev, batch, y_dev, stream);
@@ -555,6 +564,21 @@ int lif_step(lif_layer* L, const void* x_dev, int32_t batch, void* y_dev, uint8_
         else launch_ffn_down<_Float16>(L, 1, y_dev, s, true);
     }
     return check_launch();
+}
+
+int lif_step(lif_layer* L, const void* x_dev, int32_t batch, void* y_dev, uint8_t* masks_dev,
+             uint8_t* step_mask_dev, int32_t* added_dev, int32_t* n_added_dev, int32_t* removed_dev,
+             int32_t* n_removed_dev, void* stream) {
+    return step_impl(L, x_dev, batch, -1, y_dev, masks_dev, step_mask_dev, added_dev, n_added_dev, removed_dev,
+                     n_removed_dev, stream);
+}
+
+int lif_step_tokens(lif_layer* L, const void* x_dev, int32_t n_tokens, int32_t keep_tokens, void* y_dev,
+                    uint8_t* masks_dev, uint8_t* step_mask_dev, int32_t* added_dev, int32_t* n_added_dev,
+                    int32_t* removed_dev, int32_t* n_removed_dev, void* stream) {
+    if (keep_tokens < 0) return fail(LIF_INVALID_ARG, "keep must be in 0..n_tokens");
+    return step_impl(L, x_dev, n_tokens, keep_tokens, y_dev, masks_dev, step_mask_dev, added_dev, n_added_dev,
+                     removed_dev, n_removed_dev, stream);
 }
 
 int lif_set_expected_rows(lif_layer* L, int32_t rows) {

@@ -54,22 +54,31 @@ __device__ __forceinline__ bool ffn_up_mfma_tile(const _Float16* __restrict__ ma
                                                  const int32_t* __restrict__ move_dst, int tile,
                                                  const DevState* __restrict__ st) {
     __shared__ float red[GLU ? 2 : 1][kMfmaParts][64][4];
-    __shared__ int rows_lds[16];
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int i = lane & 15, q = lane >> 4;
+    const int s0 = tile * 16;
+    // requested together with the state (the list spans the capacity, so the address is valid; masked below)
+    int moved_to = -1;
+    if (MODE == kRowsChanged && s0 + i < capacity) moved_to = move_dst[s0 + i];
     const int err = st->error;
     const int n_removed = st->n_removed, n_base = st->n_base;
     const int n = (MODE == kRowsAll) ? st->num_used : (MODE == kRowsKept) ? n_base : n_removed + st->n_added;
-    const int s0 = tile * 16;
     if (err || s0 >= n) return false;                             // uniform
 
     int srow = s0 + i;                                            // slot of list entry s0 + i (-1: none)
     if (MODE == kRowsChanged) {
         const int e = s0 + i;
-        srow = (e >= n) ? -1 : (e < n_removed ? move_dst[e] : n_base + (e - n_removed));
-        if (w == 0 && q == 0) rows_lds[i] = srow;
+        srow = (e >= n) ? -1 : (e < n_removed ? moved_to : n_base + (e - n_removed));
     } else if (srow >= n) {
         srow = -1;
+    }
+    // the lane that finishes D rows 4q .. 4q + 3 for token i asks for their biases now, ahead of the row loads
+    int orow[4];
+    float obias[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        orow[r] = __shfl(srow, 4 * q + r, kWave);                 // lane j < 16 holds the slot of tile row j
+        obias[r] = (w == 0 && orow[r] >= 0) ? bias[orow[r]] : 0.f;
     }
     const _Float16* grow = matrix + (size_t)min(max(srow, 0), capacity - 1) * row_elems;   // masked rows read slot 0
     const _Float16* urow = grow + (GLU ? d : 0);
@@ -114,13 +123,12 @@ __device__ __forceinline__ bool ffn_up_mfma_tile(const _Float16* __restrict__ ma
     if (w == 0 && xok) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            const int e = s0 + 4 * q + r;                         // list entry of D row 4q + r
-            const int row = (MODE == kRowsChanged) ? rows_lds[4 * q + r] : (e < n ? e : -1);
+            const int row = orow[r];
             if (row >= 0) {
                 float su = 0.f;
 #pragma unroll
                 for (int ww = 0; ww < kMfmaParts; ++ww) su += red[0][ww][lane][r];
-                const float bs = bias[row];
+                const float bs = obias[r];
                 float act;
                 if (GLU) {
                     float sg = 0.f;

@@ -315,6 +315,14 @@ def test_batched_tokens_small_shapes(d_model, dtype, glu, batch, api):
     X = wl.make_batch_inputs(w)
     stats = run_stream(w, L, X, api=api)
     assert np.mean([s["n"] for s in stats]) > 100
+    if api == "step" and dtype == "f16" and d_model % 32 == 0:
+        # the same stream with a row-count hint large enough for the shared load + activation launch
+        from tests.harness import GpuLayer, compare_step
+        gpu = GpuLayer(w, L)
+        gpu.layer.set_expected_rows(4096)
+        ora = make_oracle(w, L)
+        for t in range(len(X)):
+            compare_step(gpu, ora, X[t], w, t, api="step")
 
 
 def test_fused_step_equals_four_calls_bit_for_bit():
@@ -349,7 +357,7 @@ def test_fused_step_equals_four_calls_bit_for_bit_batched():
     surviving rows and recomputes the slots the load wrote; every output byte equals the four separate calls."""
     from tests.harness import GpuLayer
     w = wl.scaled(wl.WORKLOADS["C1"], name="batched", d_model=608, d_ffn=2200, rank=40, window_k=3, p_active=0.06,
-                  dtype="f16", glu=True, tokens=14, batch=8, capacity_rows=2003)
+                  dtype="f16", glu=True, tokens=14, batch=8, capacity_rows=2100)   # >= 2048 rows: the shared launch is used
     L = wl.make_layer(w)
     X = wl.make_batch_inputs(w)
     res = []
@@ -417,8 +425,9 @@ def test_n1_dynamic_window_at_opt_shape():
     assert min(lens[8:]) < w.window_k
 
 
+@pytest.mark.parametrize("api", ["calls", "step"])
 @pytest.mark.parametrize("glu,dtype,d_model", [(False, "f16", 256), (True, "f16", 608), (False, "f32", 256)])
-def test_speculative_verify_passes_token_granular_window(glu, dtype, d_model):
+def test_speculative_verify_passes_token_granular_window(glu, dtype, d_model, api):
     """Passes of lambda + 1 = 5 consecutive tokens with a varying number of kept tokens (Section 4.3): per-token
     masks, window entries per token, transient masks leaving with the next pass, FFN for all five tokens."""
     from tests.harness import GpuLayer, rel_l2, REL_L2_TOL
@@ -434,13 +443,16 @@ def test_speculative_verify_passes_token_granular_window(glu, dtype, d_model):
         xb = X[5 * p:5 * p + 5]
         ref = ora.step_tokens(xb, keep)
         xd = gpu.upload_x(xb)
-        lay.predict(xd, 5)
-        lay.update_window_tokens(5, keep)
+        if api == "step":
+            lay.step_tokens(xd, gpu.y, 5, keep)                     # the whole pass in one call
+        else:
+            lay.predict(xd, 5)
+            lay.update_window_tokens(5, keep)
+            lay.load_bundles()
+            lay.sparse_ffn(xd, gpu.y, 5)
         na, nr = int(lay.n_added.item()), int(lay.n_removed.item())
         assert lay.added[:na].cpu().numpy().tolist() == ref["added"].tolist(), f"pass {p}"
         assert lay.removed[:nr].cpu().numpy().tolist() == ref["removed"].tolist(), f"pass {p}"
-        lay.load_bundles()
-        lay.sparse_ffn(xd, gpu.y, 5)
         st = lay.state()
         n = ref["num_used"]
         assert st["error"] == 0 and st["num_used"] == n and st["window_len"] == len(ora.window.masks)
