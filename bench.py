@@ -100,7 +100,7 @@ def sweep_window(args):
     larger windows hold more rows in the cache and load fewer bytes per token."""
     import torch
     import workloads as wl
-    from tests.harness import GpuLayer
+    from workloads.device import GpuLayer
     base_w = wl.WORKLOADS[args.workload]
     L = wl.make_layer(base_w)
     X = wl.make_inputs(base_w)
@@ -190,7 +190,7 @@ def sweep_rows(args):
     import torch
     import workloads as wl
     import paper_2312_11514_amd as lif
-    from tests.harness import GpuLayer
+    from workloads.device import GpuLayer
     w0 = wl.WORKLOADS[args.workload]
     w = wl.scaled(w0, capacity_rows=w0.d_ffn)
     L = wl.make_layer(w)
@@ -275,7 +275,7 @@ def main():
     import torch
     import workloads as wl
     import paper_2312_11514_amd as lif
-    from tests.harness import GpuLayer
+    from workloads.device import GpuLayer
 
     if args.pmc_copy:
         src = torch.ones(128 * 1024 * 1024, dtype=torch.float16, device="cuda:0")      # 256 MiB read + 256 MiB written
