@@ -97,7 +97,15 @@ __global__ __launch_bounds__(kScanThreads) void k_window_plan(
     unsigned long long rv[kRingRegs];
 #pragma unroll
     for (int j = 0; j < kRingRegs; ++j) rv[j] = (have && j < k) ? ring[(size_t)j * ring_words + tid] : 0ull;
-    int ptr0 = (tid < capacity) ? pointers[tid] : -1;
+    // slot owners of the first four blocks of this wave (4 x 1024 slots), for the deletion plan below; the
+    // array spans the capacity, entries past num_used are masked when used
+    constexpr int kPtrPre = 4;
+    int idpre[kPtrPre];
+#pragma unroll
+    for (int it = 0; it < kPtrPre; ++it) {
+        const int s = (w + it * NW) * kWave + lane;
+        idpre[it] = (s < capacity) ? pointers[s] : -1;
+    }
     const int err = st->error;
     const int t = st->step;
     const int n = st->num_used;
@@ -140,7 +148,7 @@ __global__ __launch_bounds__(kScanThreads) void k_window_plan(
         if (have) {
             for (int i = 0; i < ntok; ++i) now |= load_mask_word(step_mask + (size_t)i * row_bytes, tid, nbytes);
             for (int j = 0; j < k; ++j) {
-                const int since = ((j - pos) % k + k) % k;   // this entry is overwritten by kept token `since`
+                const int since = j - pos + (j < pos ? k : 0);   // (j - pos) mod k: this entry is overwritten by kept token `since`
                 if (since >= keep_tok) now |= ring[(size_t)j * ring_words + tid];
             }
         }
@@ -151,6 +159,9 @@ __global__ __launch_bounds__(kScanThreads) void k_window_plan(
         // union fits the capacity.  U_a = union of the newest a masks (a = 1: this step's mask).
         for (int a = tid; a < k; a += kScanThreads) cnt_age[a] = 0;
         __syncthreads();
+        int age_of[kRingRegs];                           // age of ring entry j: (slot - j) mod k, 0 for j == slot
+#pragma unroll
+        for (int j = 0; j < kRingRegs; ++j) age_of[j] = slot - j + (slot < j ? k : 0);
         if (k <= kRingRegs) {
             // all ring words are in registers: age of ring entry j is (slot - j) mod k (uniform), the entry
             // at `slot` itself is the one being overwritten.  Per-wave sums (two 16-bit counts per
@@ -162,10 +173,8 @@ __global__ __launch_bounds__(kScanThreads) void k_window_plan(
             for (int a = 1; a <= kRingRegs; ++a) {
                 unsigned long long u = m;
 #pragma unroll
-                for (int j = 0; j < kRingRegs; ++j) {
-                    const int age = (slot - j + k) % k;          // 0 for j == slot
-                    if (j < k && j != slot && age < a) u |= rv[j];
-                }
+                for (int j = 0; j < kRingRegs; ++j)
+                    if (j < k && j != slot && age_of[j] < a) u |= rv[j];
                 if (a <= k) pk[(a - 1) >> 1] |= (unsigned)__popcll(u) << (((a - 1) & 1) * 16);
             }
 #pragma unroll
@@ -203,10 +212,8 @@ __global__ __launch_bounds__(kScanThreads) void k_window_plan(
         now = m;
         if (k <= kRingRegs) {
 #pragma unroll
-            for (int j = 0; j < kRingRegs; ++j) {
-                const int age = (slot - j + k) % k;
-                if (j < k && j != slot && age < k_eff) now |= rv[j];
-            }
+            for (int j = 0; j < kRingRegs; ++j)
+                if (j < k && j != slot && age_of[j] < k_eff) now |= rv[j];
         } else if (have) {
             for (int a = 2; a <= k_eff; ++a) now |= ring[(size_t)((slot - (a - 1) + k) % k) * ring_words + tid];
         }
@@ -255,7 +262,16 @@ __global__ __launch_bounds__(kScanThreads) void k_window_plan(
     unsigned long long holebits = 0, fillbits = 0;   // bit it = flag of this lane in its it-th block
     for (int b = w, it = 0; b < nblk; b += NW, ++it) {
         const int s = b * kWave + lane;
-        const int id = (it == 0) ? ptr0 : ((s < n) ? pointers[s] : -1);
+        int id;
+        if (it < kPtrPre) {                          // requested with the state
+            id = idpre[0];
+#pragma unroll
+            for (int q = 1; q < kPtrPre; ++q)
+                if (it == q) id = idpre[q];
+            if (s >= n) id = -1;
+        } else {
+            id = (s < n) ? pointers[s] : -1;
+        }
         bool hole = false, fill = false;
         if (s < n) {
             const bool dead = (id < 0 || id >= F) ? true : ((rem64[id >> 6] >> (id & 63)) & 1ull);
