@@ -140,6 +140,35 @@ def test_maximum_sizes_long_hole_list():
     assert max(s["moved"] for s in stats) > 4096
 
 
+def _random_predictor_layer(w, seed):
+    """A layer with a random (not SVD-derived) predictor: the decomposition of a d = 8192 projection takes half
+    a minute on the host and the kernels do not care where A and B come from."""
+    rng = np.random.default_rng(seed)
+    d, F, r, dt = w.d_model, w.d_ffn, w.rank, w.np_dtype
+    g = lambda *shape: rng.standard_normal(shape, dtype=np.float32)
+    w_up, w_down = (g(F, d) / np.sqrt(d)).astype(dt), (g(F, d) / np.sqrt(d)).astype(dt)
+    w_gate = (g(F, d) / np.sqrt(d)).astype(dt) if w.glu else None
+    w_act = w_gate if w.glu else w_up
+    b = (-1.4 * np.linalg.norm(w_act.astype(np.float64), axis=1)).astype(np.float32)
+    A, B = (g(d, r) / np.sqrt(d)).astype(dt), g(r, F).astype(dt)
+    c = np.full(F, -1.4 * np.sqrt(r), np.float32)            # about 8 % of the logits are positive
+    parts = ([w_gate] if w.glu else []) + [w_up, w_down]
+    return wl.LayerData(w_up, w_down, w_gate, b, A, B, c, 0.0, np.ascontiguousarray(np.concatenate(parts, axis=1)))
+
+
+@pytest.mark.parametrize("api", ["calls", "step"])
+@pytest.mark.parametrize("glu,batch", [(False, 1), (True, 1), (True, 4)])
+def test_widest_rows(glu, batch, api):
+    """d_model = 8192 in fp16: the largest row the kernels take (16 loads of 16 bytes per lane and vector),
+    32 KiB and 48 KiB bundles; batch 4 runs the MFMA activation stage at this width."""
+    w = wl.scaled(wl.WORKLOADS["C1"], name="wide", d_model=8192, d_ffn=512, rank=16, window_k=3, p_active=0.08,
+                  dtype="f16", glu=glu, tokens=8, batch=batch, capacity_rows=300)
+    L = _random_predictor_layer(w, seed=5)
+    X = wl.make_inputs(w) if batch == 1 else wl.make_batch_inputs(w)
+    stats = run_stream(w, L, X, api=api)
+    assert np.mean([s["n"] for s in stats]) > 30
+
+
 def test_capacity_overflow_sets_sticky_error_and_leaves_state():
     from tests.harness import GpuLayer
     import paper_2312_11514_amd as lif
@@ -461,6 +490,22 @@ def test_speculative_verify_passes_token_granular_window(glu, dtype, d_model, ap
         assert lay.matrix[:n].cpu().numpy().tobytes() == ora.cache.matrix[:n].tobytes()
         assert rel_l2(gpu.y[:5].cpu().numpy(), ref["y"]) <= REL_L2_TOL
     assert lay.counters()["h2d_bytes"] == ora.bytes_loaded
+    # passes of a single token, kept or not (the one-token form of the same call)
+    for i, keep in enumerate([0, 1, 0]):
+        xb = X[50 + i:51 + i]
+        ref = ora.step_tokens(xb, keep)
+        xd = gpu.upload_x(xb)
+        if api == "step":
+            lay.step_tokens(xd, gpu.y, 1, keep)
+        else:
+            lay.predict(xd, 1)
+            lay.update_window_tokens(1, keep)
+            lay.load_bundles()
+            lay.sparse_ffn(xd, gpu.y, 1)
+        n = ref["num_used"]
+        assert lay.state()["num_used"] == n and lay.state()["window_len"] == len(ora.window.masks)
+        assert (lay.pointers[:n].cpu().numpy() == ora.cache.pointers[:n]).all()
+        assert rel_l2(gpu.y[:1].cpu().numpy(), ref["y"]) <= REL_L2_TOL
     # mixing with ordinary single-token steps on the same layer
     from tests.harness import compare_step
     w1 = wl.scaled(w, batch=1)
