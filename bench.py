@@ -312,10 +312,10 @@ def main():
 
     if NL == 1:
         # whole token stream of the layer in one HIP graph
-        def run_stream():
+        def run_stream(tokens=None):
             lay0 = layers[0]
             lay0.reset()
-            for t in range(T):
+            for t in range(T if tokens is None else tokens):
                 if spec:
                     lay0.step_tokens(xd[t], yd[0, t], w.batch, w.spec_keep)
                 else:
@@ -392,6 +392,40 @@ def main():
     ms_per_step = dt / steps * 1e3
     us_per_token_layer = ms_per_step * 1e3 / T / NL
 
+    # steady state (single layer, graph launches): the first 2k steps fill the cache and load far more than the
+    # later ones; a second graph over just those steps is timed and subtracted
+    steady = None
+    Wm = 2 * w.window_k
+    if NL == 1 and graph is not None and T > 2 * Wm:
+        gw = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(gw):
+            run_stream(Wm)
+        gw.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            gw.replay()
+        torch.cuda.synchronize()
+        warm_ms = (time.perf_counter() - t0) / steps * 1e3
+        steady = {"first_steps_excluded": Wm, "us_per_step": (ms_per_step - warm_ms) * 1e3 / (T - Wm),
+                  "us_per_step_in_the_first_steps": warm_ms * 1e3 / Wm}
+
+    # host link reference on the same box: one large pinned-to-device copy by the runtime (copy engine)
+    h2d_ref = None
+    if not args.no_profile:
+        src = torch.empty(256 * 1024 * 1024, dtype=torch.uint8).pin_memory()
+        dst = torch.empty(256 * 1024 * 1024, dtype=torch.uint8, device=xd.device)
+        dst.copy_(src, non_blocking=True)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(3):
+            dst.copy_(src, non_blocking=True)
+        e1.record()
+        torch.cuda.synchronize()
+        h2d_ref = 3 * src.numel() / (e0.elapsed_time(e1) * 1e-3) / 1e9
+        del src, dst
+
     # FFN alone, on the cache state the stream ends in: R rounds of lif_sparse_ffn over all layers in a HIP graph,
     # timed with HIP events on the launch stream; the byte count comes from the device counters of those calls.
     # With one layer the rows stay warm in the 256 MB Infinity Cache; with 32 layers each call reads its rows from HBM.
@@ -462,6 +496,7 @@ def main():
                                 "rows_added": added_per_call, "h2d_bytes": added_per_call * w.bundle_bytes,
                                 "nominal_bundle_bytes": nominal},
         "window_len_at_end": window_len_end,
+        "steady_state": steady,
         "speculative": ({"tokens_per_pass": w.batch, "kept_per_pass": w.spec_keep, "passes": T,
                          "us_per_accepted_token": us_per_token_layer / w.spec_keep} if spec else None),
         "end_to_end_us_per_token": us_per_token_layer * NL,
@@ -486,7 +521,8 @@ def main():
             out["roofline"]["traffic"] = tr["FETCH_SIZE"]["bytes_per_call"] + tr["WRITE_SIZE"]["bytes_per_call"]
             out["roofline"]["traffic_detail"] = tr
     if kern:
-        out["h2d"] = {"GBs_in_load_kernel": added_per_call * w.bundle_bytes / (kern["load"]["avg_us"] * 1e-6) / 1e9}
+        out["h2d"] = {"GBs_in_load_kernel": added_per_call * w.bundle_bytes / (kern["load"]["avg_us"] * 1e-6) / 1e9,
+                      "GBs_large_pinned_memcpy_same_box": h2d_ref}
         out["kernels_avg_us_event_timed"] = {k: round(v["avg_us"], 3) for k, v in kern.items()}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, base, X)
