@@ -269,7 +269,8 @@ void launch_load_up(lif_layer* L, const void* x, const int32_t* added, hipStream
     const int spec = L->expected_rows > 0 ? 1 : 0;
     const int up_blocks = spec ? std::min(kUpMaxWgs, std::max(1, std::min(L->expected_rows, c.capacity_rows) / 4))
                                : std::min((c.capacity_rows + 3) / 4, 512);
-    const int load_wgs = (int)std::min<size_t>(64, std::max<size_t>(10, kStepInflightBytes / L->row_bytes));
+    // loader waves come in pairs (activation vectors | down vector of one bundle), one wave per workgroup
+    const int load_wgs = 2 * (int)std::min<size_t>(32, std::max<size_t>(5, kStepInflightBytes / L->row_bytes));
 #define LIF_LU(NI)                                                                                            \
     hipLaunchKernelGGL((k_load_up<T, NI, GLU>), dim3(load_wgs + up_blocks), dim3(256), 0, s,                      \
                        (T*)L->buf.matrix, L->buf.pointers, L->buf.bias, (const T*)L->host_alias, L->buf.b, added, \

@@ -23,19 +23,21 @@ namespace lif {
 #endif
 // The host link runs best with a few hundred KiB of reads outstanding: measured 51 GB/s with 128 KiB in
 // flight (32 waves x 4 KiB bundles), 46 GB/s with 512 KiB (32 x 16 KiB), 44 GB/s with 1 MiB (32 x 32 KiB).
-// The number of loader waves (one bundle in flight each, one per workgroup so that they spread over
-// compute units) is therefore chosen from the bundle size: kStepInflightBytes / bundle bytes, within 10..64
-// (8 waves were measured 15 % slower than 16 at 16 KiB bundles).
+// The number of loader wave pairs (one bundle in flight per pair, one wave per workgroup so that they spread
+// over compute units) is therefore chosen from the bundle size: kStepInflightBytes / bundle bytes, within 5..32.
 constexpr int kStepInflightBytes = LIF_STEP_INFLIGHT_BYTES;
 constexpr int kStepLoadWaves = 1;                     // waves of a loader workgroup that load (the others exit at once)
 
-// Loader role, one wave per work item.  Work item q covers tail slot s = n' + q (see k_load):
-// the wave requests the whole host bundle of added[q] first (the long latency), moves the live
-// tail row to its hole meanwhile, then writes the bundle to slot s.  Lane l holds the same
-// 16-byte pieces of every vector as in the activation role (piece it * 64 + l), keeps x in
-// registers the same way and sums in the same order, so the activations it writes are bit
-// for bit those the activation kernel would compute.  32 waves x one bundle in flight keeps
-// the host link at its best operating point (a few hundred KiB outstanding).
+// Loader role.  Work item q covers tail slot s = n' + q (see k_load) and is shared by a PAIR of waves:
+// wave 2p takes the vectors the activation needs (gate | up), wave 2p + 1 the down vector, so a bundle
+// crosses the host link as two requests streams of d * E bytes (measured: 8 KiB pieces with 32 waves move
+// 4 % more than 16 KiB pieces with 16 waves at the same bytes in flight, and the tail - the last items,
+// when most waves have run out of work - is half as long).  Each wave requests its part of the host bundle of
+// added[q] first (the long latency), moves its part of the live tail row to its hole meanwhile, then writes
+// the bundle part to slot s.  In the activation wave, lane l holds the same 16-byte pieces of every vector as
+// in the activation role (piece it * 64 + l), keeps x in registers the same way and sums in the same order, so
+// the activations it writes are bit for bit those the activation kernel would compute; it also does the
+// bookkeeping of the slot (pointers, bias).  nwaves must be even.
 template <typename T, int NI, bool GLU>
 __device__ __forceinline__ void load_role(T* __restrict__ matrix, int32_t* __restrict__ pointers,
                                           float* __restrict__ bias, const T* __restrict__ host,
@@ -46,31 +48,36 @@ __device__ __forceinline__ void load_role(T* __restrict__ matrix, int32_t* __res
                                           int nwaves, DevState* st) {
     using V = typename Vec<T>::type;
     constexpr int VE = Vec<T>::N;
-    constexpr int G = GLU ? 3 : 2;
+    constexpr int GA = GLU ? 2 : 1;                      // vectors of the activation part (gate | up, or up)
     const int lane = threadIdx.x & 63;
     const int nvec = d / VE;
+    const int part = wave_id & 1;                        // 0: activation vectors and bookkeeping, 1: down vector
+    const int pair_id = wave_id >> 1, pairs = nwaves >> 1;
+    const int g0 = part ? GA : 0;                        // first vector of this wave's part
+    const int gn = part ? 1 : GA;                        // number of vectors in it
+    const bool act_wave = part == 0;
     const V* xv = reinterpret_cast<const V*>(x);
     V xr[NI];
 #pragma unroll
     for (int it = 0; it < NI; ++it) {
         const int idx = it * 64 + lane;
-        xr[it] = (idx < nvec) ? xv[idx] : V(0);
+        xr[it] = (act_wave && idx < nvec) ? xv[idx] : V(0);
     }
     // The bookkeeping of the first 64 work items of this wave (one per lane) is requested together
     // with the state, before the counts are known (the arrays span the whole capacity; entries past
     // the counts are masked afterwards): one device-memory round trip in front of the host reads.
     int dst_l = -1, nid_l = -1;
     {
-        const int ql = wave_id + lane * nwaves;
+        const int ql = pair_id + lane * pairs;
         if (ql < capacity) dst_l = move_dst[ql];
         if (ql < F) nid_l = added[ql];
     }
     if (st->error) return;
     const int n2 = st->n_base, c = st->n_removed, a = st->n_added, step = st->step;
     const int items = max(c, a);
-    for (int q0 = wave_id; q0 < items; q0 += nwaves * kWave) {
-      const int ql = q0 + lane * nwaves;                 // work item of this lane
-      if (q0 != wave_id) {                               // later batches (more than 64 items per wave)
+    for (int q0 = pair_id; q0 < items; q0 += pairs * kWave) {
+      const int ql = q0 + lane * pairs;                  // work item of this lane
+      if (q0 != pair_id) {                               // later batches (more than 64 items per wave)
           dst_l = (ql < c) ? move_dst[ql] : -1;
           nid_l = (ql < a) ? added[ql] : -1;
       }
@@ -79,7 +86,7 @@ __device__ __forceinline__ void load_role(T* __restrict__ matrix, int32_t* __res
       int optr_l = -1;
       float obias_l = 0.f, nbias_l = 0.f;
       float ogate_l = 0.f, ngate_l = 0.f;                // resident-gate activations of the moved / new neuron
-      if (ql < items) {
+      if (act_wave && ql < items) {
           optr_l = pointers[n2 + ql];
           obias_l = bias[n2 + ql];
           if (nid_l >= 0) nbias_l = b[nid_l];
@@ -88,35 +95,35 @@ __device__ __forceinline__ void load_role(T* __restrict__ matrix, int32_t* __res
               if (optr_l >= 0 && optr_l < F) ogate_l = gact[optr_l];
           }
       }
-      const int nitems = min(kWave, (items - q0 + nwaves - 1) / nwaves);
+      const int nitems = min(kWave, (items - q0 + pairs - 1) / pairs);
       // Software pipeline over the items of this wave: the reads of item j+1 are requested as soon
       // as the registers of item j are free (after its stores and per-lane dot products) and fly
       // while item j's wave reductions and bookkeeping writes complete.  Device rows (the move) are
       // requested before host rows so that waiting for them does not wait for the host link.
       int dst = __shfl(dst_l, 0, kWave), nid = __shfl(nid_l, 0, kWave);
-      V hv[G][NI], mv[G][NI];
+      V hv[GA][NI], mv[GA][NI];
       {
-          const V* hrow = reinterpret_cast<const V*>(host + (size_t)max(nid, 0) * row_elems);
-          const V* srow = reinterpret_cast<const V*>(matrix + (size_t)(n2 + q0) * row_elems);
+          const V* hrow = reinterpret_cast<const V*>(host + (size_t)max(nid, 0) * row_elems) + (size_t)g0 * nvec;
+          const V* srow = reinterpret_cast<const V*>(matrix + (size_t)(n2 + q0) * row_elems) + (size_t)g0 * nvec;
 #pragma unroll
-          for (int g = 0; g < G; ++g)
+          for (int g = 0; g < GA; ++g)
 #pragma unroll
               for (int it = 0; it < NI; ++it) {
                   const int idx = it * 64 + lane;
-                  mv[g][it] = (dst >= 0 && idx < nvec) ? srow[g * nvec + idx] : V(0);
+                  mv[g][it] = (dst >= 0 && g < gn && idx < nvec) ? srow[g * nvec + idx] : V(0);
               }
 #pragma unroll
-          for (int g = 0; g < G; ++g)
+          for (int g = 0; g < GA; ++g)
 #pragma unroll
               for (int it = 0; it < NI; ++it) {
                   const int idx = it * 64 + lane;
-                  hv[g][it] = (nid >= 0 && idx < nvec) ? hrow[g * nvec + idx] : V(0);
+                  hv[g][it] = (nid >= 0 && g < gn && idx < nvec) ? hrow[g * nvec + idx] : V(0);
               }
       }
       for (int j = 0; j < nitems; ++j) {
-        const int s = n2 + q0 + j * nwaves;
-        V* srow = reinterpret_cast<V*>(matrix + (size_t)s * row_elems);
-        V* drow = reinterpret_cast<V*>(matrix + (size_t)max(dst, 0) * row_elems);
+        const int s = n2 + q0 + j * pairs;
+        V* srow = reinterpret_cast<V*>(matrix + (size_t)s * row_elems) + (size_t)g0 * nvec;
+        V* drow = reinterpret_cast<V*>(matrix + (size_t)max(dst, 0) * row_elems) + (size_t)g0 * nvec;
         const int32_t old_ptr = __shfl(optr_l, j, kWave);
         const float old_bias = __shfl(obias_l, j, kWave);
         const float new_bias = __shfl(nbias_l, j, kWave);
@@ -124,55 +131,59 @@ __device__ __forceinline__ void load_role(T* __restrict__ matrix, int32_t* __res
         float mdu = 0.f, mdg = 0.f, hdu = 0.f, hdg = 0.f;
         if (dst >= 0) {                                   // wave-uniform
 #pragma unroll
-            for (int g = 0; g < G; ++g)
+            for (int g = 0; g < GA; ++g)
 #pragma unroll
                 for (int it = 0; it < NI; ++it) {
                     const int idx = it * 64 + lane;
-                    if (idx < nvec) drow[g * nvec + idx] = mv[g][it];
+                    if (g < gn && idx < nvec) drow[g * nvec + idx] = mv[g][it];
                 }
+            if (act_wave) {
 #pragma unroll
-            for (int it = 0; it < NI; ++it) {
-                mdu = dot_acc(mv[GLU ? 1 : 0][it], xr[it], mdu);
-                if (GLU) mdg = dot_acc(mv[0][it], xr[it], mdg);
+                for (int it = 0; it < NI; ++it) {
+                    mdu = dot_acc(mv[GLU ? 1 : 0][it], xr[it], mdu);
+                    if (GLU) mdg = dot_acc(mv[0][it], xr[it], mdg);
+                }
             }
         }
         if (nid >= 0) {                                   // wave-uniform
 #pragma unroll
-            for (int g = 0; g < G; ++g)
+            for (int g = 0; g < GA; ++g)
 #pragma unroll
                 for (int it = 0; it < NI; ++it) {
                     const int idx = it * 64 + lane;
-                    if (idx < nvec) srow[g * nvec + idx] = hv[g][it];
+                    if (g < gn && idx < nvec) srow[g * nvec + idx] = hv[g][it];
                 }
+            if (act_wave) {
 #pragma unroll
-            for (int it = 0; it < NI; ++it) {
-                hdu = dot_acc(hv[GLU ? 1 : 0][it], xr[it], hdu);
-                if (GLU) hdg = dot_acc(hv[0][it], xr[it], hdg);
+                for (int it = 0; it < NI; ++it) {
+                    hdu = dot_acc(hv[GLU ? 1 : 0][it], xr[it], hdu);
+                    if (GLU) hdg = dot_acc(hv[0][it], xr[it], hdg);
+                }
             }
         }
         // request item j + 1
         const int dst_n = (j + 1 < nitems) ? __shfl(dst_l, j + 1, kWave) : -1;
         const int nid_n = (j + 1 < nitems) ? __shfl(nid_l, j + 1, kWave) : -1;
         if (j + 1 < nitems) {
-            const V* hrow = reinterpret_cast<const V*>(host + (size_t)max(nid_n, 0) * row_elems);
-            const V* nrow = reinterpret_cast<const V*>(matrix + (size_t)(s + nwaves) * row_elems);
+            const V* hrow = reinterpret_cast<const V*>(host + (size_t)max(nid_n, 0) * row_elems) + (size_t)g0 * nvec;
+            const V* nrow = reinterpret_cast<const V*>(matrix + (size_t)(s + pairs) * row_elems) + (size_t)g0 * nvec;
 #pragma unroll
-            for (int g = 0; g < G; ++g)
+            for (int g = 0; g < GA; ++g)
 #pragma unroll
                 for (int it = 0; it < NI; ++it) {
                     const int idx = it * 64 + lane;
-                    mv[g][it] = (dst_n >= 0 && idx < nvec) ? nrow[g * nvec + idx] : V(0);
+                    mv[g][it] = (dst_n >= 0 && g < gn && idx < nvec) ? nrow[g * nvec + idx] : V(0);
                 }
 #pragma unroll
-            for (int g = 0; g < G; ++g)
+            for (int g = 0; g < GA; ++g)
 #pragma unroll
                 for (int it = 0; it < NI; ++it) {
                     const int idx = it * 64 + lane;
-                    hv[g][it] = (nid_n >= 0 && idx < nvec) ? hrow[g * nvec + idx] : V(0);
+                    hv[g][it] = (nid_n >= 0 && g < gn && idx < nvec) ? hrow[g * nvec + idx] : V(0);
                 }
         }
         // finish item j: same order of operations as the activation kernel
-        if (dst >= 0) {
+        if (act_wave && dst >= 0) {
             const float du = wave_sum(mdu);
             float act;
             if (GLU) {
@@ -190,7 +201,7 @@ __device__ __forceinline__ void load_role(T* __restrict__ matrix, int32_t* __res
                 stamp[dst] = step;
             }
         }
-        if (nid >= 0) {
+        if (act_wave && nid >= 0) {
             const float du = wave_sum(hdu);
             float act;
             if (GLU) {
