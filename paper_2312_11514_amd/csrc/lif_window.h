@@ -159,30 +159,40 @@ __global__ __launch_bounds__(kScanThreads) void k_window_plan(
         // union fits the capacity.  U_a = union of the newest a masks (a = 1: this step's mask).
         for (int a = tid; a < k; a += kScanThreads) cnt_age[a] = 0;
         __syncthreads();
-        int age_of[kRingRegs];                           // age of ring entry j: (slot - j) mod k, 0 for j == slot
+        unsigned long long ua[kRingRegs];                // ua[a - 1] = U_a, a = 1 .. min(k, kRingRegs)
+        if (k <= kRingRegs && tid >= ((nwords + kWave - 1) & ~(kWave - 1))) {
+            // this wave holds no mask word: nothing to count (all 16 waves share one compute unit, so the
+            // idle ones would only slow the few that hold the masks)
 #pragma unroll
-        for (int j = 0; j < kRingRegs; ++j) age_of[j] = slot - j + (slot < j ? k : 0);
-        if (k <= kRingRegs) {
-            // all ring words are in registers: age of ring entry j is (slot - j) mod k (uniform), the entry
-            // at `slot` itself is the one being overwritten.  Per-wave sums (two 16-bit counts per
-            // shuffled word), then one LDS atomic per wave and age.
+            for (int a = 0; a < kRingRegs; ++a) ua[a] = 0ull;
+        } else if (k <= kRingRegs) {
+            // The ring entries are read again in order of age (entry slot - a holds the mask pushed a steps ago;
+            // the words are in L2 from the loads above): a run-time index into the register copy would cost far
+            // more instructions.  Per-wave sums (two 16-bit counts per shuffled word), then one LDS atomic
+            // per wave and age.
+            unsigned long long e[kRingRegs];
+#pragma unroll
+            for (int a = 1; a < kRingRegs; ++a) {
+                const int idx = slot - a + (slot < a ? k : 0);
+                e[a] = (have && a < k) ? ring[(size_t)idx * ring_words + tid] : 0ull;
+            }
+            unsigned long long u = m;
+            ua[0] = u;
+#pragma unroll
+            for (int a = 1; a < kRingRegs; ++a) {
+                u |= e[a];
+                ua[a] = u;
+            }
             unsigned pk[kRingRegs / 2];
 #pragma unroll
-            for (int i = 0; i < kRingRegs / 2; ++i) pk[i] = 0u;
-#pragma unroll
-            for (int a = 1; a <= kRingRegs; ++a) {
-                unsigned long long u = m;
-#pragma unroll
-                for (int j = 0; j < kRingRegs; ++j)
-                    if (j < k && j != slot && age_of[j] < a) u |= rv[j];
-                if (a <= k) pk[(a - 1) >> 1] |= (unsigned)__popcll(u) << (((a - 1) & 1) * 16);
-            }
+            for (int i = 0; i < kRingRegs / 2; ++i)
+                pk[i] = (unsigned)__popcll(ua[2 * i]) | ((unsigned)__popcll(ua[2 * i + 1]) << 16);
 #pragma unroll
             for (int i = 0; i < kRingRegs / 2; ++i) {
                 unsigned v = pk[i];
 #pragma unroll
                 for (int msk = 32; msk >= 1; msk >>= 1) v += __shfl_xor(v, msk, kWave);   // 64 lanes x 64 bits < 2^16
-                if (lane == 0) {
+                if (lane == 0 && v) {
                     if (2 * i < k) atomicAdd(&cnt_age[2 * i], (int)(v & 0xffffu));
                     if (2 * i + 1 < k) atomicAdd(&cnt_age[2 * i + 1], (int)(v >> 16));
                 }
@@ -212,8 +222,8 @@ __global__ __launch_bounds__(kScanThreads) void k_window_plan(
         now = m;
         if (k <= kRingRegs) {
 #pragma unroll
-            for (int j = 0; j < kRingRegs; ++j)
-                if (j < k && j != slot && age_of[j] < k_eff) now |= rv[j];
+            for (int a = 1; a < kRingRegs; ++a)
+                if (a < k_eff) now = ua[a];                  // U_a grows with a: the last one taken is U_{k_eff}
         } else if (have) {
             for (int a = 2; a <= k_eff; ++a) now |= ring[(size_t)((slot - (a - 1) + k) % k) * ring_words + tid];
         }
