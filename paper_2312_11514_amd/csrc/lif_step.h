@@ -37,7 +37,8 @@ constexpr int kStepLoadWaves = 1;                     // waves of a loader workg
 // the bundle part to slot s.  In the activation wave, lane l holds the same 16-byte pieces of every vector as
 // in the activation role (piece it * 64 + l), keeps x in registers the same way and sums in the same order, so
 // the activations it writes are bit for bit those the activation kernel would compute; it also does the
-// bookkeeping of the slot (pointers, bias).  nwaves must be even.
+// bookkeeping of the slot (pointers, bias).  nwaves must be even.  Rows of at most 2 KiB per vector (NI <= 2)
+// are not split: one wave takes the whole bundle.
 template <typename T, int NI, bool GLU>
 __device__ __forceinline__ void load_role(T* __restrict__ matrix, int32_t* __restrict__ pointers,
                                           float* __restrict__ bias, const T* __restrict__ host,
@@ -48,11 +49,13 @@ __device__ __forceinline__ void load_role(T* __restrict__ matrix, int32_t* __res
                                           int nwaves, DevState* st) {
     using V = typename Vec<T>::type;
     constexpr int VE = Vec<T>::N;
-    constexpr int GA = GLU ? 2 : 1;                      // vectors of the activation part (gate | up, or up)
+    constexpr bool PAIRED = NI > 2;                      // vectors of up to 2 KiB: one wave per bundle (halves of
+                                                         // small bundles cross the host link badly)
+    constexpr int GA = PAIRED ? (GLU ? 2 : 1) : (GLU ? 3 : 2);   // vectors a wave handles at most
     const int lane = threadIdx.x & 63;
     const int nvec = d / VE;
-    const int part = wave_id & 1;                        // 0: activation vectors and bookkeeping, 1: down vector
-    const int pair_id = wave_id >> 1, pairs = nwaves >> 1;
+    const int part = PAIRED ? (wave_id & 1) : 0;         // 0: activation vectors and bookkeeping, 1: down vector
+    const int pair_id = PAIRED ? (wave_id >> 1) : wave_id, pairs = PAIRED ? (nwaves >> 1) : nwaves;
     const int g0 = part ? GA : 0;                        // first vector of this wave's part
     const int gn = part ? 1 : GA;                        // number of vectors in it
     const bool act_wave = part == 0;
