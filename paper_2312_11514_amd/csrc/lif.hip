@@ -167,7 +167,7 @@ int launch_predict(lif_layer* L, const void* x, int batch, uint8_t* masks, uint8
     hipLaunchKernelGGL((k_predict_mask<T, BT>), dim3(grid), dim3(256), sizeof(double) * BT * c.rank, s,          \
                        (const T*)L->buf.B, L->buf.c, L->tpart, c.rank, c.d_ffn, batch, c.threshold, masks,         \
                        step_mask, L->st)
-    // tokens per pass over B: all of them when the partial sums fit LDS (BT * rank doubles <= 48 KiB)
+    // tokens per pass over B: all of them when t of those tokens fits LDS (BT * rank doubles <= 48 KiB)
     if (batch == 1 || c.rank > 1536) LIF_MASK(1);
     else if (batch <= 4 || c.rank > 768) LIF_MASK(4);
     else LIF_MASK(8);
@@ -183,12 +183,8 @@ void launch_predict_gate(lif_layer* L, const void* x, uint8_t* masks, uint8_t* s
     const int grid = std::min((c.d_ffn / 8 + 3) / 4, 2048);
     Timed t(L, LIF_K_PREDICT_MASK, s);
 #define LIF_PG(NI)                                                                                           \
-    do {                                                                                                     \
-        hipLaunchKernelGGL((k_predict_gate<T, NI>), dim3(grid), dim3(256), 0, s, (const T*)L->buf.A, L->buf.b,   \
-                           (const T*)x, c.d_model, c.d_ffn, c.threshold, masks, L->gact, L->st);                 \
-        if (step_mask != masks)                                                                              \
-            hipMemcpyAsync(step_mask, masks, c.d_ffn / 8, hipMemcpyDeviceToDevice, s);                        \
-    } while (0)
+    hipLaunchKernelGGL((k_predict_gate<T, NI>), dim3(grid), dim3(256), 0, s, (const T*)L->buf.A, L->buf.b,       \
+                       (const T*)x, c.d_model, c.d_ffn, c.threshold, masks, step_mask, L->gact, L->st)
     if (ni <= 1) LIF_PG(1);
     else if (ni <= 2) LIF_PG(2);
     else if (ni <= 4) LIF_PG(4);

@@ -7,11 +7,11 @@
 //   ffn_up    one wave per cached row: all 16-byte loads of the row's up (and gate) vector are
 //             issued before the first use; the wave reduces the dot product and writes the
 //             activation h[s].
-//   ffn_down  one workgroup per slice of output columns: it owns those columns of y, so no
-//             cross-workgroup reduction or atomics are needed and the summation order is
-//             fixed.  It compacts the rows with a non-zero activation (prefix sum in LDS) and
-//             streams only their down columns.  (A variant without compaction - predicated
-//             loads over all rows - measured 1.6 us slower at the OPT-6.7B shape.)
+//   ffn_down  workgroups per slice of output columns (and per chunk of rows once the cache is large): no
+//             atomics, fixed summation order.  It compacts the rows with a non-zero activation
+//             (prefix sum in LDS) and streams only their down columns.  (A variant without
+//             compaction - predicated loads over all rows - measured 1.6 us slower at the
+//             OPT-6.7B shape.)
 #pragma once
 
 #include "lif_common.h"

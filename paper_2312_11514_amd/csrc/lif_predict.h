@@ -7,7 +7,7 @@
 // stays bandwidth bound (one fp64 FMA per 2 or 4 bytes read).
 //
 // Both kernels are a few microseconds long, i.e. latency bound: each issues all of its
-// global loads (weights, partial sums, offsets, state) before the first dependent use.
+// global loads (weights, offsets, state) before the first dependent use.
 #pragma once
 
 #include <type_traits>
@@ -210,8 +210,8 @@ __global__ __launch_bounds__(256) void k_predict_mask(const T* __restrict__ B, c
 template <typename T, int NI>
 __global__ __launch_bounds__(256) void k_predict_gate(const T* __restrict__ Wg, const float* __restrict__ b,
                                                       const T* __restrict__ x, int d, int F, float theta,
-                                                      uint8_t* __restrict__ mask, float* __restrict__ gact,
-                                                      const DevState* __restrict__ st) {
+                                                      uint8_t* __restrict__ mask, uint8_t* __restrict__ step_mask,
+                                                      float* __restrict__ gact, const DevState* __restrict__ st) {
     using V = typename Vec<T>::type;
     constexpr int VE = Vec<T>::N;
     const int tid = threadIdx.x, lane = tid & 63;
@@ -250,7 +250,10 @@ __global__ __launch_bounds__(256) void k_predict_gate(const T* __restrict__ Wg, 
             if (a > th) byte |= 1u << e;
             if (lane == e) keep_act = (float)(a > 0.0 ? a : 0.0);
         }
-        if (lane == 0) mask[grp] = (uint8_t)byte;
+        if (lane == 0) {
+            mask[grp] = (uint8_t)byte;
+            if (step_mask != mask) step_mask[grp] = (uint8_t)byte;   // one token: the step mask is the mask
+        }
         if (lane < 8) gact[grp * 8 + lane] = keep_act;
     }
 }

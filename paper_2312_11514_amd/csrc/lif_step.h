@@ -1,4 +1,4 @@
-// Fused cache update + activation stage for single-token steps (lif_step).
+// Fused cache update + activation stage (lif_step, lif_step_tokens).
 //
 // The host-to-device gather of new bundles is bound by the host link and keeps only ~32
 // workgroups busy for tens of microseconds (Section 3.3 item 2), while the activation stage of
@@ -21,8 +21,9 @@ namespace lif {
 #ifndef LIF_STEP_INFLIGHT_BYTES
 #define LIF_STEP_INFLIGHT_BYTES (256 * 1024)
 #endif
-// The host link runs best with a few hundred KiB of reads outstanding: measured 51 GB/s with 128 KiB in
-// flight (32 waves x 4 KiB bundles), 46 GB/s with 512 KiB (32 x 16 KiB), 44 GB/s with 1 MiB (32 x 32 KiB).
+// The host link runs best with a few hundred KiB of reads outstanding: a read-only gather of 146 bundles of
+// 16 KiB measured 52 GB/s with 256 KiB in flight in pieces of 1 to 8 KiB per wave, 50 GB/s with 384 KiB,
+// 42 GB/s with 16 KiB pieces.
 // The number of loader wave pairs (one bundle in flight per pair, one wave per workgroup so that they spread
 // over compute units) is therefore chosen from the bundle size: kStepInflightBytes / bundle bytes, within 5..32.
 constexpr int kStepInflightBytes = LIF_STEP_INFLIGHT_BYTES;
@@ -30,7 +31,7 @@ constexpr int kStepLoadWaves = 1;                     // waves of a loader workg
 
 // Loader role.  Work item q covers tail slot s = n' + q (see k_load) and is shared by a PAIR of waves:
 // wave 2p takes the vectors the activation needs (gate | up), wave 2p + 1 the down vector, so a bundle
-// crosses the host link as two requests streams of d * E bytes (measured: 8 KiB pieces with 32 waves move
+// crosses the host link as two request streams of d * E bytes (measured: 8 KiB pieces with 32 waves move
 // 4 % more than 16 KiB pieces with 16 waves at the same bytes in flight, and the tail - the last items,
 // when most waves have run out of work - is half as long).  Each wave requests its part of the host bundle of
 // added[q] first (the long latency), moves its part of the live tail row to its hole meanwhile, then writes
