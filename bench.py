@@ -54,6 +54,26 @@ def cpu_baseline(w, L, X, budget_s=20.0):
     out = {"value": dt / done * 1e6, "unit": "us/token/layer", "cores": int(cores), "kind": "oracle",
            "sample": f"first {done} steps of the same stream on layer 0, whole path "
                      f"(predict, window, delete, insert, FFN)"}
+    # the same oracle on one core, on a shorter sample
+    try:
+        from threadpoolctl import threadpool_limits
+        ora1 = O.OracleLayer(w.d_model, w.d_ffn, w.window_k, w.capacity_rows, w.glu and not gate, L.A, L.B, L.c,
+                             L.theta, L.b, L.bundles, shrink=w.shrink, w_gate=L.w_gate if gate else None)
+        with threadpool_limits(limits=1):
+            t0 = time.perf_counter()
+            done1 = 0
+            for t in range(len(X)):
+                if w.spec_keep > 0:
+                    ora1.step_tokens(X[t], w.spec_keep)
+                else:
+                    ora1.step(X[t])
+                done1 += 1
+                if time.perf_counter() - t0 > budget_s / 4:
+                    break
+            out["one_core"] = {"value": (time.perf_counter() - t0) / done1 * 1e6, "unit": "us/token/layer",
+                               "sample": f"first {done1} steps"}
+    except ImportError:
+        pass
     # untimed: how good the synthetic predictor is on a few tokens (the oracle's mask against the sign of the
     # true pre-activation) - describes the workload, not the kernels
     import numpy as np
