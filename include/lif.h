@@ -194,7 +194,7 @@ int lif_update_window(lif_layer* layer, const uint8_t* step_mask_dev,
 
 /*
  * Step 2 for a verification pass of speculative decoding (Section 4.3 "Speculative Decoding";
- * Appendix, related work: "the window ... is updated with multiple tokens rather than one").
+ * Appendix, related work on speculative decoding: the window then moves by several tokens at once).
  *   masks_dev  [n_tokens x d_ffn/8] bytes, device, 8-byte aligned: the per-token masks of the
  *              pass (as written by lif_predict with batch = n_tokens); d_ffn % 64 == 0
  *   keep       0..n_tokens: the first `keep` tokens (those expected to be accepted; the paper's

@@ -27,8 +27,8 @@ Readings of the paper taken here (the paper is silent or ambiguous):
   * a neuron is active iff its logit is strictly greater than the threshold;
   * the predictor may carry a per-neuron offset c (null = 0);
   * deletion pairs the lowest dead slot with the highest live slot, repeatedly
-    ("replaced with the most recent elements"); insertion appends in ascending
-    neuron id;
+    (Section 3.3: a deleted row is overwritten by a row taken from the end);
+    insertion appends in ascending neuron id;
   * the FFN sums over every cached row (the window union), not only over the
     current token's mask;
   * a batch of tokens shares one cache: its step mask is the OR of the
