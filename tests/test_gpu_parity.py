@@ -559,3 +559,90 @@ def test_gate_predictor_rejects_batches_and_gated_bundles():
     x2 = gpu.upload_x(np.stack([wl.make_inputs(w)[0]] * 2))
     with pytest.raises(Exception):
         gpu.layer.predict(x2, 2)
+
+
+# ----------------------------------------------------------------------------- seeded random configurations
+def _random_config(i):
+    rng = np.random.default_rng(9000 + i)
+    dtype = ["f16", "f32"][int(rng.integers(2))]
+    ve = 8 if dtype == "f16" else 4
+    d = int(rng.integers(2, 90)) * ve                      # ragged vector counts, below and above one wave of 16-byte loads
+    F = int(rng.integers(8, 400)) * 8
+    batch = int([1, 1, 1, 2, 3, 8][int(rng.integers(6))])
+    glu = bool(rng.integers(2))
+    k = int(rng.integers(1, 10))
+    p = float(rng.uniform(0.02, 0.2))
+    shrink = bool(rng.integers(2)) and batch == 1
+    cap = F if not shrink else max(int(F * p * 2.5), 16)
+    r = int(rng.integers(1, 6)) * ve
+    return wl.scaled(wl.WORKLOADS["C1"], name=f"rand{i}", d_model=d, d_ffn=F, rank=min(r, d), window_k=k, p_active=p,
+                     rho=float(rng.uniform(0.0, 0.95)), dtype=dtype, glu=glu, tokens=14, batch=batch,
+                     capacity_rows=cap, shrink=shrink)
+
+
+@pytest.mark.parametrize("i", range(60))
+def test_seeded_random_configurations(i):
+    """Shapes, window sizes, activity levels, batch sizes, dtypes and the dynamic window drawn from a seeded
+    generator: every step of both APIs against the oracle (a single mask above the capacity ends the stream
+    with the same error on both sides)."""
+    from tests.harness import GpuLayer, compare_step
+    w = _random_config(i)
+    L = wl.make_layer(w)
+    X = wl.make_inputs(w) if w.batch == 1 else wl.make_batch_inputs(w)
+    for api in ("calls", "step"):
+        gpu = GpuLayer(w, L, ffn_mode=i % 2)
+        ora = O.OracleLayer(w.d_model, w.d_ffn, w.window_k, w.capacity_rows, w.glu, L.A, L.B, L.c, L.theta, L.b,
+                            L.bundles, shrink=w.shrink)
+        for t in range(len(X)):
+            try:
+                compare_step(gpu, ora, X[t], w, t, api=api)
+            except OverflowError:
+                # the oracle refused the step (its mask alone is above the capacity): the device reports the same
+                xd = gpu.upload_x(X[t])
+                (gpu.layer.step if api == "step" else gpu.layer.step_calls)(xd, gpu.y, w.batch)
+                assert gpu.layer.state()["error"] == 3
+                break
+        assert ora.min_margin > 1e-10
+
+
+@pytest.mark.parametrize("i", range(16))
+def test_seeded_random_speculative_passes(i):
+    """Token-granular window updates on seeded random shapes, pass lengths and keep counts (both APIs)."""
+    from tests.harness import GpuLayer, rel_l2, REL_L2_TOL
+    rng = np.random.default_rng(7000 + i)
+    dtype = ["f16", "f32"][int(rng.integers(2))]
+    ve = 8 if dtype == "f16" else 4
+    ntok = int(rng.integers(2, 9))
+    w = wl.scaled(wl.WORKLOADS["C1"], name=f"spec{i}", d_model=int(rng.integers(2, 80)) * ve,
+                  d_ffn=int(rng.integers(2, 40)) * 64, rank=2 * ve, window_k=int(rng.integers(1, 8)),
+                  p_active=float(rng.uniform(0.02, 0.12)), dtype=dtype, glu=bool(rng.integers(2)),
+                  tokens=ntok * 10, batch=ntok)
+    w = wl.scaled(w, capacity_rows=w.d_ffn)
+    L = wl.make_layer(w)
+    X = wl.make_inputs(w)
+    keeps = [int(rng.integers(0, ntok + 1)) for _ in range(10)]
+    for api in ("calls", "step"):
+        gpu = GpuLayer(w, L, max_batch=ntok)
+        lay = gpu.layer
+        ora = make_oracle(w, L)
+        for p, keep in enumerate(keeps):
+            xb = X[ntok * p:ntok * (p + 1)]
+            ref = ora.step_tokens(xb, keep)
+            xd = gpu.upload_x(xb)
+            if api == "step":
+                lay.step_tokens(xd, gpu.y, ntok, keep)
+            else:
+                lay.predict(xd, ntok)
+                lay.update_window_tokens(ntok, keep)
+                lay.load_bundles()
+                lay.sparse_ffn(xd, gpu.y, ntok)
+            na, nr = int(lay.n_added.item()), int(lay.n_removed.item())
+            assert lay.added[:na].cpu().numpy().tolist() == ref["added"].tolist(), f"pass {p}"
+            assert lay.removed[:nr].cpu().numpy().tolist() == ref["removed"].tolist(), f"pass {p}"
+            n = ref["num_used"]
+            st = lay.state()
+            assert st["error"] == 0 and st["num_used"] == n and st["window_len"] == len(ora.window.masks)
+            assert (lay.pointers[:n].cpu().numpy() == ora.cache.pointers[:n]).all()
+            assert lay.matrix[:n].cpu().numpy().tobytes() == ora.cache.matrix[:n].tobytes()
+            assert rel_l2(gpu.y[:ntok].cpu().numpy(), ref["y"]) <= REL_L2_TOL
+        assert ora.min_margin > 1e-10
