@@ -33,9 +33,12 @@ Readings of the paper taken here (the paper is silent or ambiguous):
     current token's mask;
   * a batch of tokens shares one cache: its step mask is the OR of the
     per-token masks and the window counts steps;
-  * dynamic window (optional): "reduces window size dynamically whenever the
-    memory usage passes the limit" is read as dropping the oldest masks, for
-    good, until the union of the remaining ones fits the cache.
+  * dynamic window (optional; Appendix, Persimmon, window configuration: the
+    window gets smaller whenever the cache would outgrow its memory share) is
+    read as dropping the oldest masks, for good, until the union of the
+    remaining ones fits the cache;
+  * the threshold is the fp32 value the C ABI carries (theta rounded to fp32
+    once, then compared in fp64), for both predictors.
 Pins: tests/test_oracle_*.py.  Nothing here is "parity unpinned".
 """
 from __future__ import annotations
@@ -252,8 +255,9 @@ def gate_predict_mask(x, w_gate, b, theta):
     pre-activations a_i = gate_i . x + b_i are known before anything is loaded and a_i > theta names
     exactly the neurons that fire.  Returns (mask, margin, relu(a)) in fp64."""
     a = np.asarray(x, np.float64) @ np.asarray(w_gate, np.float64).T + np.asarray(b, np.float64)
-    margin = float(np.min(np.abs(a - theta))) if a.size else float("inf")
-    return a > theta, margin, np.maximum(a, 0.0)
+    th = np.float64(np.float32(theta))
+    margin = float(np.min(np.abs(a - th))) if np.isfinite(th) and a.size else float("inf")
+    return a > th, margin, np.maximum(a, 0.0)
 
 
 def sparse_ffn_resident_gate(cache: NeuronCache, gate_act, x, d_model: int):

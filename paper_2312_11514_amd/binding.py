@@ -9,7 +9,7 @@ import ctypes as C
 import os
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.environ.get("LIF_LIBRARY", os.path.join(HERE, "liblif.so"))   # override: an alternative build
+LIB_PATH = os.path.join(HERE, "liblif.so")
 
 LIF_OK, LIF_INVALID_ARG, LIF_BAD_STATE, LIF_CAPACITY, LIF_HIP_ERROR = 0, 1, 2, 3, 4
 LIF_F32, LIF_F16 = 0, 1

@@ -16,8 +16,7 @@ HIPCC_FLAGS = [
 
 def build_library(verbose: bool = False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    extra = os.environ.get("LIF_EXTRA_HIPCC_FLAGS", "").split()      # tuning experiments (-DLIF_...=N)
-    cmd = [hipcc, *HIPCC_FLAGS, *extra, "-o", LIB_PATH, *SOURCES]
+    cmd = [hipcc, *HIPCC_FLAGS, "-o", LIB_PATH, *SOURCES]
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + res.stdout + res.stderr)

@@ -18,10 +18,6 @@
 
 using namespace lif;
 
-#ifndef LIF_NO_MFMA
-#define LIF_NO_MFMA 0
-#endif
-
 namespace {
 
 thread_local char g_err[512] = "";
@@ -118,6 +114,7 @@ struct lif_layer {
     size_t row_elems, row_bytes;
     bool window_pending;
     int expected_rows;          // hint, 0 = none
+    int mask_bt[9];             // tokens per pass of the mask kernel for a batch of b tokens (1, 4 or 8)
     // event timing
     bool prof_on;
     int prof_max;
@@ -167,9 +164,10 @@ int launch_predict(lif_layer* L, const void* x, int batch, uint8_t* masks, uint8
     hipLaunchKernelGGL((k_predict_mask<T, BT>), dim3(grid), dim3(256), sizeof(double) * BT * c.rank, s,          \
                        (const T*)L->buf.B, L->buf.c, L->tpart, c.rank, c.d_ffn, batch, c.threshold, masks,         \
                        step_mask, L->st)
-    // tokens per pass over B: all of them when t of those tokens fits LDS (BT * rank doubles <= 48 KiB)
-    if (batch == 1 || c.rank > 1536) LIF_MASK(1);
-    else if (batch <= 4 || c.rank > 768) LIF_MASK(4);
+    // tokens per pass over B: chosen at lif_create so that t of those tokens and the kernel's own LDS fit a workgroup
+    const int bt = L->mask_bt[batch];
+    if (bt == 1) LIF_MASK(1);
+    else if (bt == 4) LIF_MASK(4);
     else LIF_MASK(8);
 #undef LIF_MASK
     return LIF_OK;
@@ -286,7 +284,7 @@ void launch_load_up(lif_layer* L, const void* x, const int32_t* added, hipStream
 constexpr int kFuseBatchedMinRows = 2048;
 
 bool mfma_path(const lif_config& c, int batch) {
-    return !LIF_NO_MFMA && c.dtype == LIF_F16 && batch > 1 && c.d_model % 32 == 0;
+    return c.dtype == LIF_F16 && batch > 1 && c.d_model % 32 == 0;
 }
 
 template <int MODE>
@@ -321,6 +319,33 @@ void launch_load_up_mfma(lif_layer* L, const void* x, int batch, const int32_t* 
                            c.d_ffn, (const _Float16*)x, L->h, c.d_model, batch, c.capacity_rows, kLoadGrid, L->st);
 }
 
+// LDS a workgroup of k_predict_mask<T, BT> needs for a predictor of rank r: its static arrays plus BT * r doubles.
+template <typename T, int BT>
+int mask_lds_bytes(int r, size_t* out) {
+    hipFuncAttributes fa;
+    LIF_HIP(hipFuncGetAttributes(&fa, reinterpret_cast<const void*>(&k_predict_mask<T, BT>)));
+    *out = fa.sharedSizeBytes + sizeof(double) * BT * (size_t)r;
+    return LIF_OK;
+}
+
+// For every batch size the largest token tile (8, 4 or 1 tokens per pass over B) whose LDS fits the device limit.
+template <typename T>
+int choose_mask_tiles(lif_layer* L, size_t lds_limit) {
+    size_t need[3];
+    int rc = mask_lds_bytes<T, 1>(L->cfg.rank, &need[0]);
+    if (!rc) rc = mask_lds_bytes<T, 4>(L->cfg.rank, &need[1]);
+    if (!rc) rc = mask_lds_bytes<T, 8>(L->cfg.rank, &need[2]);
+    if (rc) return rc;
+    if (need[0] > lds_limit) return fail(LIF_INVALID_ARG, "rank too large for the LDS of a workgroup on this device");
+    for (int b = 0; b <= 8; ++b) {
+        int bt = 1;
+        if (b > 1 && need[1] <= lds_limit) bt = 4;
+        if (b > 4 && need[2] <= lds_limit) bt = 8;
+        L->mask_bt[b] = bt;
+    }
+    return LIF_OK;
+}
+
 int check_launch() {
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(LIF_HIP_ERROR, "kernel launch: %s", hipGetErrorString(e));
@@ -331,7 +356,7 @@ int check_launch() {
 
 extern "C" {
 
-int lif_version(void) { return 1; }
+int lif_version(void) { return 2; }
 
 const char* lif_last_error_string(void) { return g_err; }
 
@@ -384,6 +409,21 @@ int lif_create(const lif_config* cfg, const lif_buffers* buf, lif_layer** out) {
     L->expected_rows = 0;
     L->prof_on = false;
     L->prof_max = 0;
+    for (int b = 0; b <= 8; ++b) L->mask_bt[b] = 1;
+    if (cfg->predictor == LIF_PRED_LOWRANK) {
+        // the mask kernel keeps t = x A of a tile of tokens in LDS: pick the tile that fits this device
+        int dev = 0, lds_limit = 0;
+        int rc = LIF_OK;
+        hipError_t e = hipGetDevice(&dev);
+        if (e == hipSuccess) e = hipDeviceGetAttribute(&lds_limit, hipDeviceAttributeMaxSharedMemoryPerBlock, dev);
+        if (e != hipSuccess) rc = fail(LIF_HIP_ERROR, "device LDS limit: %s", hipGetErrorString(e));
+        if (!rc) rc = cfg->dtype == LIF_F32 ? choose_mask_tiles<float>(L, (size_t)lds_limit)
+                                            : choose_mask_tiles<_Float16>(L, (size_t)lds_limit);
+        if (rc) {
+            delete L;
+            return rc;
+        }
+    }
     *out = L;
     return LIF_OK;
 }
@@ -406,12 +446,18 @@ int lif_reset(lif_layer* L, void* stream) {
     return check_launch();
 }
 
-int lif_predict(lif_layer* L, const void* x_dev, int32_t batch, uint8_t* masks_dev, uint8_t* step_mask_dev,
-                void* stream) {
+static int check_predict(lif_layer* L, const void* x_dev, int32_t batch, uint8_t* masks_dev, uint8_t* step_mask_dev) {
     if (!L || !x_dev || !masks_dev || !step_mask_dev) return fail(LIF_INVALID_ARG, "null argument");
     if (batch < 1 || batch > L->cfg.max_batch) return fail(LIF_INVALID_ARG, "batch out of range");
     if ((uintptr_t)x_dev % 16) return fail(LIF_INVALID_ARG, "x must be 16-byte aligned");
     if (batch > 1 && masks_dev == step_mask_dev) return fail(LIF_INVALID_ARG, "step mask must not alias the masks when batch > 1");
+    return LIF_OK;
+}
+
+int lif_predict(lif_layer* L, const void* x_dev, int32_t batch, uint8_t* masks_dev, uint8_t* step_mask_dev,
+                void* stream) {
+    int rc = check_predict(L, x_dev, batch, masks_dev, step_mask_dev);
+    if (rc) return rc;
     hipStream_t s = (hipStream_t)stream;
     if (L->cfg.predictor == LIF_PRED_GATE) {
         if (L->cfg.dtype == LIF_F32) launch_predict_gate<float>(L, x_dev, masks_dev, step_mask_dev, s);
@@ -424,12 +470,28 @@ int lif_predict(lif_layer* L, const void* x_dev, int32_t batch, uint8_t* masks_d
     return check_launch();
 }
 
-static int update_window_impl(lif_layer* L, const uint8_t* masks_dev, int ntok, int keep, int32_t* added_dev,
-                              int32_t* n_added_dev, int32_t* removed_dev, int32_t* n_removed_dev, void* stream) {
+static int check_update_window(lif_layer* L, const uint8_t* masks_dev, const int32_t* added_dev,
+                               const int32_t* n_added_dev, const int32_t* removed_dev, const int32_t* n_removed_dev) {
     if (!L || !masks_dev || !added_dev || !n_added_dev || !removed_dev || !n_removed_dev)
         return fail(LIF_INVALID_ARG, "null argument");
     if ((uintptr_t)masks_dev % 8) return fail(LIF_INVALID_ARG, "step mask must be 8-byte aligned");
     if (L->window_pending) return fail(LIF_BAD_STATE, "lif_update_window called twice without lif_load_bundles");
+    return LIF_OK;
+}
+
+static int check_window_tokens(lif_layer* L, int32_t n_tokens, int32_t keep) {
+    if (!L) return fail(LIF_INVALID_ARG, "layer is null");
+    if (n_tokens < 1 || n_tokens > L->cfg.max_batch) return fail(LIF_INVALID_ARG, "n_tokens out of range");
+    if (keep < 0 || keep > n_tokens) return fail(LIF_INVALID_ARG, "keep must be in 0..n_tokens");
+    if (L->cfg.d_ffn % 64) return fail(LIF_INVALID_ARG, "token-granular window updates need d_ffn % 64 == 0");
+    if (L->cfg.shrink_window) return fail(LIF_INVALID_ARG, "token-granular window updates do not combine with shrink_window");
+    return LIF_OK;
+}
+
+static int update_window_impl(lif_layer* L, const uint8_t* masks_dev, int ntok, int keep, int32_t* added_dev,
+                              int32_t* n_added_dev, int32_t* removed_dev, int32_t* n_removed_dev, void* stream) {
+    int rc = check_update_window(L, masks_dev, added_dev, n_added_dev, removed_dev, n_removed_dev);
+    if (rc) return rc;
     hipStream_t s = (hipStream_t)stream;
     const lif_config& c = L->cfg;
     {
@@ -451,11 +513,8 @@ int lif_update_window(lif_layer* L, const uint8_t* step_mask_dev, int32_t* added
 int lif_update_window_tokens(lif_layer* L, const uint8_t* masks_dev, int32_t n_tokens, int32_t keep,
                              int32_t* added_dev, int32_t* n_added_dev, int32_t* removed_dev, int32_t* n_removed_dev,
                              void* stream) {
-    if (!L) return fail(LIF_INVALID_ARG, "layer is null");
-    if (n_tokens < 1 || n_tokens > L->cfg.max_batch) return fail(LIF_INVALID_ARG, "n_tokens out of range");
-    if (keep < 0 || keep > n_tokens) return fail(LIF_INVALID_ARG, "keep must be in 0..n_tokens");
-    if (L->cfg.d_ffn % 64) return fail(LIF_INVALID_ARG, "token-granular window updates need d_ffn % 64 == 0");
-    if (L->cfg.shrink_window) return fail(LIF_INVALID_ARG, "token-granular window updates do not combine with shrink_window");
+    int rc = check_window_tokens(L, n_tokens, keep);
+    if (rc) return rc;
     if (n_tokens == 1 && keep == 1)
         return update_window_impl(L, masks_dev, 1, 1, added_dev, n_added_dev, removed_dev, n_removed_dev, stream);
     return update_window_impl(L, masks_dev, n_tokens, keep, added_dev, n_added_dev, removed_dev, n_removed_dev, stream);
@@ -513,9 +572,16 @@ int lif_sparse_ffn(lif_layer* L, const void* x_dev, int32_t batch, void* y_dev, 
 static int step_impl(lif_layer* L, const void* x_dev, int32_t batch, int32_t keep, void* y_dev, uint8_t* masks_dev,
                      uint8_t* step_mask_dev, int32_t* added_dev, int32_t* n_added_dev, int32_t* removed_dev,
                      int32_t* n_removed_dev, void* stream) {
-    int rc = lif_predict(L, x_dev, batch, masks_dev, step_mask_dev, stream);
+    // every argument and call-order check of the four calls comes before the first launch: a rejected step
+    // leaves the device buffers untouched
+    int rc = check_predict(L, x_dev, batch, masks_dev, step_mask_dev);
     if (rc) return rc;
     if (!y_dev || (uintptr_t)y_dev % 16) return fail(LIF_INVALID_ARG, "y must be a 16-byte aligned device pointer");
+    rc = check_update_window(L, keep < 0 ? step_mask_dev : masks_dev, added_dev, n_added_dev, removed_dev, n_removed_dev);
+    if (rc) return rc;
+    if (keep >= 0 && (rc = check_window_tokens(L, batch, keep))) return rc;
+    rc = lif_predict(L, x_dev, batch, masks_dev, step_mask_dev, stream);
+    if (rc) return rc;
     rc = keep < 0 ? lif_update_window(L, step_mask_dev, added_dev, n_added_dev, removed_dev, n_removed_dev, stream)
                   : lif_update_window_tokens(L, masks_dev, batch, keep, added_dev, n_added_dev, removed_dev,
                                              n_removed_dev, stream);

@@ -41,16 +41,14 @@ template <> struct Vec<float> {
 };
 
 // acc + sum_e a[e] * b[e], products of E-typed values, fp32 accumulation.
+#if defined(__HIP_DEVICE_COMPILE__)     // (the host pass only parses device functions)
+static_assert(__has_builtin(__builtin_amdgcn_fdot2), "built for gfx950: the packed fp16 dot product is required");
+#endif
 __device__ __forceinline__ float dot_acc(f16x8 a, f16x8 b, float acc) {
-#if __has_builtin(__builtin_amdgcn_fdot2)
     acc = __builtin_amdgcn_fdot2(__builtin_shufflevector(a, a, 0, 1), __builtin_shufflevector(b, b, 0, 1), acc, false);
     acc = __builtin_amdgcn_fdot2(__builtin_shufflevector(a, a, 2, 3), __builtin_shufflevector(b, b, 2, 3), acc, false);
     acc = __builtin_amdgcn_fdot2(__builtin_shufflevector(a, a, 4, 5), __builtin_shufflevector(b, b, 4, 5), acc, false);
     acc = __builtin_amdgcn_fdot2(__builtin_shufflevector(a, a, 6, 7), __builtin_shufflevector(b, b, 6, 7), acc, false);
-#else
-#pragma unroll
-    for (int e = 0; e < 8; ++e) acc = __builtin_fmaf((float)a[e], (float)b[e], acc);
-#endif
     return acc;
 }
 __device__ __forceinline__ float dot_acc(f32x4 a, f32x4 b, float acc) {

@@ -167,35 +167,17 @@ __global__ __launch_bounds__(256) void k_ffn_up(const T* __restrict__ matrix, co
                                   &st->num_used, pointers, gact, gact_n, st);
 }
 
-#ifndef LIF_UP_MAX_WGS
-#define LIF_UP_MAX_WGS 1024
-#endif
-constexpr int kUpMaxWgs = LIF_UP_MAX_WGS;   // workgroups of the activation stage: beyond this, waves loop over rows (x stays in registers)
+constexpr int kUpMaxWgs = 1024;   // workgroups of the activation stage: beyond this, waves loop over rows (x stays in registers)
 
 constexpr int kXcds = 8;            // accelerator complex dies of an MI355X, each with a private L2
 constexpr int kDownTile = 2048;     // activations (rows x tokens) compacted per pass (at least 512 rows)
 constexpr int kDownChunksMax = 32;  // row chunks of the down projection (partial outputs per chunk)
-#ifndef LIF_DOWN_LANES_1
-#define LIF_DOWN_LANES_1 4
-#endif
-#ifndef LIF_DOWN_LANES_N
-#define LIF_DOWN_LANES_N 8
-#endif
-#ifndef LIF_DOWN_LANES_B
-#define LIF_DOWN_LANES_B 16
-#endif
-#ifndef LIF_DOWN_ROWS_BATCH
-#define LIF_DOWN_ROWS_BATCH 512
-#endif
-constexpr int kDownLanesB = LIF_DOWN_LANES_B;   // ... for several tokens
-constexpr int kDownLanes1 = LIF_DOWN_LANES_1;   // lanes per column slice, single token skipping dead rows (latency bound)
-constexpr int kDownLanesN = LIF_DOWN_LANES_N;   // ... when most rows are read: 8 x 16 B = one 128-byte line per row
-#ifndef LIF_DOWN_ROWS_SPARSE
-#define LIF_DOWN_ROWS_SPARSE 2048
-#endif
-#ifndef LIF_DOWN_ROWS_DENSE
-#define LIF_DOWN_ROWS_DENSE 512
-#endif
+constexpr int kDownLanesB = 16;       // lanes per column slice for several tokens
+constexpr int kDownLanes1 = 4;        // ... single token skipping dead rows (latency bound)
+constexpr int kDownLanesN = 8;        // ... when most rows are read: 8 x 16 B = one 128-byte line per row
+constexpr int kDownRowsSparse = 2048; // rows per chunk: single token, rows without activation skipped
+constexpr int kDownRowsDense = 512;   // ... single token, every row read
+constexpr int kDownRowsBatch = 512;   // ... several tokens
 
 // Row chunks in use for n cached rows.  For a single token and up to 2048 rows (1024 in full-bundle mode), one
 // chunk (one workgroup per column slice, no partial sums) is the shortest path: the kernel is latency bound
@@ -206,8 +188,8 @@ constexpr int kDownLanesN = LIF_DOWN_LANES_N;   // ... when most rows are read: 
 // workgroups) reach only about 3 TB/s.  The host sizes the grid with the same rule.
 template <int BT, bool SKIP>
 __host__ __device__ __forceinline__ int down_chunks(int n) {
-    constexpr int per = (BT == 1 && SKIP) ? LIF_DOWN_ROWS_SPARSE : (BT == 1 ? LIF_DOWN_ROWS_DENSE : LIF_DOWN_ROWS_BATCH);
-    if (BT == 1 && n <= (SKIP ? LIF_DOWN_ROWS_SPARSE : 2 * LIF_DOWN_ROWS_DENSE)) return 1;
+    constexpr int per = (BT == 1 && SKIP) ? kDownRowsSparse : (BT == 1 ? kDownRowsDense : kDownRowsBatch);
+    if (BT == 1 && n <= (SKIP ? kDownRowsSparse : 2 * kDownRowsDense)) return 1;
     const int c = (n + per - 1) / per;
     return c < 1 ? 1 : (c > kDownChunksMax ? kDownChunksMax : c);
 }

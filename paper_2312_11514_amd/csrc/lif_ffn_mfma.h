@@ -11,10 +11,7 @@
 
 namespace lif {
 
-#ifndef LIF_MFMA_UNROLL
-#define LIF_MFMA_UNROLL 8
-#endif
-constexpr int kMfmaUnroll = LIF_MFMA_UNROLL;     // k-steps (32 elements each) a wave keeps in flight
+constexpr int kMfmaUnroll = 8;     // k-steps (32 elements each) a wave keeps in flight
 
 // grid = ceil(capacity / 16) workgroups of 4 (or 16) waves; workgroup b owns 16 rows and exits at once if
 // they are not in use.  Each wave takes contiguous k-steps (a wave instruction reads 64 bytes of 16 rows;
@@ -24,15 +21,9 @@ constexpr int kMfmaUnroll = LIF_MFMA_UNROLL;     // k-steps (32 elements each) a
 // of B for the k sub-block (l div 16); it receives D[4 * (l div 16) + r][l mod 16], r = 0..3.
 // Here A = rows of the cache, B = tokens (columns >= batch are zero).
 // Requires d % 32 == 0.
-#ifndef LIF_MFMA_WAVES
-#define LIF_MFMA_WAVES 4
-#endif
 constexpr int kMfmaParts = 16;                   // parts of the k range, each summed from zero (see ffn_up_mfma_tile)
-constexpr int kMfmaWaves = LIF_MFMA_WAVES;       // waves per 16-row tile (each takes a contiguous part of the k-steps)
-#ifndef LIF_MFMA_WAVES_FIX
-#define LIF_MFMA_WAVES_FIX 16
-#endif
-constexpr int kMfmaWavesFix = LIF_MFMA_WAVES_FIX; // ... for the short pass over the rows a load wrote: few tiles, so a
+constexpr int kMfmaWaves = 4;       // waves per 16-row tile (each takes a contiguous part of the k-steps)
+constexpr int kMfmaWavesFix = 16; // ... for the short pass over the rows a load wrote: few tiles, so a
                                                   // tile is spread over 16 waves (one round of loads each)
 
 // Which rows a launch of the MFMA activation stage covers.

@@ -18,15 +18,12 @@
 
 namespace lif {
 
-#ifndef LIF_STEP_INFLIGHT_BYTES
-#define LIF_STEP_INFLIGHT_BYTES (256 * 1024)
-#endif
 // The host link runs best with a few hundred KiB of reads outstanding: a read-only gather of 146 bundles of
 // 16 KiB measured 52 GB/s with 256 KiB in flight in pieces of 1 to 8 KiB per wave, 50 GB/s with 384 KiB,
 // 42 GB/s with 16 KiB pieces.
 // The number of loader wave pairs (one bundle in flight per pair, one wave per workgroup so that they spread
 // over compute units) is therefore chosen from the bundle size: kStepInflightBytes / bundle bytes, within 5..32.
-constexpr int kStepInflightBytes = LIF_STEP_INFLIGHT_BYTES;
+constexpr int kStepInflightBytes = 256 * 1024;
 constexpr int kStepLoadWaves = 1;                     // waves of a loader workgroup that load (the others exit at once)
 
 // Loader role.  Work item q covers tail slot s = n' + q (see k_load) and is shared by a PAIR of waves:

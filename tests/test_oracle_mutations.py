@@ -47,8 +47,19 @@ MUTATIONS = [
      "        down, up = rows[:, :d], rows[:, d:]\n", "test_ffn_hand_worked", (None,)),
     ("bundle bytes: gate row forgotten", "return (3 if glu else 2) * d_model * num_bytes",
      "return 2 * d_model * num_bytes", "test_bundle_size_matches_paper_constants", ()),
-    ("gate predictor: activation not rectified", "return a > theta, margin, np.maximum(a, 0.0)",
-     "return a > theta, margin, a", "test_gate_predictor_reproduces_the_dense_gated_ffn", ()),
+    ("gate predictor: activation not rectified", "return a > th, margin, np.maximum(a, 0.0)",
+     "return a > th, margin, a", "test_gate_predictor_reproduces_the_dense_gated_ffn", ()),
+    ("gate predictor: margin measured from zero, not from theta",
+     "    margin = float(np.min(np.abs(a - th))) if np.isfinite(th) and a.size else float(\"inf\")",
+     "    margin = float(np.min(np.abs(a))) if np.isfinite(th) and a.size else float(\"inf\")",
+     "test_gate_predictor_hand_worked", ()),
+    ("gate predictor: threshold not rounded to the ABI's fp32", "    th = np.float64(np.float32(theta))\n    margin = float(np.min(np.abs(a - th)))",
+     "    th = np.float64(theta)\n    margin = float(np.min(np.abs(a - th)))", "test_threshold_is_the_fp32_value_the_abi_carries", ()),
+    ("predictor: threshold not rounded to the ABI's fp32", "    th = np.float64(np.float32(theta))\n    mask = z > th",
+     "    th = np.float64(theta)\n    mask = z > th", "test_threshold_is_the_fp32_value_the_abi_carries", ()),
+    ("pass of tokens: transient masks forgotten", "        for i in range(len(masks)):                    # also one that enters and leaves the window at once\n            transient |= masks[i]",
+     "        for i in range(keep, keep):\n            transient |= masks[i]",
+     "test_layer_pass_of_tokens_equals_the_dense_ffn_restricted_to_the_held_set", ()),
     ("gate ffn: activation looked up by slot", "np.asarray(gate_act, np.float64)[cache.pointers[:n]]",
      "np.asarray(gate_act, np.float64)[:n]", "test_gate_predictor_reproduces_the_dense_gated_ffn", ()),
 ]

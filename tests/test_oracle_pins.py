@@ -191,6 +191,28 @@ def test_threshold_extremes_and_strictness():
     assert list(m[:2]) == [False, True]
 
 
+def test_threshold_is_the_fp32_value_the_abi_carries():
+    """theta crosses the C ABI as a float: both predictors compare against theta rounded to fp32 (0.1 rounds up
+    to 0.100000001490116...), so a logit between the fp64 and the fp32 value of 0.1 is inactive, and the margin
+    is measured from the rounded value."""
+    th32 = float(np.float32(0.1))
+    assert 0.1 < 0.1000000005 < th32
+    z = [0.1000000005, 0.2]
+    A = np.eye(2); B = np.array([[1.0, 0, 0, 0, 0, 0, 0, 0], [0, 1.0, 0, 0, 0, 0, 0, 0]])
+    c = np.array([0, 0, 9, 9, 9, 9, 9, 9.0])
+    m, margin = O.predict_mask(z, A, B, c, 0.1)
+    assert list(m[:2]) == [False, True]
+    assert margin == th32 - 0.1000000005
+    gate = np.eye(2)
+    m, margin, act = O.gate_predict_mask(z, gate, np.zeros(2), 0.1)
+    assert list(m) == [False, True]
+    assert margin == th32 - 0.1000000005
+    assert list(act) == z                                       # the activation is relu(a), whatever theta is
+    # infinite thresholds have no margin to report
+    assert O.gate_predict_mask(z, gate, np.zeros(2), np.inf)[1] == float("inf")
+    assert O.gate_predict_mask(z, gate, np.zeros(2), -np.inf)[0].all()
+
+
 def test_batch_masks_and_step_mask():
     w, L, X = _small_layer()
     M, _ = O.predict_mask(X[:4], L.A, L.B, L.c, 0.0)
@@ -492,6 +514,7 @@ def test_gate_predictor_hand_worked():
         lay = _gate_layer(g, case["theta"])
         r = lay.step(x)
         assert r["masks"].astype(int).tolist() == case["mask"]
+        assert lay.min_margin == case["margin"]                         # min |a - theta|, worked by hand
         assert r["added"].tolist() == [i for i, m in enumerate(case["mask"]) if m]
         assert r["loaded"] == sum(case["mask"]) * 2 * 2 * 4           # up | down of d = 2 fp32 values
         np.testing.assert_allclose(r["y"], case["y"], rtol=0, atol=1e-12)
@@ -522,3 +545,34 @@ def test_gate_predictor_reproduces_the_dense_gated_ffn():
         dense = O.dense_ffn(L.w_up, L.w_down, L.b, x, w_gate=L.w_gate)
         np.testing.assert_allclose(r["y"], dense, rtol=1e-11, atol=1e-13)
         assert r["loaded"] == len(r["added"]) * w.bundle_bytes
+
+
+def test_layer_pass_of_tokens_equals_the_dense_ffn_restricted_to_the_held_set():
+    """OracleLayer.step_tokens (Section 4.3): every token of a pass is computed over the same held set (kept
+    window masks and all masks of the pass), so row i of y is the dense FFN restricted to that set; a pass of one
+    kept token is the ordinary step; bytes loaded = |added| x bundle bytes."""
+    w = wl.scaled(wl.WORKLOADS["C1"], name="spec", d_model=48, d_ffn=128, rank=8, window_k=3, p_active=0.1,
+                  tokens=40, capacity_rows=128)
+    L = wl.make_layer(w)
+    X = wl.make_inputs(w)
+    mk = lambda: O.OracleLayer(w.d_model, w.d_ffn, w.window_k, w.capacity_rows, False, L.A, L.B, L.c, 0.0, L.b,
+                               L.bundles)
+    lay = mk()
+    pos = 0
+    for keep in (4, 2, 0, 1, 4, 3):
+        xb = X[pos:pos + 4]
+        pos += 4
+        r = lay.step_tokens(xb, keep)
+        held = lay.window.active_set()
+        assert set(lay.cache.pointers[:lay.cache.num_used].tolist()) == set(np.flatnonzero(held).tolist())
+        assert r["loaded"] == len(r["added"]) * w.bundle_bytes
+        for i in range(4):
+            assert (r["masks"][i] <= held).all()                     # every token's own mask is held
+            ref = O.dense_ffn(L.w_up, L.w_down, L.b, xb[i], only=held)
+            np.testing.assert_allclose(r["y"][i], ref, rtol=1e-11, atol=1e-13)
+    a, b = mk(), mk()
+    for x in X[:10]:
+        ra, rb = a.step_tokens(x[None, :], 1), b.step(x)
+        assert ra["added"].tolist() == rb["added"].tolist() and ra["removed"].tolist() == rb["removed"].tolist()
+        assert (a.cache.pointers == b.cache.pointers).all()
+        np.testing.assert_array_equal(ra["y"][0], rb["y"])
