@@ -602,7 +602,7 @@ def test_seeded_random_configurations(i):
                 (gpu.layer.step if api == "step" else gpu.layer.step_calls)(xd, gpu.y, w.batch)
                 assert gpu.layer.state()["error"] == 3
                 break
-        assert ora.min_margin > 1e-10
+        assert ora.min_margin > 1e-9
 
 
 @pytest.mark.parametrize("i", range(16))
@@ -645,4 +645,126 @@ def test_seeded_random_speculative_passes(i):
             assert (lay.pointers[:n].cpu().numpy() == ora.cache.pointers[:n]).all()
             assert lay.matrix[:n].cpu().numpy().tobytes() == ora.cache.matrix[:n].tobytes()
             assert rel_l2(gpu.y[:ntok].cpu().numpy(), ref["y"]) <= REL_L2_TOL
-        assert ora.min_margin > 1e-10
+        assert ora.min_margin > 1e-9
+
+
+# ----------------------------------------------------------------------------- advertised paths: ranks, offsets, thresholds, widths
+LOGIT_07, LOGIT_04 = float(np.log(0.7 / 0.3)), float(np.log(0.4 / 0.6))     # sigmoid thresholds 0.7 and 0.4 as logits
+
+
+@pytest.mark.parametrize("batch", [1, 4, 8])
+@pytest.mark.parametrize("rank,dtype", [(512, "f16"), (768, "f16"), (1024, "f16"), (1152, "f16"), (2048, "f16"),
+                                        (1024, "f32"), (2048, "f32")])
+def test_predictor_ranks_of_the_papers_last_layers(rank, dtype, batch):
+    """Predictor ranks above 256 (Appendix: 1024 for the last four OPT layers, 1152 for Falcon and Persimmon):
+    the mask kernel's loop over further rank groups, and the token tiles the host picks from the LDS limit
+    (rank 768 at batch 8 asks for the most LDS)."""
+    w = wl.scaled(wl.WORKLOADS["C1"], name=f"rank{rank}", d_model=256, d_ffn=1096, rank=rank, window_k=3,
+                  p_active=0.08, dtype=dtype, tokens=6, batch=batch, capacity_rows=1096)
+    L = _random_predictor_layer(w, seed=rank + batch)
+    X = wl.make_inputs(w) if batch == 1 else wl.make_batch_inputs(w)
+    stats = run_stream(w, L, X, api="calls" if rank % 1024 else "step")
+    assert np.mean([s["n"] for s in stats]) > 40
+
+
+@pytest.mark.parametrize("api", ["calls", "step"])
+@pytest.mark.parametrize("batch", [1, 3])
+def test_predictor_without_offset(batch, api):
+    """c = NULL: logits are (x A) B alone (about half the neurons are predicted)."""
+    from tests.harness import GpuLayer, compare_step
+    w = wl.scaled(wl.WORKLOADS["C1"], name="noc", d_model=128, d_ffn=520, rank=24, window_k=2, dtype="f16",
+                  tokens=8, batch=batch, capacity_rows=520)
+    L = wl.make_layer(w)
+    L.c = None
+    X = wl.make_inputs(w) if batch == 1 else wl.make_batch_inputs(w)
+    gpu = GpuLayer(w, L, use_c=False)
+    ora = make_oracle(w, L)
+    for t in range(len(X)):
+        r = compare_step(gpu, ora, X[t], w, t, api=api)
+    assert 150 < r["n"] <= 520 and ora.min_margin > 1e-9
+
+
+@pytest.mark.parametrize("api", ["calls", "step"])
+@pytest.mark.parametrize("theta", [LOGIT_07, LOGIT_04])
+@pytest.mark.parametrize("kind", ["lowrank-f16", "lowrank-f32-batch4", "gate-f16", "gate-f32"])
+def test_finite_nonzero_thresholds(kind, theta, api):
+    """theta = logit(0.7) and logit(0.4) (Appendix: sigmoid thresholds of the trained predictors), carried as
+    fp32 through the ABI, for the low-rank and the gate predictor."""
+    gate = kind.startswith("gate")
+    dtype = "f32" if "f32" in kind else "f16"
+    batch = 4 if "batch4" in kind else 1
+    w = wl.scaled(wl.WORKLOADS["C1"], name=kind, d_model=264 if dtype == "f16" else 132, d_ffn=1096, rank=40,
+                  window_k=3, p_active=0.1, dtype=dtype, glu=gate, gate_resident=gate, tokens=12, batch=batch,
+                  capacity_rows=1096)
+    L = wl.make_layer(w)
+    L.theta = theta
+    if not gate:
+        L.c = (L.c * 0.5).astype(np.float32)         # logits of both signs around the threshold
+    X = wl.make_inputs(w) if batch == 1 else wl.make_batch_inputs(w)
+    stats = run_stream(w, L, X, api=api)
+    assert np.mean([s["n"] for s in stats]) > 20
+
+
+@pytest.mark.parametrize("api", ["calls", "step"])
+@pytest.mark.parametrize("variant", ["plain", "gated", "gate-predictor", "batch4"])
+@pytest.mark.parametrize("d_model,dtype", [(2048, "f16"), (2560, "f16"), (5120, "f16"), (1024, "f32"), (1288, "f32")])
+def test_row_widths_between_the_benchmark_shapes(d_model, dtype, variant, api):
+    """d_model 2048, 2560 (Phi-2) and 5120 in fp16, 1024 and 1288 in fp32: 4, 5/6 and 10/12 loads of 16 bytes per
+    lane and vector, the kernel instantiations that the benchmark shapes (1, 2, 8, 9, 16 loads) do not use."""
+    gate = variant == "gate-predictor"
+    batch = 4 if variant == "batch4" else 1
+    w = wl.scaled(wl.WORKLOADS["C1"], name=f"w{d_model}", d_model=d_model, d_ffn=512, rank=16, window_k=3,
+                  p_active=0.08, dtype=dtype, glu=(variant != "plain" and variant != "batch4"), gate_resident=gate,
+                  tokens=6, batch=batch, capacity_rows=300)
+    L = _random_predictor_layer(wl.scaled(w, gate_resident=False), seed=d_model)
+    if gate:                                             # bundles without the gate row; the gate stays resident
+        L.bundles = np.ascontiguousarray(np.concatenate([L.w_up, L.w_down], axis=1))
+    X = wl.make_inputs(w) if batch == 1 else wl.make_batch_inputs(w)
+    stats = run_stream(w, L, X, api=api)
+    assert np.mean([s["n"] for s in stats]) > 20
+
+
+@pytest.mark.parametrize("api", ["calls", "step"])
+@pytest.mark.parametrize("batch", [6, 7])
+@pytest.mark.parametrize("d_model,dtype,glu", [(608, "f16", True), (568, "f16", False), (256, "f32", False)])
+def test_batches_of_six_and_seven_tokens(d_model, dtype, glu, batch, api):
+    w = wl.scaled(wl.WORKLOADS["C1"], name="batched", d_model=d_model, d_ffn=1096, rank=40, window_k=3,
+                  p_active=0.06, dtype=dtype, glu=glu, tokens=8, batch=batch, capacity_rows=1003)
+    run_stream(w, wl.make_layer(w), wl.make_batch_inputs(w), api=api)
+
+
+def test_rejected_step_leaves_device_buffers_untouched():
+    """lif_step checks every argument and the call order before its first launch: a rejected call changes neither
+    the masks nor the state."""
+    from tests.harness import GpuLayer
+    import paper_2312_11514_amd as lif
+    import ctypes as C
+    w = wl.scaled(wl.WORKLOADS["C1"], tokens=3)
+    L = wl.make_layer(w)
+    gpu = GpuLayer(w, L)
+    lay = gpu.layer
+    X = gpu.upload_x(wl.make_inputs(w))
+    lay.step(X[0], gpu.y)
+    torch.cuda.synchronize()
+    snap = lambda: (lay.masks.clone(), lay.step_mask.clone(), lay.added.clone(), lay.state(), lay.counters())
+    before = snap()
+    st = C.c_void_p(torch.cuda.current_stream().cuda_stream)
+    p = lambda t: C.c_void_p(t.data_ptr())
+    args = lambda y: (lay.handle, p(X[1]), 1, y, p(lay.masks), p(lay.step_mask), p(lay.added), p(lay.n_added),
+                      p(lay.removed), p(lay.n_removed), st)
+    assert lay.lib.lif_step(*args(C.c_void_p(0))) == lif.LIF_INVALID_ARG                   # y is null
+    assert lay.lib.lif_step(*args(C.c_void_p(gpu.y.data_ptr() + 2))) == lif.LIF_INVALID_ARG   # y misaligned
+    lay.predict(X[1])
+    lay.update_window()                                                                   # a window update is pending
+    mid = snap()
+    assert lay.lib.lif_step(*args(p(gpu.y))) == lif.LIF_BAD_STATE
+    assert lay.lib.lif_step_tokens(lay.handle, p(X[1]), 1, 2, p(gpu.y), p(lay.masks), p(lay.step_mask), p(lay.added),
+                                   p(lay.n_added), p(lay.removed), p(lay.n_removed), st) == lif.LIF_INVALID_ARG
+    torch.cuda.synchronize()
+    after = snap()
+    for a, b in zip(mid, after):
+        assert (torch.equal(a, b) if isinstance(a, torch.Tensor) else a == b)
+    assert before[3]["step"] + 1 == after[3]["step"]
+    lay.load_bundles()
+    lay.sparse_ffn(X[1], gpu.y)
+    assert lay.state()["error"] == 0
