@@ -417,6 +417,7 @@ int lif_create(const lif_config* cfg, const lif_buffers* buf, lif_layer** out) {
         hipError_t e = hipGetDevice(&dev);
         if (e == hipSuccess) e = hipDeviceGetAttribute(&lds_limit, hipDeviceAttributeMaxSharedMemoryPerBlock, dev);
         if (e != hipSuccess) rc = fail(LIF_HIP_ERROR, "device LDS limit: %s", hipGetErrorString(e));
+        lds_limit = std::min(lds_limit, 64 * 1024);      // no launch of this library asks for more than 64 KiB
         if (!rc) rc = cfg->dtype == LIF_F32 ? choose_mask_tiles<float>(L, (size_t)lds_limit)
                                             : choose_mask_tiles<_Float16>(L, (size_t)lds_limit);
         if (rc) {
@@ -577,9 +578,9 @@ static int step_impl(lif_layer* L, const void* x_dev, int32_t batch, int32_t kee
     int rc = check_predict(L, x_dev, batch, masks_dev, step_mask_dev);
     if (rc) return rc;
     if (!y_dev || (uintptr_t)y_dev % 16) return fail(LIF_INVALID_ARG, "y must be a 16-byte aligned device pointer");
+    if (keep >= 0 && (rc = check_window_tokens(L, batch, keep))) return rc;
     rc = check_update_window(L, keep < 0 ? step_mask_dev : masks_dev, added_dev, n_added_dev, removed_dev, n_removed_dev);
     if (rc) return rc;
-    if (keep >= 0 && (rc = check_window_tokens(L, batch, keep))) return rc;
     rc = lif_predict(L, x_dev, batch, masks_dev, step_mask_dev, stream);
     if (rc) return rc;
     rc = keep < 0 ? lif_update_window(L, step_mask_dev, added_dev, n_added_dev, removed_dev, n_removed_dev, stream)
