@@ -239,6 +239,26 @@ int lif_load_bundles(lif_layer* layer, const int32_t* added_dev, const int32_t* 
 int lif_sparse_ffn(lif_layer* layer, const void* x_dev, int32_t batch, void* y_dev, void* stream);
 
 /*
+ * lif_sparse_ffn for callers that cannot allocate and want no scratch of their own in the call: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid allocation.  Same arguments, same arithmetic
+ * and bit-identical results; the activations and the partial outputs of the call (the scratch that
+ * lif_sparse_ffn keeps in the layer's workspace) live in a static device array inside the library instead, of
+ * lif_static_scratch_bytes() = 5 MiB, which every GPU the library runs on holds until the process ends.  The call
+ * allocates nothing and frees nothing.
+ *   limit   256-byte-rounded 4 * batch * capacity_rows  +  4 * 32 * batch * d_model  <=  lif_static_scratch_bytes()
+ *           (batch 8 at d_model 4096 fits up to 32768 rows, a single token at any shape); beyond it LIF_INVALID_ARG,
+ *           nothing is launched
+ *   errors  as lif_sparse_ffn; LIF_HIP_ERROR if the array's address could not be obtained on the layer's device
+ * All layers on one GPU share the array: calls that overlap on one GPU (different streams, different layers)
+ * race on it; calls on one stream are safe.  Nothing in the array has to be cleared between calls (every value a
+ * call reads was written by that call), and its contents after a call are unspecified.
+ */
+int lif_sparse_ffn_static(lif_layer* layer, const void* x_dev, int32_t batch, void* y_dev, void* stream);
+
+/* Size in bytes of the static scratch array behind lif_sparse_ffn_static. */
+size_t lif_static_scratch_bytes(void);
+
+/*
  * One whole step in one call: lif_predict, lif_update_window, lif_load_bundles and
  * lif_sparse_ffn on the same x, with the same arguments, results and error behaviour as the
  * four calls in sequence.  The cache update and the activation stage of the FFN share one

@@ -55,6 +55,8 @@ EXPORTS = {
     "lif_update_window_tokens": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32] + [C.c_void_p] * 4 + [C.c_void_p]),
     "lif_load_bundles": (C.c_int, [C.c_void_p] + [C.c_void_p] * 4 + [C.c_void_p]),
     "lif_sparse_ffn": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]),
+    "lif_sparse_ffn_static": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]),
+    "lif_static_scratch_bytes": (C.c_size_t, []),
     "lif_step": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p] + [C.c_void_p] * 6 + [C.c_void_p]),
     "lif_step_tokens": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p] + [C.c_void_p] * 6 +
                         [C.c_void_p]),
@@ -189,6 +191,10 @@ class Layer:
 
     def sparse_ffn(self, x, y, batch=1):
         _check(self.lib.lif_sparse_ffn(self.handle, _ptr(x), batch, _ptr(y), _stream()))
+
+    def sparse_ffn_static(self, x, y, batch=1):
+        """lif_sparse_ffn_static: the same call with its scratch in the library's static device array."""
+        _check(self.lib.lif_sparse_ffn_static(self.handle, _ptr(x), batch, _ptr(y), _stream()))
 
     def step(self, x, y, batch=1):
         """lif_step: the whole step in one call (fused cache update + activations for batch 1)."""

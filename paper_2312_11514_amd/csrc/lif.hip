@@ -18,6 +18,11 @@
 
 using namespace lif;
 
+// Scratch of lif_sparse_ffn_static: activations and partial outputs of one FFN call.  One copy per GPU, at its own
+// address on each; host code reaches it only through the pointer hipGetSymbolAddress returns for the current device.
+constexpr size_t kStaticScratchBytes = 5u << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 namespace {
 
 thread_local char g_err[512] = "";
@@ -115,6 +120,7 @@ struct lif_layer {
     bool window_pending;
     int expected_rows;          // hint, 0 = none
     int mask_bt[9];             // tokens per pass of the mask kernel for a batch of b tokens (1, 4 or 8)
+    unsigned char* static_scratch;  // this device's copy of the library's static scratch array (null: lookup failed)
     // event timing
     bool prof_on;
     int prof_max;
@@ -193,8 +199,10 @@ void launch_predict_gate(lif_layer* L, const void* x, uint8_t* masks, uint8_t* s
 #undef LIF_PG
 }
 
+// `h` (activations) and `ypart` (partial outputs) of the FFN launches: the workspace arrays of the layer, or the
+// library's static scratch (lif_sparse_ffn_static)
 template <typename T, bool GLU>
-void launch_ffn_up(lif_layer* L, const void* x, int batch, hipStream_t s) {
+void launch_ffn_up(lif_layer* L, const void* x, int batch, float* h, hipStream_t s) {
     const lif_config& c = L->cfg;
     const int nvec = c.d_model / Vec<T>::N;
     const int ni = (nvec + 63) / 64;
@@ -205,7 +213,7 @@ void launch_ffn_up(lif_layer* L, const void* x, int batch, hipStream_t s) {
     const size_t shm = batch == 1 ? 0 : (size_t)batch * c.d_model * sizeof(T);
 #define LIF_UP_X(NI, XREG)                                                                                   \
     hipLaunchKernelGGL((k_ffn_up<T, NI, GLU, XREG>), dim3(grid), dim3(256), shm, s, (const T*)L->buf.matrix,    \
-                       L->buf.bias, (const T*)x, L->h, c.d_model, batch, c.capacity_rows, L->row_elems, spec,     \
+                       L->buf.bias, (const T*)x, h, c.d_model, batch, c.capacity_rows, L->row_elems, spec,        \
                        L->buf.pointers, L->gact, c.d_ffn, L->st)
 #define LIF_UP(NI) do { if (batch == 1) LIF_UP_X(NI, true); else LIF_UP_X(NI, false); } while (0)
     if (ni <= 1) LIF_UP(1);
@@ -221,7 +229,7 @@ void launch_ffn_up(lif_layer* L, const void* x, int batch, hipStream_t s) {
 }
 
 template <typename T, int BT, bool SKIP, int LANES>
-void launch_ffn_down_as(lif_layer* L, int batch, void* y, hipStream_t s, bool use_new) {
+void launch_ffn_down_as(lif_layer* L, int batch, void* y, float* h, float* ypart, hipStream_t s, bool use_new) {
     const lif_config& c = L->cfg;
     const int cols = LANES * Vec<T>::N;
     int slices = (c.d_model + cols - 1) / cols;
@@ -233,25 +241,25 @@ void launch_ffn_down_as(lif_layer* L, int batch, void* y, hipStream_t s, bool us
     const int wg_rows = down_chunks<BT, SKIP>(rows_hint);
     const int down_off = (c.glu ? 2 : 1) * c.d_model;
     hipLaunchKernelGGL((k_ffn_down<T, BT, SKIP, LANES>), dim3(slices, wg_rows), dim3(256), 0, s,
-                       (const T*)L->buf.matrix, L->h, use_new ? L->h_new : nullptr, use_new ? L->stamp : nullptr,
-                       (T*)y, L->ypart, c.d_model, batch, c.capacity_rows, L->row_elems, down_off, L->st);
+                       (const T*)L->buf.matrix, h, use_new ? L->h_new : nullptr, use_new ? L->stamp : nullptr,
+                       (T*)y, ypart, c.d_model, batch, c.capacity_rows, L->row_elems, down_off, L->st);
     if (wg_rows > 1)
         hipLaunchKernelGGL((k_ffn_down_finish<T, BT, SKIP>), dim3((batch * c.d_model + 255) / 256), dim3(256), 0, s,
-                           L->ypart, (T*)y, c.d_model, batch, L->st);
+                           ypart, (T*)y, c.d_model, batch, L->st);
 }
 
 template <typename T>
-void launch_ffn_down(lif_layer* L, int batch, void* y, hipStream_t s, bool use_new = false) {
+void launch_ffn_down(lif_layer* L, int batch, void* y, float* h, float* ypart, hipStream_t s, bool use_new = false) {
     const bool skip = L->cfg.ffn_mode == LIF_FFN_SKIP_DEAD;
     if (batch == 1) {
-        if (skip) launch_ffn_down_as<T, 1, true, kDownLanes1>(L, batch, y, s, use_new);
-        else launch_ffn_down_as<T, 1, false, kDownLanesN>(L, batch, y, s, use_new);
+        if (skip) launch_ffn_down_as<T, 1, true, kDownLanes1>(L, batch, y, h, ypart, s, use_new);
+        else launch_ffn_down_as<T, 1, false, kDownLanesN>(L, batch, y, h, ypart, s, use_new);
     } else if (batch <= 4) {
-        if (skip) launch_ffn_down_as<T, 4, true, kDownLanesB>(L, batch, y, s, use_new);
-        else launch_ffn_down_as<T, 4, false, kDownLanesB>(L, batch, y, s, use_new);
+        if (skip) launch_ffn_down_as<T, 4, true, kDownLanesB>(L, batch, y, h, ypart, s, use_new);
+        else launch_ffn_down_as<T, 4, false, kDownLanesB>(L, batch, y, h, ypart, s, use_new);
     } else {
-        if (skip) launch_ffn_down_as<T, 8, true, kDownLanesB>(L, batch, y, s, use_new);
-        else launch_ffn_down_as<T, 8, false, kDownLanesB>(L, batch, y, s, use_new);
+        if (skip) launch_ffn_down_as<T, 8, true, kDownLanesB>(L, batch, y, h, ypart, s, use_new);
+        else launch_ffn_down_as<T, 8, false, kDownLanesB>(L, batch, y, h, ypart, s, use_new);
     }
 }
 
@@ -288,7 +296,7 @@ bool mfma_path(const lif_config& c, int batch) {
 }
 
 template <int MODE>
-void launch_ffn_up_mfma(lif_layer* L, const void* x, int batch, hipStream_t s) {
+void launch_ffn_up_mfma(lif_layer* L, const void* x, int batch, float* h, hipStream_t s) {
     const lif_config& c = L->cfg;
     constexpr int W = (MODE == kRowsChanged) ? kMfmaWavesFix : kMfmaWaves;
     // the rows a load wrote are few: a small grid strides over their tiles
@@ -296,11 +304,11 @@ void launch_ffn_up_mfma(lif_layer* L, const void* x, int batch, hipStream_t s) {
     const int grid = (MODE == kRowsChanged) ? std::min(tiles, 64) : tiles;
     if (c.glu)
         hipLaunchKernelGGL((k_ffn_up_mfma<true, MODE, W>), dim3(grid), dim3(W * 64), 0, s,
-                           (const _Float16*)L->buf.matrix, L->buf.bias, (const _Float16*)x, L->h, c.d_model, batch,
+                           (const _Float16*)L->buf.matrix, L->buf.bias, (const _Float16*)x, h, c.d_model, batch,
                            c.capacity_rows, L->row_elems, L->move_dst, L->st);
     else
         hipLaunchKernelGGL((k_ffn_up_mfma<false, MODE, W>), dim3(grid), dim3(W * 64), 0, s,
-                           (const _Float16*)L->buf.matrix, L->buf.bias, (const _Float16*)x, L->h, c.d_model, batch,
+                           (const _Float16*)L->buf.matrix, L->buf.bias, (const _Float16*)x, h, c.d_model, batch,
                            c.capacity_rows, L->row_elems, L->move_dst, L->st);
 }
 
@@ -410,6 +418,13 @@ int lif_create(const lif_config* cfg, const lif_buffers* buf, lif_layer** out) {
     L->prof_on = false;
     L->prof_max = 0;
     for (int b = 0; b <= 8; ++b) L->mask_bt[b] = 1;
+    {
+        // address of the static scratch array on the device that is current now (the layer's device)
+        void* p = nullptr;
+        hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        L->static_scratch = (e == hipSuccess) ? (unsigned char*)p : nullptr;
+        if (e != hipSuccess) (void)hipGetLastError();      // reported by lif_sparse_ffn_static, not by a later launch
+    }
     if (cfg->predictor == LIF_PRED_LOWRANK) {
         // the mask kernel keeps t = x A of a tile of tokens in LDS: pick the tile that fits this device
         int dev = 0, lds_limit = 0;
@@ -540,32 +555,61 @@ int lif_load_bundles(lif_layer* L, const int32_t* added_dev, const int32_t* n_ad
     return check_launch();
 }
 
-int lif_sparse_ffn(lif_layer* L, const void* x_dev, int32_t batch, void* y_dev, void* stream) {
+static int check_ffn(lif_layer* L, const void* x_dev, int32_t batch, void* y_dev) {
     if (!L || !x_dev || !y_dev) return fail(LIF_INVALID_ARG, "null argument");
     if (batch < 1 || batch > L->cfg.max_batch) return fail(LIF_INVALID_ARG, "batch out of range");
     if ((uintptr_t)x_dev % 16 || (uintptr_t)y_dev % 16) return fail(LIF_INVALID_ARG, "x and y must be 16-byte aligned");
-    hipStream_t s = (hipStream_t)stream;
+    return LIF_OK;
+}
+
+// the two FFN stages with their scratch: activations h, partial outputs ypart
+static int ffn_launches(lif_layer* L, const void* x_dev, int32_t batch, void* y_dev, float* h, float* ypart,
+                        hipStream_t s) {
     const lif_config& c = L->cfg;
     if (mfma_path(c, batch)) {
         // batched tokens: the activation stage is a dense contraction -> matrix cores
         Timed t(L, LIF_K_FFN_UP, s);
-        launch_ffn_up_mfma<kRowsAll>(L, x_dev, batch, s);
+        launch_ffn_up_mfma<kRowsAll>(L, x_dev, batch, h, s);
     } else {
         Timed t(L, LIF_K_FFN_UP, s);
         if (c.dtype == LIF_F32) {
-            if (c.glu) launch_ffn_up<float, true>(L, x_dev, batch, s);
-            else launch_ffn_up<float, false>(L, x_dev, batch, s);
+            if (c.glu) launch_ffn_up<float, true>(L, x_dev, batch, h, s);
+            else launch_ffn_up<float, false>(L, x_dev, batch, h, s);
         } else {
-            if (c.glu) launch_ffn_up<_Float16, true>(L, x_dev, batch, s);
-            else launch_ffn_up<_Float16, false>(L, x_dev, batch, s);
+            if (c.glu) launch_ffn_up<_Float16, true>(L, x_dev, batch, h, s);
+            else launch_ffn_up<_Float16, false>(L, x_dev, batch, h, s);
         }
     }
     {
         Timed t(L, LIF_K_FFN_DOWN, s);
-        if (c.dtype == LIF_F32) launch_ffn_down<float>(L, batch, y_dev, s);
-        else launch_ffn_down<_Float16>(L, batch, y_dev, s);
+        if (c.dtype == LIF_F32) launch_ffn_down<float>(L, batch, y_dev, h, ypart, s);
+        else launch_ffn_down<_Float16>(L, batch, y_dev, h, ypart, s);
     }
     return check_launch();
+}
+
+int lif_sparse_ffn(lif_layer* L, const void* x_dev, int32_t batch, void* y_dev, void* stream) {
+    int rc = check_ffn(L, x_dev, batch, y_dev);
+    if (rc) return rc;
+    return ffn_launches(L, x_dev, batch, y_dev, L->h, L->ypart, (hipStream_t)stream);
+}
+
+size_t lif_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+int lif_sparse_ffn_static(lif_layer* L, const void* x_dev, int32_t batch, void* y_dev, void* stream) {
+    int rc = check_ffn(L, x_dev, batch, y_dev);
+    if (rc) return rc;
+    if (!L->static_scratch) return fail(LIF_HIP_ERROR, "the static scratch array has no address on this device");
+    // activations [batch x capacity_rows] fp32, then the partial outputs [row chunks x batch x d_model] fp32
+    const lif_config& c = L->cfg;
+    const size_t h_bytes = align_up(sizeof(float) * (size_t)batch * c.capacity_rows, 256);
+    const size_t ypart_bytes = sizeof(float) * (size_t)kDownChunksMax * batch * c.d_model;
+    if (h_bytes + ypart_bytes > kStaticScratchBytes)
+        return fail(LIF_INVALID_ARG, "batch x capacity_rows and batch x d_model exceed the static scratch (5 MiB); use lif_sparse_ffn");
+    // the kernels take the scratch as arguments, exactly as they take the workspace arrays in lif_sparse_ffn;
+    // nothing in it has to start at zero: every activation and every partial that is read was written by this call
+    return ffn_launches(L, x_dev, batch, y_dev, reinterpret_cast<float*>(L->static_scratch),
+                        reinterpret_cast<float*>(L->static_scratch + h_bytes), (hipStream_t)stream);
 }
 
 // keep < 0: the window advances by one step whose mask is the OR over the batch (lif_update_window);
@@ -605,10 +649,10 @@ static int step_impl(lif_layer* L, const void* x_dev, int32_t batch, int32_t kee
         L->window_pending = false;
         {
             Timed t(L, LIF_K_FFN_UP, s);
-            launch_ffn_up_mfma<kRowsChanged>(L, x_dev, batch, s);
+            launch_ffn_up_mfma<kRowsChanged>(L, x_dev, batch, L->h, s);
         }
         Timed t(L, LIF_K_FFN_DOWN, s);
-        launch_ffn_down<_Float16>(L, batch, y_dev, s);
+        launch_ffn_down<_Float16>(L, batch, y_dev, L->h, L->ypart, s);
         return check_launch();
     }
     {
@@ -624,8 +668,8 @@ static int step_impl(lif_layer* L, const void* x_dev, int32_t batch, int32_t kee
     L->window_pending = false;
     {
         Timed t(L, LIF_K_FFN_DOWN, s);
-        if (c.dtype == LIF_F32) launch_ffn_down<float>(L, 1, y_dev, s, true);
-        else launch_ffn_down<_Float16>(L, 1, y_dev, s, true);
+        if (c.dtype == LIF_F32) launch_ffn_down<float>(L, 1, y_dev, L->h, L->ypart, s, true);
+        else launch_ffn_down<_Float16>(L, 1, y_dev, L->h, L->ypart, s, true);
     }
     return check_launch();
 }
