@@ -52,6 +52,8 @@ def cpu_baseline(w, L, X, budget_s=20.0):
             break
     dt = time.perf_counter() - t0
     out = {"value": dt / done * 1e6, "unit": "us/token/layer", "cores": int(cores), "kind": "oracle",
+           "cores_note": "threads of the BLAS pool under numpy's matrix products; the oracle itself is one Python "
+                         "thread (its window, delete and insert steps are plain loops), so more threads do not help it",
            "sample": f"first {done} steps of the same stream on layer 0, whole path "
                      f"(predict, window, delete, insert, FFN)"}
     # the same oracle on one core, on a shorter sample
@@ -105,13 +107,22 @@ def pmc_traffic(pmc_dir):
         if not copies or max(copies) <= 0:
             return None
         scale = 262144.0 / max(copies)                       # reported KiB -> true KiB (the copy moves 256 MiB each way)
-        up = [(int(r["Dispatch_Id"]), float(r["Counter_Value"])) for r in rows if "k_ffn_up" in r["Kernel_Name"]]
-        if not up:
+        # one lif_sparse_ffn call = a k_ffn_up dispatch and the k_ffn_down (+ finish) dispatches right after it
+        # (lif_step never launches k_ffn_up on its own, so these are exactly the FFN-only calls)
+        rows.sort(key=lambda r: int(r["Dispatch_Id"]))
+        calls, total, open_call = 0, 0.0, False
+        for r in rows:
+            name = r["Kernel_Name"]
+            if "k_ffn_up" in name:
+                calls, open_call = calls + 1, True
+                total += float(r["Counter_Value"])
+            elif open_call and "k_ffn_down" in name:
+                total += float(r["Counter_Value"])
+            else:
+                open_call = False
+        if not calls:
             return None
-        lo, hi = min(i for i, _ in up), max(i for i, _ in up)  # the FFN-only phase (lif_step never launches k_ffn_up alone)
-        ffn = [float(r["Counter_Value"]) for r in rows
-               if lo <= int(r["Dispatch_Id"]) <= hi and "k_ffn_" in r["Kernel_Name"]]
-        out[counter] = {"scale": scale, "bytes_per_call": sum(ffn) * scale * 1024.0 / len(up)}
+        out[counter] = {"scale": scale, "bytes_per_call": total * scale * 1024.0 / calls, "calls": calls}
     return out
 
 
@@ -256,6 +267,242 @@ def sweep_rows(args):
     print(json.dumps({"sweep": "cached rows per lif_sparse_ffn call", "workload": describe(w), "rows": out}))
 
 
+_T0 = time.perf_counter()
+
+
+def progress(msg):
+    print(f"[bench {time.perf_counter() - _T0:6.1f}s] {msg}", file=sys.stderr, flush=True)
+
+
+def _timed_replays(graph, reps):
+    """HIP events on the launch stream around `reps` replays of a captured graph; returns milliseconds."""
+    import torch
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        graph.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1)
+
+
+def read_floor(dev, sizes):
+    """Same-box reference for the roofline: a plain streaming-read kernel (lif_profile_read) launched back to back
+    inside a HIP graph, for an empty launch and for the given byte counts.  Buffers up to 64 MB are read again and
+    again (warm in the 256 MB Infinity Cache, like a single layer's cache); the larger ones cycle through 2 GiB."""
+    import torch
+    import paper_2312_11514_amd as lif
+    big = torch.empty(2 << 30, dtype=torch.uint8, device=dev)
+    big.zero_()
+    sink = torch.zeros(4, dtype=torch.int32, device=dev)
+    out = {}
+    for name, nbytes in sizes:
+        nbytes = int(nbytes) // 16 * 16
+        warm = nbytes <= (64 << 20)
+        n_launch = 200 if warm else max(4, min(64, (8 << 30) // max(nbytes, 1)))
+        slots = 1 if warm else max(1, (2 << 30) // nbytes)
+        g = torch.cuda.CUDAGraph()
+        lif.profile_read(big, nbytes, sink)
+        torch.cuda.synchronize()
+        with torch.cuda.graph(g):
+            for i in range(n_launch):
+                lif.profile_read(big[(i % slots) * nbytes:], nbytes, sink)
+        g.replay()
+        torch.cuda.synchronize()
+        us = _timed_replays(g, 5) * 1e3 / (5 * n_launch)
+        out[name] = {"bytes": nbytes, "us_per_launch": us, "GBs": nbytes / us / 1e3 if nbytes else None,
+                     "source": "Infinity-Cache warm" if warm else "HBM (2 GiB cycled)"}
+    del big
+    return out
+
+
+def ffn_over_states(w, gpu0, L0, states, xd, mode, hint, no_graph):
+    """The FFN alone over several (cache state, x) pairs of the stream.
+
+    One more layer handle per state shares layer 0's predictor arrays and bundle store and holds that token's cache
+    (same slot order).  warm: per state, a HIP graph of 50 back-to-back lif_sparse_ffn calls (the rows stay in the
+    256 MB Infinity Cache).  cold: one HIP graph that calls every state's layer in turn, 8 rounds: 32 caches of
+    ~20 MB are 640 MB, so every call streams its rows from HBM."""
+    import torch
+    from workloads.device import GpuLayer
+    import numpy as np
+    E, d, G = w.elem_bytes, w.d_model, w.vectors_per_bundle
+    reads_all = mode != 0
+    lays = []
+    for t, ids in states:
+        g = GpuLayer(w, L0, ffn_mode=mode, share=gpu0)
+        g.fill_cache(ids, L0)
+        if hint:
+            g.layer.set_expected_rows(hint)
+        if w.gate_resident:
+            g.layer.predict(xd[t], w.batch)           # leaves the gate activations the FFN of this variant reads
+        lays.append((t, g))
+    torch.cuda.synchronize()
+
+    def measure(calls_fn, n_calls, reps, which):
+        if no_graph:
+            class _E:
+                replay = staticmethod(calls_fn)
+            g = _E()
+        else:
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                calls_fn()
+        g.replay()
+        torch.cuda.synchronize()
+        c0 = [l.layer.counters() for _, l in which]
+        ms = _timed_replays(g, reps)
+        c1 = [l.layer.counters() for _, l in which]
+        calls = sum(b["ffn_calls"] - a["ffn_calls"] for a, b in zip(c0, c1))
+        assert calls == n_calls * reps, (calls, n_calls, reps)
+        rows = sum(b["ffn_rows"] - a["ffn_rows"] for a, b in zip(c0, c1)) / calls
+        act = sum(b["ffn_active"] - a["ffn_active"] for a, b in zip(c0, c1)) / calls
+        return ms * 1e3 / calls, rows, act
+
+    def fig(us, rows, act):
+        touched = rows * (G - 1) * d * E + (rows if reads_all else act) * d * E
+        nominal = rows * G * d * E
+        return {"avg_launch_us": us, "rows": rows, "rows_active": act, "algorithmic_bytes_per_launch": touched,
+                "achieved": touched / us / 1e3, "nominal_bundle_bytes": nominal, "nominal_GBs": nominal / us / 1e3}
+
+    per_state = []
+    for t, g in lays[:16]:
+        def calls(g=g, t=t):
+            for _ in range(50):
+                g.layer.sparse_ffn(xd[t], g.y, w.batch)
+        per_state.append(fig(*measure(calls, 50, 4, [(t, g)])))
+
+    def all_layers():
+        for _ in range(8):
+            for t, g in lays:
+                g.layer.sparse_ffn(xd[t], g.y, w.batch)
+    cold = fig(*measure(all_layers, 8 * len(lays), 5, lays))
+    cold["caches"] = len(lays)
+    cold["bytes_cycled"] = sum(len(ids) for _, ids in states) * G * d * E
+    for _, g in lays:
+        g.layer.close()
+    return per_state, cold
+
+
+def roofline_object(f, kernel, extra=None):
+    out = {"bound": "hbm", "kernel": kernel, "achieved": f["achieved"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+           "frac": f["achieved"] / HBM_PEAK_GBS, "traffic": None,
+           "algorithmic_bytes_per_launch": f["algorithmic_bytes_per_launch"], "avg_launch_us": f["avg_launch_us"],
+           "rows": f["rows"], "rows_active": f["rows_active"], "nominal_bundle_bytes": f["nominal_bundle_bytes"],
+           "nominal_GBs": f["nominal_GBs"], "nominal_frac": f["nominal_GBs"] / HBM_PEAK_GBS}
+    out.update(extra or {})
+    return out
+
+
+def bench_stacked(w, base, mode, steps, warmup, no_graph=False, hint=True, ffn_rounds=8, profile=True):
+    """Stacked layers (C5): every layer has its own predictor, window, cache and pinned bundle store; one HIP graph
+    per token covers all layers.  Returns the figures of the bench line that depend on the run."""
+    import torch
+    import workloads as wl
+    from workloads.device import GpuLayer
+    NL = w.layers
+    X = wl.make_inputs(w)
+    T = len(X)
+    gpus = []
+    for l in range(NL):
+        Ll = wl.make_layer_variant(base, w, l)
+        gpus.append(GpuLayer(w, Ll, ffn_mode=mode))      # uploads A, B, c, b; pins the bundle store
+        del Ll
+        if l % 8 == 7:
+            progress(f"  layer {l + 1} of {NL} uploaded")
+    layers = [g.layer for g in gpus]
+    xd = gpus[0].upload_x(X)
+    x_stage = torch.zeros_like(xd[0])
+    y_stage = torch.zeros((NL,) + tuple(xd[0].shape), dtype=xd.dtype, device=xd.device)
+
+    def token_all_layers():
+        for l, lay in enumerate(layers):
+            lay.step(x_stage, y_stage[l], w.batch)
+    for lay in layers:
+        lay.reset()
+    x_stage.copy_(xd[0])
+    token_all_layers()
+    torch.cuda.synchronize()
+
+    def capture():
+        if no_graph:
+            return token_all_layers
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            token_all_layers()
+        return g.replay
+    tok = capture()
+
+    def step():
+        for lay in layers:
+            lay.reset()
+        for t in range(T):
+            x_stage.copy_(xd[t])
+            tok()
+    step()                                            # validation pass, fills counters
+    torch.cuda.synchronize()
+    progress("  stacked validation pass done")
+    sts = [lay.state() for lay in layers]
+    assert all(s["error"] == 0 for s in sts), sts
+    cnts = [lay.counters() for lay in layers]
+    tot = {k: sum(c[k] for c in cnts) for k in cnts[0]}
+    rows_per_call = tot["ffn_rows"] / tot["ffn_calls"]
+    if hint:
+        for lay in layers:
+            lay.set_expected_rows(int(0.9 * rows_per_call))
+        tok = capture()
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) / steps * 1e3
+    res = {"T": T, "NL": NL, "ms_per_step": ms_per_step, "us_per_token_layer": ms_per_step * 1e3 / T / NL,
+           "rows_per_call": rows_per_call, "active_per_call": tot["ffn_active"] / tot["ffn_calls"],
+           "added_per_call": tot["added"] / tot["steps"], "window_len_end": sts[0]["window_len"],
+           "launch": "eager" if no_graph else "one hip-graph per token (all layers), x copied to a staging buffer",
+           "ffn": None, "kern": {}}
+    if profile:
+        # FFN alone on the cache states the stream ends in: every call reads another layer's rows, i.e. from HBM
+        x_last = xd[T - 1]
+
+        def rounds():
+            for _ in range(ffn_rounds):
+                for l, lay in enumerate(layers):
+                    lay.sparse_ffn(x_last, y_stage[l], w.batch)
+        if no_graph:
+            class _E:
+                replay = staticmethod(rounds)
+            g2 = _E()
+        else:
+            g2 = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g2):
+                rounds()
+        g2.replay()
+        torch.cuda.synchronize()
+        c0 = [lay.counters() for lay in layers]
+        ms = _timed_replays(g2, 5)
+        c1 = [lay.counters() for lay in layers]
+        calls = sum(b["ffn_calls"] - a["ffn_calls"] for a, b in zip(c0, c1))
+        res["ffn"] = {"us": ms * 1e3 / calls,
+                      "rows": sum(b["ffn_rows"] - a["ffn_rows"] for a, b in zip(c0, c1)) / calls,
+                      "active": sum(b["ffn_active"] - a["ffn_active"] for a, b in zip(c0, c1)) / calls}
+        layers[0].profile_begin(7 * T + 8)
+        for lay in layers:
+            lay.reset()
+        for t in range(T):
+            x_stage.copy_(xd[t])
+            token_all_layers()
+        for k, (ms, n) in layers[0].profile_collect().items():
+            if n:
+                res["kern"][k] = {"avg_us": ms / n * 1e3, "launches": n}
+    for lay in layers:
+        lay.close()
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -267,6 +514,8 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="launch every kernel from the host instead of a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true")
+    ap.add_argument("--no-c5", action="store_true",
+                    help="skip the stacked-layer leg (32 layers, 512 tokens) that the default C2 line carries as `c5`")
     ap.add_argument("--pmc-copy", action="store_true",
                     help="also run a plain 256 MiB device copy three times (calibration of rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--pmc-dir", default=None,
@@ -292,6 +541,7 @@ def main():
     if args.sweep == "rows":
         return sweep_rows(args)
 
+    import numpy as np
     import torch
     import workloads as wl
     import paper_2312_11514_amd as lif
@@ -311,195 +561,154 @@ def main():
     warmup = args.warmup if args.warmup is not None else (3 if NL == 1 else 1)
     mode = {"skip": lif.FFN_SKIP_DEAD, "full": lif.FFN_FULL_BUNDLE}[args.ffn_mode]
     reads_all = args.ffn_mode == "full"
+    E, d, G = w.elem_bytes, w.d_model, w.vectors_per_bundle
 
+    progress(f"building workload {w.name}")
     base = wl.make_layer(w, structured=args.structured, overpredict=args.overpredict)
     spec = w.spec_keep > 0
     X = wl.make_inputs(w) if (w.batch == 1 or spec) else wl.make_batch_inputs(w)
     if spec:
         # pass p verifies tokens [p * keep, p * keep + batch): the next pass starts after the accepted ones
-        import numpy as np
         n_pass = (len(X) - w.batch) // w.spec_keep + 1
         X = np.stack([X[p * w.spec_keep:p * w.spec_keep + w.batch] for p in range(n_pass)])
     T = len(X)
-    gpus = []
-    for l in range(NL):
-        Ll = wl.make_layer_variant(base, w, l)
-        gpus.append(GpuLayer(w, Ll, ffn_mode=mode))      # uploads A, B, c, b; pins the bundle store
-        del Ll
-    layers = [g.layer for g in gpus]
-    xd = gpus[0].upload_x(X)                              # [T, (batch,) d] resident in HBM
-    yd = torch.zeros((NL,) + tuple(xd.shape), dtype=xd.dtype, device=xd.device)
 
-    if NL == 1:
-        # whole token stream of the layer in one HIP graph
+    steady = ffn_states = ffn_cold = floor = breakdown = None
+    kern = {}
+    ffn = None
+    if NL > 1:
+        r = bench_stacked(w, base, mode, steps, warmup, no_graph=args.no_graph, hint=not args.no_hint,
+                          profile=not args.no_profile)
+        ms_per_step, us_per_token_layer = r["ms_per_step"], r["us_per_token_layer"]
+        rows_per_call, active_per_call, added_per_call = r["rows_per_call"], r["active_per_call"], r["added_per_call"]
+        window_len_end, launch, ffn, kern = r["window_len_end"], r["launch"], r["ffn"], r["kern"]
+        h2d_ref = None
+    else:
+        progress("uploading layer 0")
+        gpu0 = GpuLayer(w, base, ffn_mode=mode)               # uploads A, B, c, b; pins the bundle store
+        lay0 = gpu0.layer
+        xd = gpu0.upload_x(X)                                  # [T, (batch,) d] resident in HBM
+        yd = torch.zeros_like(xd)
+
+        def one_step(t, calls=False):
+            if spec:
+                lay0.step_tokens(xd[t], yd[t], w.batch, w.spec_keep)
+            elif calls:
+                lay0.step_calls(xd[t], yd[t], w.batch)
+            else:
+                lay0.step(xd[t], yd[t], w.batch)
+
         def run_stream(tokens=None):
-            lay0 = layers[0]
             lay0.reset()
             for t in range(T if tokens is None else tokens):
-                if spec:
-                    lay0.step_tokens(xd[t], yd[0, t], w.batch, w.spec_keep)
-                else:
-                    lay0.step(xd[t], yd[0, t], w.batch)
-        graph = None
-        run_stream()                                      # eager pass: validates the chain, fills counters
+                one_step(t)
+
+        # eager pass: validates the chain, fills the counters, and keeps the cache layout at 32 tokens spread over
+        # the steady part of the stream (the FFN alone is timed on those states afterwards)
+        snap_at = sorted(set(np.linspace(min(T - 1, 4 * w.window_k), T - 1, 32).astype(int).tolist()))
+        states = []
+        lay0.reset()
+        for t in range(T):
+            one_step(t)
+            if t in snap_at and not args.no_profile:
+                n = lay0.state()["num_used"]
+                states.append((t, lay0.pointers[:n].cpu().numpy().astype(np.int64)))
         torch.cuda.synchronize()
+        st0 = lay0.state()
+        assert st0["error"] == 0, st0
+        window_len_end = st0["window_len"]
+        tot = lay0.counters()
+        rows_per_call = tot["ffn_rows"] / tot["ffn_calls"]
+        active_per_call = tot["ffn_active"] / tot["ffn_calls"]
+        added_per_call = tot["added"] / tot["steps"]
+        hint = 0 if args.no_hint else int(0.9 * rows_per_call)   # launch geometry only: 90 % of the mean rows in use
+        lay0.set_expected_rows(hint)
+
+        progress("validation pass done; capturing and timing the token stream")
+        graph = None
         if not args.no_graph:
-            graph = torch.cuda.CUDAGraph()
+            graph = torch.cuda.CUDAGraph()                     # whole token stream of the layer in one HIP graph
             with torch.cuda.graph(graph):
                 run_stream()
         step = graph.replay if graph is not None else run_stream
         launch = "eager" if graph is None else "hip-graph of the whole token stream"
-    else:
-        # one HIP graph per token (all layers); x of the token is copied to a fixed staging buffer first
-        x_stage = torch.zeros_like(xd[0])
-        y_stage = torch.zeros((NL,) + tuple(xd[0].shape), dtype=xd.dtype, device=xd.device)
-
-        def token_all_layers():
-            for l, lay in enumerate(layers):
-                lay.step(x_stage, y_stage[l], w.batch)
-        for lay in layers:
-            lay.reset()
-        x_stage.copy_(xd[0])
-        token_all_layers()
-        torch.cuda.synchronize()
-        graph = None
-        if not args.no_graph:
-            graph = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(graph):
-                token_all_layers()
-        tok = graph.replay if graph is not None else token_all_layers
-
-        def step():
-            for lay in layers:
-                lay.reset()
-            for t in range(T):
-                x_stage.copy_(xd[t])
-                tok()
-        step()                                            # validation pass, fills counters
-        torch.cuda.synchronize()
-        launch = "eager" if graph is None else "one hip-graph per token (all layers), x copied to a staging buffer"
-
-    sts = [lay.state() for lay in layers]
-    assert all(s["error"] == 0 for s in sts), sts
-    window_len_end = sts[0]["window_len"]
-    cnts = [lay.counters() for lay in layers]
-    tot = {k: sum(c[k] for c in cnts) for k in cnts[0]}
-    rows_per_call = tot["ffn_rows"] / tot["ffn_calls"]
-    active_per_call = tot["ffn_active"] / tot["ffn_calls"]
-    added_per_call = tot["added"] / tot["steps"]
-
-    # row-count hint for the FFN launch geometry (performance only): 90 % of the mean rows in use
-    if not args.no_hint:
-        for lay in layers:
-            lay.set_expected_rows(int(0.9 * rows_per_call))
-        if graph is not None:                             # launch geometry changed: capture again
-            graph = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(graph):
-                (run_stream if NL == 1 else token_all_layers)()
-            if NL == 1:
-                step = graph.replay
-            else:
-                tok = graph.replay
-
-    for _ in range(warmup):
-        step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(steps):
-        step()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    ms_per_step = dt / steps * 1e3
-    us_per_token_layer = ms_per_step * 1e3 / T / NL
-
-    # steady state (single layer, graph launches): the first 2k steps fill the cache and load far more than the
-    # later ones; a second graph over just those steps is timed and subtracted
-    steady = None
-    Wm = 2 * w.window_k
-    if NL == 1 and graph is not None and T > 2 * Wm:
-        gw = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(gw):
-            run_stream(Wm)
-        gw.replay()
+        for _ in range(warmup):
+            step()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(steps):
+            step()
+        torch.cuda.synchronize()
+        ms_per_step = (time.perf_counter() - t0) / steps * 1e3
+        us_per_token_layer = ms_per_step * 1e3 / T
+
+        # steady state: the first 2k steps fill the cache and load far more than the later ones; a second graph over
+        # just those steps is timed and subtracted
+        Wm = 2 * w.window_k
+        if graph is not None and T > 2 * Wm:
+            gw = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(gw):
+                run_stream(Wm)
             gw.replay()
-        torch.cuda.synchronize()
-        warm_ms = (time.perf_counter() - t0) / steps * 1e3
-        steady = {"first_steps_excluded": Wm, "us_per_step": (ms_per_step - warm_ms) * 1e3 / (T - Wm),
-                  "us_per_step_in_the_first_steps": warm_ms * 1e3 / Wm}
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                gw.replay()
+            torch.cuda.synchronize()
+            warm_ms = (time.perf_counter() - t0) / steps * 1e3
+            steady = {"first_steps_excluded": Wm, "us_per_step": (ms_per_step - warm_ms) * 1e3 / (T - Wm),
+                      "us_per_step_in_the_first_steps": warm_ms * 1e3 / Wm}
 
-    # host link reference on the same box: one large pinned-to-device copy by the runtime (copy engine)
-    h2d_ref = None
-    if not args.no_profile:
-        src = torch.empty(256 * 1024 * 1024, dtype=torch.uint8).pin_memory()
-        dst = torch.empty(256 * 1024 * 1024, dtype=torch.uint8, device=xd.device)
-        dst.copy_(src, non_blocking=True)
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(3):
+        h2d_ref = None
+        if not args.no_profile:
+            # host link reference on the same box: one large pinned-to-device copy by the runtime (copy engine)
+            src = torch.empty(256 * 1024 * 1024, dtype=torch.uint8).pin_memory()
+            dst = torch.empty(256 * 1024 * 1024, dtype=torch.uint8, device=xd.device)
             dst.copy_(src, non_blocking=True)
-        e1.record()
-        torch.cuda.synchronize()
-        h2d_ref = 3 * src.numel() / (e0.elapsed_time(e1) * 1e-3) / 1e9
-        del src, dst
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(3):
+                dst.copy_(src, non_blocking=True)
+            e1.record()
+            torch.cuda.synchronize()
+            h2d_ref = 3 * src.numel() / (e0.elapsed_time(e1) * 1e-3) / 1e9
+            del src, dst
 
-    # FFN alone, on the cache state the stream ends in: R rounds of lif_sparse_ffn over all layers in a HIP graph,
-    # timed with HIP events on the launch stream; the byte count comes from the device counters of those calls.
-    # With one layer the rows stay warm in the 256 MB Infinity Cache; with 32 layers each call reads its rows from HBM.
-    ffn = None
-    if not args.no_profile:
-        R = 200 if NL == 1 else 8
-        x_last = xd[T - 1]
-        def ffn_rounds():
-            for _ in range(R):
-                for l, lay in enumerate(layers):
-                    lay.sparse_ffn(x_last, yd[l, T - 1], w.batch)
-        if args.no_graph:
-            class _Eager:
-                replay = staticmethod(ffn_rounds)
-            g2 = _Eager()
-        else:
-            g2 = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(g2):
-                ffn_rounds()
-        g2.replay()
-        torch.cuda.synchronize()
-        c0 = [lay.counters() for lay in layers]
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        reps = 5
-        e0.record()
-        for _ in range(reps):
-            g2.replay()
-        e1.record()
-        torch.cuda.synchronize()
-        c1 = [lay.counters() for lay in layers]
-        calls = sum(b["ffn_calls"] - a["ffn_calls"] for a, b in zip(c0, c1))
-        assert calls == R * reps * NL
-        rows = sum(b["ffn_rows"] - a["ffn_rows"] for a, b in zip(c0, c1)) / calls
-        act = sum(b["ffn_active"] - a["ffn_active"] for a, b in zip(c0, c1)) / calls
-        ffn = {"us": e0.elapsed_time(e1) * 1e3 / calls, "rows": rows, "active": act}
+            progress("timed; FFN alone over the kept cache states")
+            # FFN alone over the (cache state, x) pairs kept above: warm (one state per graph) and HBM-cold
+            ffn_states, ffn_cold = ffn_over_states(w, gpu0, base, states, xd, mode, hint, args.no_graph)
+            mean_bytes = float(np.mean([f["algorithmic_bytes_per_launch"] for f in ffn_states]))
+            mean_nominal = float(np.mean([f["nominal_bundle_bytes"] for f in ffn_states]))
+            progress("read floor of the box")
+            floor = read_floor(xd.device, [("empty_launch", 0), ("ffn_algorithmic_bytes", mean_bytes),
+                                           ("ffn_nominal_bundle_bytes", mean_nominal), ("256MiB", 256 << 20),
+                                           ("1GiB", 1 << 30)])
 
-    # per-kernel durations over one more eager pass (layer 0 only is instrumented): HIP events recorded by the
-    # library on the launch stream around every kernel (these include ~2 us of event/dispatch overhead per launch)
-    kern = {}
-    if not args.no_profile:
-        layers[0].profile_begin(7 * T + 8)
-        if NL == 1:
-            run_stream()
-        else:
-            for lay in layers:
-                lay.reset()
-            for t in range(T):
-                x_stage.copy_(xd[t])
-                token_all_layers()
-        for k, (ms, n) in layers[0].profile_collect().items():
-            if n:
-                kern[k] = {"avg_us": ms / n * 1e3, "launches": n}
+            # per-kernel durations over two more eager passes: HIP events recorded by the library on the launch
+            # stream around every kernel (these include ~2 us of event/dispatch overhead per launch); first the
+            # lif_step path that `value` times, then the four separate calls for the paper's three cost columns
+            progress("event-timed passes")
+            for calls in (False, True):
+                lay0.profile_begin(7 * T + 8)
+                lay0.reset()
+                for t in range(T):
+                    one_step(t, calls=calls)
+                got = {k: {"avg_us": ms / n * 1e3, "launches": n}
+                       for k, (ms, n) in lay0.profile_collect().items() if n}
+                if not calls:
+                    kern = got
+                elif not spec:
+                    per_tok = {k: v["avg_us"] * v["launches"] / T for k, v in got.items()}
+                    breakdown = {"io": per_tok.get("load", 0.0), "mem": per_tok.get("window", 0.0),
+                                 "compute": sum(per_tok.get(k, 0.0) for k in ("predict_xa", "predict_mask", "ffn_up",
+                                                                              "ffn_down")),
+                                 "path": "four separate calls, event-timed per kernel (about 2 us of event overhead "
+                                         "in each figure), microseconds per token",
+                                 "definition": "io = bundle gather from pinned host memory (the row moves of the "
+                                               "deletion ride in the same kernel, hidden behind the host reads); "
+                                               "mem = window update and deletion plan; compute = predictor + FFN"}
 
-    E, d, G = w.elem_bytes, w.d_model, w.vectors_per_bundle
     nominal = rows_per_call * G * d * E
     out = {
         "metric": "sparse-FFN us/token/layer (whole hot path: predict + window + load + FFN)",
@@ -522,20 +731,37 @@ def main():
         "end_to_end_us_per_token": us_per_token_layer * NL,
         "h2d_bytes_per_token": added_per_call * w.bundle_bytes * NL,
     }
-    if ffn:
+    kernel_name = "ffn_up + ffn_down (one lif_sparse_ffn call)"
+    if ffn_states:
+        us = [f["avg_launch_us"] for f in ffn_states]
+        tot_b = sum(f["algorithmic_bytes_per_launch"] for f in ffn_states)
+        tot_n = sum(f["nominal_bundle_bytes"] for f in ffn_states)
+        mean = {"avg_launch_us": float(np.mean(us)), "rows": float(np.mean([f["rows"] for f in ffn_states])),
+                "rows_active": float(np.mean([f["rows_active"] for f in ffn_states])),
+                "algorithmic_bytes_per_launch": tot_b / len(us), "achieved": tot_b / sum(us) / 1e3,
+                "nominal_bundle_bytes": tot_n / len(us), "nominal_GBs": tot_n / sum(us) / 1e3}
+        out["roofline"] = roofline_object(mean, kernel_name, {
+            "memory": "warm: one cache state per graph of 50 calls, the rows stay in the 256 MB Infinity Cache",
+            "states": {"count": len(us), "tokens": [t for t, _ in states[:16]],
+                       "us_min": min(us), "us_max": max(us),
+                       "rows_active_min": min(f["rows_active"] for f in ffn_states),
+                       "rows_active_max": max(f["rows_active"] for f in ffn_states),
+                       "frac_min": min(f["achieved"] for f in ffn_states) / HBM_PEAK_GBS,
+                       "frac_max": max(f["achieved"] for f in ffn_states) / HBM_PEAK_GBS},
+            "floor": floor})
+        out["roofline_cold"] = roofline_object(ffn_cold, kernel_name, {
+            "memory": f"HBM: {ffn_cold['caches']} caches of this layer ({ffn_cold['bytes_cycled'] / 1e6:.0f} MB of "
+                      "bundles) called in turn, so no call finds its rows in the Infinity Cache"})
+    elif ffn:
         up_bytes = ffn["rows"] * (G - 1) * d * E
         down_bytes = (ffn["rows"] if reads_all else ffn["active"]) * d * E
-        touched = up_bytes + down_bytes
         nominal_f = ffn["rows"] * G * d * E
-        ach = touched / (ffn["us"] * 1e-6) / 1e9
-        out["roofline"] = {"bound": "hbm", "kernel": "ffn_up + ffn_down (one lif_sparse_ffn call)",
-                           "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
-                           "traffic": None, "algorithmic_bytes_per_launch": touched, "avg_launch_us": ffn["us"],
-                           "rows": ffn["rows"], "rows_active": ffn["active"],
-                           "nominal_bundle_bytes": nominal_f,
-                           "nominal_GBs": nominal_f / (ffn["us"] * 1e-6) / 1e9,
-                           "nominal_frac": nominal_f / (ffn["us"] * 1e-6) / 1e9 / HBM_PEAK_GBS}
-    if ffn and args.pmc_dir:
+        f = {"avg_launch_us": ffn["us"], "rows": ffn["rows"], "rows_active": ffn["active"],
+             "algorithmic_bytes_per_launch": up_bytes + down_bytes,
+             "achieved": (up_bytes + down_bytes) / ffn["us"] / 1e3,
+             "nominal_bundle_bytes": nominal_f, "nominal_GBs": nominal_f / ffn["us"] / 1e3}
+        out["roofline"] = roofline_object(f, kernel_name, {"memory": "HBM: every call reads another layer's rows"})
+    if "roofline" in out and args.pmc_dir:
         tr = pmc_traffic(args.pmc_dir)
         if tr:
             out["roofline"]["traffic"] = tr["FETCH_SIZE"]["bytes_per_call"] + tr["WRITE_SIZE"]["bytes_per_call"]
@@ -544,8 +770,24 @@ def main():
         out["h2d"] = {"GBs_in_load_kernel": added_per_call * w.bundle_bytes / (kern["load"]["avg_us"] * 1e-6) / 1e9,
                       "GBs_large_pinned_memcpy_same_box": h2d_ref}
         out["kernels_avg_us_event_timed"] = {k: round(v["avg_us"], 3) for k, v in kern.items()}
+    if breakdown:
+        out["breakdown_us"] = breakdown
+    if NL == 1:
+        del gpu0, lay0
+    if args.workload == "C2" and not args.no_c5 and not args.structured and args.overpredict == 1.0:
+        # configuration 5 (32 stacked layers of this shape, 512 tokens, own pinned store per layer): one timed pass
+        w5 = wl.WORKLOADS["C5"]
+        progress("stacked-layer leg (C5)")
+        r5 = bench_stacked(w5, base, mode, 1, 0, no_graph=args.no_graph, hint=not args.no_hint, profile=False)
+        out["c5"] = {"workload": describe(w5), "launch": r5["launch"], "timed_passes": 1,
+                     "end_to_end_us_per_token": r5["us_per_token_layer"] * r5["NL"],
+                     "us_per_token_per_layer": r5["us_per_token_layer"],
+                     "h2d_bytes_per_token": r5["added_per_call"] * w5.bundle_bytes * r5["NL"],
+                     "rows_in_cache_per_layer": r5["rows_per_call"]}
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w, base, X)
+        progress("oracle on the host cores")
+        out["cpu_baseline"] = cpu_baseline(w, base, X, budget_s=15.0)
+    progress("done")
     print(json.dumps(out))
 
 

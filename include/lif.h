@@ -305,6 +305,14 @@ int lif_get_counters(lif_layer* layer, lif_counters* out, void* stream);
 int lif_profile_begin(lif_layer* layer, int32_t max_launches);
 int lif_profile_collect(lif_layer* layer, double* ms, int64_t* launches, void* stream);
 
+/*
+ * Bandwidth reference of the box, for the roofline figures of a benchmark (not part of the method): one launch of a
+ * plain streaming-read kernel over [src_dev, src_dev + bytes) (16-byte loads, every byte read once, nothing
+ * written unless the folded words hit one magic value: sink_dev, 4 bytes of device memory, is then written).
+ * bytes = 0 launches an empty kernel (the launch floor).  src_dev 16-byte aligned, bytes a multiple of 16.
+ */
+int lif_profile_read(const void* src_dev, size_t bytes, void* sink_dev, void* stream);
+
 /* Message of the last LIF_HIP_ERROR / LIF_INVALID_ARG on the calling thread. */
 const char* lif_last_error_string(void);
 

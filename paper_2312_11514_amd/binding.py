@@ -63,6 +63,7 @@ EXPORTS = {
     "lif_set_expected_rows": (C.c_int, [C.c_void_p, C.c_int32]),
     "lif_get_state": (C.c_int, [C.c_void_p, C.POINTER(LifState), C.c_void_p]),
     "lif_get_counters": (C.c_int, [C.c_void_p, C.POINTER(LifCounters), C.c_void_p]),
+    "lif_profile_read": (C.c_int, [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]),
     "lif_profile_begin": (C.c_int, [C.c_void_p, C.c_int32]),
     "lif_profile_collect": (C.c_int, [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.c_void_p]),
 }
@@ -104,6 +105,11 @@ def _ptr(t):
 def _stream():
     import torch
     return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def profile_read(src, nbytes, sink):
+    """lif_profile_read: one plain streaming read of the first nbytes bytes of the device tensor src."""
+    _check(load_library().lif_profile_read(_ptr(src), int(nbytes), _ptr(sink), _stream()))
 
 
 class Layer:

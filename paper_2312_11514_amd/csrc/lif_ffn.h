@@ -318,15 +318,29 @@ __global__ __launch_bounds__(256) void k_ffn_down(const T* __restrict__ matrix, 
             }
             __syncthreads();
             if (col_ok) {
-#pragma unroll 4
-                for (int i = rg; i < cnt; i += RG) {
-                    const int s = list[i];
-                    const V v = *reinterpret_cast<const V*>(base + (size_t)s * row_elems);
+                // all row loads of a pass over kInFlight rows per thread are issued before the first use (a loop with a
+                // run-time trip count would wait for every load in turn); the adds stay in ascending row order
+                constexpr int kInFlight = (BT == 1) ? 8 : 4;
+                for (int i0 = rg; i0 < cnt; i0 += RG * kInFlight) {
+                    V v[kInFlight];
 #pragma unroll
-                    for (int b = 0; b < BT; ++b) {
-                        const float hb = hv[b][i];
+                    for (int u = 0; u < kInFlight; ++u) {
+                        const int i = i0 + u * RG;
+                        const int s = list[i < cnt ? i : i0];
+                        v[u] = (i < cnt) ? *reinterpret_cast<const V*>(base + (size_t)s * row_elems) : V(0);
+                    }
 #pragma unroll
-                        for (int e = 0; e < VE; ++e) acc[b * VE + e] = __builtin_fmaf(hb, (float)v[e], acc[b * VE + e]);
+                    for (int u = 0; u < kInFlight; ++u) {
+                        const int i = i0 + u * RG;
+                        if (i < cnt) {
+#pragma unroll
+                            for (int b = 0; b < BT; ++b) {
+                                const float hb = hv[b][i];
+#pragma unroll
+                                for (int e = 0; e < VE; ++e)
+                                    acc[b * VE + e] = __builtin_fmaf(hb, (float)v[u][e], acc[b * VE + e]);
+                            }
+                        }
                     }
                 }
             }

@@ -17,22 +17,31 @@ def require_gpu():
 
 
 class GpuLayer:
-    def __init__(self, w, L, ffn_mode=lif.FFN_SKIP_DEAD, capacity=None, max_batch=None, use_c=True, shrink=False):
+    def __init__(self, w, L, ffn_mode=lif.FFN_SKIP_DEAD, capacity=None, max_batch=None, use_c=True, shrink=False,
+                 share=None):
+        """share: another GpuLayer of the same workload and layer data whose predictor arrays and pinned bundle
+        store this one reuses (its own cache, window state and workspace): several caches of one layer."""
         require_gpu()
         dev = torch.device("cuda:0")
         self.w, self.dev = w, dev
         self.tdtype = torch.float32 if w.dtype == "f32" else torch.float16
         up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
-        self.host = torch.from_numpy(L.bundles).pin_memory()
         gate = w.gate_resident
+        if share is not None:
+            sl = share.layer
+            self.host, A, B, c, b = share.host, sl.A, sl.B, sl.c, sl.b
+        else:
+            self.host = torch.from_numpy(L.bundles).pin_memory()
+            A = up(L.w_gate if gate else L.A.T)      # the ABI takes the contraction dimension contiguous: [rank, d_model]
+            B = None if gate else up(L.B)
+            c = up(L.c) if (use_c and not gate) else None
+            b = up(L.b)
         self.layer = lif.Layer(
             d_model=w.d_model, d_ffn=w.d_ffn, rank=w.rank, window_k=w.window_k,
             capacity_rows=capacity or w.capacity_rows, max_batch=max_batch or w.batch,
             glu=(w.glu and not gate), dtype=w.dtype, ffn_mode=ffn_mode, shrink_window=(shrink or w.shrink),
             predictor=lif.PRED_GATE if gate else lif.PRED_LOWRANK, threshold=L.theta,
-            A=up(L.w_gate if gate else L.A.T),       # the ABI takes the contraction dimension contiguous: [rank, d_model]
-            B=None if gate else up(L.B),
-            c=up(L.c) if (use_c and not gate) else None, b=up(L.b), host_bundles=self.host)
+            A=A, B=B, c=c, b=b, host_bundles=self.host)
         self.y = torch.zeros((max_batch or w.batch, w.d_model), dtype=self.tdtype, device=dev)
 
     def upload_x(self, x):
