@@ -263,11 +263,12 @@ def gate_predict_mask(x, w_gate, b, theta):
 def sparse_ffn_resident_gate(cache: NeuronCache, gate_act, x, d_model: int):
     """FFN over the cached rows when bundles hold up row | down column and the gate activation
     relu(gate_i . x + b_i) comes from the resident gate projection (indexed by original neuron id):
-    y = sum_s gate_act[pointers[s]] * (up_s . x) * down_s."""
+    y = sum_s gate_act[pointers[s]] * (up_s . x) * down_s.  x [d] with gate_act [F], or a batch of tokens
+    x [batch, d] with gate_act [batch, F] (one row of y per token, all over the same cached rows)."""
     n = cache.num_used
     m = cache.matrix[:n].astype(np.float64)
     up, down = m[:, :d_model], m[:, d_model:2 * d_model]
-    h = np.asarray(gate_act, np.float64)[cache.pointers[:n]] * (up @ np.asarray(x, np.float64))
+    h = np.asarray(gate_act, np.float64)[..., cache.pointers[:n]] * (np.asarray(x, np.float64) @ up.T)
     return h @ down
 
 

@@ -60,8 +60,12 @@ MUTATIONS = [
     ("pass of tokens: transient masks forgotten", "        for i in range(len(masks)):                    # also one that enters and leaves the window at once\n            transient |= masks[i]",
      "        for i in range(keep, keep):\n            transient |= masks[i]",
      "test_layer_pass_of_tokens_equals_the_dense_ffn_restricted_to_the_held_set", ()),
-    ("gate ffn: activation looked up by slot", "np.asarray(gate_act, np.float64)[cache.pointers[:n]]",
-     "np.asarray(gate_act, np.float64)[:n]", "test_gate_predictor_reproduces_the_dense_gated_ffn", ()),
+    ("gate ffn, batch: every token takes the first token's gate activations",
+     "np.asarray(gate_act, np.float64)[..., cache.pointers[:n]]",
+     "np.atleast_2d(np.asarray(gate_act, np.float64))[0, cache.pointers[:n]]",
+     "test_gate_predictor_batch_rows_equal_single_token_evaluation", ()),
+    ("gate ffn: activation looked up by slot", "np.asarray(gate_act, np.float64)[..., cache.pointers[:n]]",
+     "np.asarray(gate_act, np.float64)[..., :n]", "test_gate_predictor_reproduces_the_dense_gated_ffn", ()),
 ]
 
 

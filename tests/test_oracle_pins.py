@@ -547,6 +547,36 @@ def test_gate_predictor_reproduces_the_dense_gated_ffn():
         assert r["loaded"] == len(r["added"]) * w.bundle_bytes
 
 
+def test_gate_predictor_batch_rows_equal_single_token_evaluation():
+    """Several tokens per step with the resident gate as predictor: every token has its own gate activations, the
+    step mask is the OR of the per-token masks, and row t of y is the dense gated FFN of token t (exact predictor:
+    cached neurons that do not fire for token t contribute exactly zero), also in a pass of tokens of which only
+    some stay in the window (Section 4.3)."""
+    w = wl.scaled(wl.WORKLOADS["C1"], name="gateb", d_model=48, d_ffn=160, rank=8, window_k=3, p_active=0.1,
+                  glu=True, gate_resident=True, tokens=12, batch=3, capacity_rows=160)
+    L = wl.make_layer(w)
+    X = wl.make_batch_inputs(w)                                   # [T, 3, d]
+    mk = lambda: O.OracleLayer(w.d_model, w.d_ffn, w.window_k, w.capacity_rows, False, None, None, None, 0.0, L.b,
+                               L.bundles, w_gate=L.w_gate)
+    lay = mk()
+    for xb in X[:6]:
+        r = lay.step(xb)
+        assert r["masks"].shape == (3, w.d_ffn) and r["y"].shape == (3, w.d_model)
+        held = lay.window.active_set()
+        for t in range(3):
+            m1, _, act1 = O.gate_predict_mask(xb[t], L.w_gate, L.b, 0.0)
+            assert (r["masks"][t] == m1).all() and (m1 <= held).all()
+            np.testing.assert_allclose(lay.gate_act[t], act1, rtol=1e-12, atol=1e-14)   # matrix and vector products round apart
+            dense = O.dense_ffn(L.w_up, L.w_down, L.b, xb[t], w_gate=L.w_gate)
+            np.testing.assert_allclose(r["y"][t], dense, rtol=1e-11, atol=1e-13)
+    lay = mk()
+    for xb, keep in zip(X[6:], (3, 1, 0, 2, 3, 0)):
+        r = lay.step_tokens(xb, keep)
+        for t in range(3):
+            dense = O.dense_ffn(L.w_up, L.w_down, L.b, xb[t], w_gate=L.w_gate)
+            np.testing.assert_allclose(r["y"][t], dense, rtol=1e-11, atol=1e-13)
+
+
 def test_layer_pass_of_tokens_equals_the_dense_ffn_restricted_to_the_held_set():
     """OracleLayer.step_tokens (Section 4.3): every token of a pass is computed over the same held set (kept
     window masks and all masks of the pass), so row i of y is the dense FFN restricted to that set; a pass of one
