@@ -60,7 +60,8 @@ enum lif_predictor {
     LIF_PRED_LOWRANK = 0,  /* low-rank predictor (x A) B + c > theta (Section 3.1, Fig. 3b)               */
     LIF_PRED_GATE = 1      /* the resident gate projection itself (Appendix, Llama 2, "Alternative         */
                            /* approaches"): mask_i = gate_i . x + b_i > theta, exact; bundles = up | down; */
-                           /* y = sum_s relu(gate . x + b)_s * (up_s . x) * down_s; batch 1, glu = 0        */
+                           /* y_t = sum_s relu(gate . x_t + b)_s * (up_s . x_t) * down_s; glu = 0; batches */
+                           /* and passes of several tokens as with the low-rank predictor                  */
 };
 
 typedef struct lif_config {

@@ -64,8 +64,8 @@ bool config_ok(const lif_config* c, const char** why) {
     if (c->glu != 0 && c->glu != 1) return (*why = "glu", false);
     if (c->shrink_window != 0 && c->shrink_window != 1) return (*why = "shrink_window", false);
     if (c->predictor != LIF_PRED_LOWRANK && c->predictor != LIF_PRED_GATE) return (*why = "predictor", false);
-    if (c->predictor == LIF_PRED_GATE && (c->glu || c->max_batch != 1))
-        return (*why = "the gate predictor takes plain (up | down) bundles and batch 1", false);
+    if (c->predictor == LIF_PRED_GATE && c->glu)
+        return (*why = "the gate predictor takes plain (up | down) bundles", false);
     if (c->ffn_mode != LIF_FFN_SKIP_DEAD && c->ffn_mode != LIF_FFN_FULL_BUNDLE) return (*why = "ffn_mode", false);
     if ((size_t)c->max_batch * c->d_model * elem_bytes(*c) > 64 * 1024) return (*why = "max_batch * d_model exceeds the 64 KiB LDS staging area", false);
     return true;
@@ -93,8 +93,8 @@ Layout make_layout(const lif_config& c) {
     off = align_up(off + sizeof(float) * c.capacity_rows, 256);
     L.stamp = off;                     // step number at which h_new[slot] was written
     off = align_up(off + sizeof(int32_t) * c.capacity_rows, 256);
-    L.gact = off;                      // gate predictor: relu(gate_i . x + b_i) per original neuron
-    off = align_up(off + (c.predictor == LIF_PRED_GATE ? sizeof(float) * c.d_ffn : 0), 256);
+    L.gact = off;                      // gate predictor: relu(gate_i . x_t + b_i) per token and original neuron
+    off = align_up(off + (c.predictor == LIF_PRED_GATE ? sizeof(float) * c.max_batch * c.d_ffn : 0), 256);
     L.total = off;
     return L;
 }
@@ -180,15 +180,18 @@ int launch_predict(lif_layer* L, const void* x, int batch, uint8_t* masks, uint8
 }
 
 template <typename T>
-void launch_predict_gate(lif_layer* L, const void* x, uint8_t* masks, uint8_t* step_mask, hipStream_t s) {
+void launch_predict_gate(lif_layer* L, const void* x, int batch, uint8_t* masks, uint8_t* step_mask, hipStream_t s) {
     const lif_config& c = L->cfg;
     const int nvec = c.d_model / Vec<T>::N;
     const int ni = (nvec + 63) / 64;
     const int grid = std::min((c.d_ffn / 8 + 3) / 4, 2048);
+    const size_t shm = batch == 1 ? 0 : (size_t)batch * c.d_model * sizeof(T);
     Timed t(L, LIF_K_PREDICT_MASK, s);
-#define LIF_PG(NI)                                                                                           \
-    hipLaunchKernelGGL((k_predict_gate<T, NI>), dim3(grid), dim3(256), 0, s, (const T*)L->buf.A, L->buf.b,       \
-                       (const T*)x, c.d_model, c.d_ffn, c.threshold, masks, step_mask, L->gact, L->st)
+#define LIF_PG_X(NI, XREG)                                                                                   \
+    hipLaunchKernelGGL((k_predict_gate<T, NI, XREG>), dim3(grid), dim3(256), shm, s, (const T*)L->buf.A,         \
+                       L->buf.b, (const T*)x, c.d_model, c.d_ffn, batch, c.threshold, masks, step_mask, L->gact, \
+                       L->st)
+#define LIF_PG(NI) do { if (batch == 1) LIF_PG_X(NI, true); else LIF_PG_X(NI, false); } while (0)
     if (ni <= 1) LIF_PG(1);
     else if (ni <= 2) LIF_PG(2);
     else if (ni <= 4) LIF_PG(4);
@@ -197,6 +200,7 @@ void launch_predict_gate(lif_layer* L, const void* x, uint8_t* masks, uint8_t* s
     else if (ni <= 12) LIF_PG(12);
     else LIF_PG(16);
 #undef LIF_PG
+#undef LIF_PG_X
 }
 
 // `h` (activations) and `ypart` (partial outputs) of the FFN launches: the workspace arrays of the layer, or the
@@ -305,11 +309,11 @@ void launch_ffn_up_mfma(lif_layer* L, const void* x, int batch, float* h, hipStr
     if (c.glu)
         hipLaunchKernelGGL((k_ffn_up_mfma<true, MODE, W>), dim3(grid), dim3(W * 64), 0, s,
                            (const _Float16*)L->buf.matrix, L->buf.bias, (const _Float16*)x, h, c.d_model, batch,
-                           c.capacity_rows, L->row_elems, L->move_dst, L->st);
+                           c.capacity_rows, L->row_elems, L->move_dst, L->buf.pointers, L->gact, c.d_ffn, L->st);
     else
         hipLaunchKernelGGL((k_ffn_up_mfma<false, MODE, W>), dim3(grid), dim3(W * 64), 0, s,
                            (const _Float16*)L->buf.matrix, L->buf.bias, (const _Float16*)x, h, c.d_model, batch,
-                           c.capacity_rows, L->row_elems, L->move_dst, L->st);
+                           c.capacity_rows, L->row_elems, L->move_dst, L->buf.pointers, L->gact, c.d_ffn, L->st);
 }
 
 // batch > 1, fp16: bundle load next to the activation stage of the surviving rows, then the rows the load wrote
@@ -320,11 +324,13 @@ void launch_load_up_mfma(lif_layer* L, const void* x, int batch, const int32_t* 
     if (c.glu)
         hipLaunchKernelGGL((k_load_up_mfma<true>), dim3(kLoadGrid + tiles), dim3(256), 0, s, (_Float16*)L->buf.matrix,
                            L->buf.pointers, L->buf.bias, L->host_alias, L->buf.b, added, L->move_dst, L->row_bytes,
-                           c.d_ffn, (const _Float16*)x, L->h, c.d_model, batch, c.capacity_rows, kLoadGrid, L->st);
+                           c.d_ffn, (const _Float16*)x, L->h, c.d_model, batch, c.capacity_rows, kLoadGrid, L->gact,
+                           L->st);
     else
         hipLaunchKernelGGL((k_load_up_mfma<false>), dim3(kLoadGrid + tiles), dim3(256), 0, s, (_Float16*)L->buf.matrix,
                            L->buf.pointers, L->buf.bias, L->host_alias, L->buf.b, added, L->move_dst, L->row_bytes,
-                           c.d_ffn, (const _Float16*)x, L->h, c.d_model, batch, c.capacity_rows, kLoadGrid, L->st);
+                           c.d_ffn, (const _Float16*)x, L->h, c.d_model, batch, c.capacity_rows, kLoadGrid, L->gact,
+                           L->st);
 }
 
 // LDS a workgroup of k_predict_mask<T, BT> needs for a predictor of rank r: its static arrays plus BT * r doubles.
@@ -500,8 +506,8 @@ int lif_predict(lif_layer* L, const void* x_dev, int32_t batch, uint8_t* masks_d
     if (rc) return rc;
     hipStream_t s = (hipStream_t)stream;
     if (L->cfg.predictor == LIF_PRED_GATE) {
-        if (L->cfg.dtype == LIF_F32) launch_predict_gate<float>(L, x_dev, masks_dev, step_mask_dev, s);
-        else launch_predict_gate<_Float16>(L, x_dev, masks_dev, step_mask_dev, s);
+        if (L->cfg.dtype == LIF_F32) launch_predict_gate<float>(L, x_dev, batch, masks_dev, step_mask_dev, s);
+        else launch_predict_gate<_Float16>(L, x_dev, batch, masks_dev, step_mask_dev, s);
     } else if (L->cfg.dtype == LIF_F32) {
         launch_predict<float>(L, x_dev, batch, masks_dev, step_mask_dev, s);
     } else {

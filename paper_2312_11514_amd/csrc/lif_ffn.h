@@ -31,7 +31,8 @@ namespace lif {
 // address of the number of rows to cover (num_used, or the rows kept by a pending deletion).
 // `gact` (may be null, plain bundles only): per-neuron gate activations relu(gate_i . x + b_i) written by the
 // gate predictor (Appendix, Llama 2, "Alternative approaches": the resident gate projection is the predictor);
-// the activation of slot s is then gact[pointers[s]] * (up_s . x).  gact_n = d_ffn bounds the lookup.
+// the activation of slot s for token t is then gact[t][pointers[s]] * (up_s . x_t), gact [batch x gact_n];
+// gact_n = d_ffn bounds the lookup.
 template <typename T, int NI, bool GLU, bool XREG>
 __device__ __forceinline__ void ffn_up_role(const T* __restrict__ matrix, const float* __restrict__ bias,
                                             const T* __restrict__ x, float* __restrict__ h, int d, int batch,
@@ -73,7 +74,7 @@ __device__ __forceinline__ void ffn_up_role(const T* __restrict__ matrix, const 
                 u[it] = in ? row[idx] : V(0);
             }
         }
-        if (ok) bs = gact ? gact[min(max(pointers[gw], 0), gact_n - 1)] : bias[gw];
+        if (ok) bs = gact ? gact[min(max(pointers[gw], 0), gact_n - 1)] : bias[gw];     // token 0 (the only one if XREG)
     }
     const int err = st->error;
     const int n = *n_ptr;
@@ -140,7 +141,10 @@ __device__ __forceinline__ void ffn_up_role(const T* __restrict__ matrix, const 
                 dg = wave_sum(dg);
                 act = fmaxf(dg + bs, 0.f) * du;
             } else if (gact) {
-                act = bs * du;                        // resident gate: bs = relu(gate . x + bias) from the predictor
+                // resident gate: relu(gate . x_b + bias) from the predictor (bs holds token 0's)
+                const float gb = (XREG || b == 0) ? bs
+                                                  : gact[(size_t)b * gact_n + min(max(pointers[s], 0), gact_n - 1)];
+                act = gb * du;
             } else {
                 act = fmaxf(du + bs, 0.f);
             }

@@ -38,12 +38,15 @@ enum MfmaRows {
 // kRowsAll / kRowsKept; for kRowsChanged it is move_dst[e] for e < n_removed (-1 = tail slot that was not
 // moved: skipped) and slot n_base + (e - n_removed) for the n_added entries after that.
 // Returns false (for the whole workgroup) when the tile lies past the end of the list.
+// `gact` (may be null; plain bundles only): gate activations relu(gate_i . x_t + b_i) per token and neuron,
+// [batch x gact_n], written by the gate predictor; the activation of a row is then gact[t][pointers[row]] * (up . x_t).
 template <bool GLU, int MODE, int WAVES>
 __device__ __forceinline__ bool ffn_up_mfma_tile(const _Float16* __restrict__ matrix, const float* __restrict__ bias,
                                                  const _Float16* __restrict__ x, float* __restrict__ h, int d,
                                                  int batch, int capacity, size_t row_elems,
                                                  const int32_t* __restrict__ move_dst, int tile,
-                                                 const DevState* __restrict__ st) {
+                                                 const int32_t* __restrict__ pointers, const float* __restrict__ gact,
+                                                 int gact_n, const DevState* __restrict__ st) {
     __shared__ float red[GLU ? 2 : 1][kMfmaParts][64][4];
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int i = lane & 15, q = lane >> 4;
@@ -69,7 +72,11 @@ __device__ __forceinline__ bool ffn_up_mfma_tile(const _Float16* __restrict__ ma
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
         orow[r] = __shfl(srow, 4 * q + r, kWave);                 // lane j < 16 holds the slot of tile row j
-        obias[r] = (w == 0 && orow[r] >= 0) ? bias[orow[r]] : 0.f;
+        obias[r] = 0.f;
+        if (w == 0 && orow[r] >= 0) {
+            if (GLU || !gact) obias[r] = bias[orow[r]];
+            else if (i < batch) obias[r] = gact[(size_t)i * gact_n + min(max(pointers[orow[r]], 0), gact_n - 1)];
+        }
     }
     const _Float16* grow = matrix + (size_t)min(max(srow, 0), capacity - 1) * row_elems;   // masked rows read slot 0
     const _Float16* urow = grow + (GLU ? d : 0);
@@ -126,6 +133,8 @@ __device__ __forceinline__ bool ffn_up_mfma_tile(const _Float16* __restrict__ ma
 #pragma unroll
                     for (int ww = 0; ww < kMfmaParts; ++ww) sg += red[GLU ? 1 : 0][ww][lane][r];
                     act = fmaxf(sg + bs, 0.f) * su;
+                } else if (gact) {
+                    act = bs * su;                    // bs = this token's gate activation of the row's neuron
                 } else {
                     act = fmaxf(su + bs, 0.f);
                 }
@@ -142,10 +151,13 @@ __global__ __launch_bounds__(WAVES * 64) void k_ffn_up_mfma(const _Float16* __re
                                                                  const _Float16* __restrict__ x, float* __restrict__ h,
                                                                  int d, int batch, int capacity, size_t row_elems,
                                                                  const int32_t* __restrict__ move_dst,
+                                                                 const int32_t* __restrict__ pointers,
+                                                                 const float* __restrict__ gact, int gact_n,
                                                                  const DevState* __restrict__ st) {
     // grid-stride over tiles (the grid may be smaller than the tile count; LDS is reused between tiles)
     for (int tile = blockIdx.x;; tile += gridDim.x) {
-        if (!ffn_up_mfma_tile<GLU, MODE, WAVES>(matrix, bias, x, h, d, batch, capacity, row_elems, move_dst, tile, st))
+        if (!ffn_up_mfma_tile<GLU, MODE, WAVES>(matrix, bias, x, h, d, batch, capacity, row_elems, move_dst, tile,
+                                                pointers, gact, gact_n, st))
             break;
         __syncthreads();
     }

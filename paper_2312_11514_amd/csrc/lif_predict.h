@@ -16,6 +16,20 @@
 
 namespace lif {
 
+// acc + sum_q a[q] * b[q] with every product and sum in fp64.  A product of two fp16 values is exact in fp32
+// (22 significant bits, exponents far inside the fp32 range), so for fp16 it is formed there and widened once:
+// the same bits as widening both factors, at half the conversions.
+__device__ __forceinline__ double dot_f64(f16x8 a, f16x8 b, double acc) {
+#pragma unroll
+    for (int q = 0; q < 8; ++q) acc += (double)((float)a[q] * (float)b[q]);
+    return acc;
+}
+__device__ __forceinline__ double dot_f64(f32x4 a, f32x4 b, double acc) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) acc = __builtin_fma((double)a[q], (double)b[q], acc);
+    return acc;
+}
+
 constexpr int kMaskCols = 8;       // mask bytes (groups of 8 neurons) per workgroup of predict_mask
 constexpr int kMaskJg = 32;        // rank groups per workgroup of predict_mask
 constexpr int kMaskRows = 8;       // rows of B a thread keeps in flight
@@ -46,9 +60,7 @@ __global__ __launch_bounds__(256) void k_predict_xa(const T* __restrict__ x, con
     const int err = st->error;
     double acc = 0.0;
 #pragma unroll
-    for (int it = 0; it < NI; ++it)
-#pragma unroll
-        for (int q = 0; q < VE; ++q) acc = __builtin_fma((double)a[it][q], (double)xr[it][q], acc);
+    for (int it = 0; it < NI; ++it) acc = dot_f64(a[it], xr[it], acc);
 #pragma unroll
     for (int msk = 32; msk >= 1; msk >>= 1) acc += __shfl_xor(acc, msk, kWave);
     if (lane == 0 && !err) t[(size_t)b * r + j] = acc;
@@ -204,31 +216,41 @@ __global__ __launch_bounds__(256) void k_predict_mask(const T* __restrict__ B, c
 
 // Gate projection as the predictor (Appendix, Llama 2, "Alternative approaches"): the gate matrix stays
 // resident and  a_i = gate_i . x + b_i  decides exactly which neurons fire (mask bit = a_i > theta); the same
-// pass leaves relu(a_i) per neuron for the FFN, so bundles hold only up row | down column.
-// One wave per group of 8 neurons (one mask byte): 16-byte loads along the row, fp64 accumulation (bit-exact
-// decision), wave reduction.  grid-stride over F / 8 groups, block = 256.  NI as in the FFN kernels.
-template <typename T, int NI>
+// pass leaves relu(a_i) per token and neuron for the FFN, so bundles hold only up row | down column.
+// One wave per group of 8 neurons (one mask byte per token): 16-byte loads along the row, fp64 accumulation
+// (bit-exact decision), wave reduction.  grid-stride over F / 8 groups, block = 256.  NI as in the FFN kernels.
+// XREG (one token): x stays in registers.  Otherwise the tokens' x are staged in LDS (dynamic LDS: batch * d
+// elements) and every gate row, loaded once, is applied to each token in turn; masks [batch x F/8], step mask = OR
+// over the tokens, gact [batch x F].
+template <typename T, int NI, bool XREG>
 __global__ __launch_bounds__(256) void k_predict_gate(const T* __restrict__ Wg, const float* __restrict__ b,
-                                                      const T* __restrict__ x, int d, int F, float theta,
+                                                      const T* __restrict__ x, int d, int F, int batch, float theta,
                                                       uint8_t* __restrict__ mask, uint8_t* __restrict__ step_mask,
                                                       float* __restrict__ gact, const DevState* __restrict__ st) {
     using V = typename Vec<T>::type;
     constexpr int VE = Vec<T>::N;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_gate[];
+    V* xs = reinterpret_cast<V*>(smem_gate);
     const int tid = threadIdx.x, lane = tid & 63;
     const int nvec = d / VE;
     const int gw = blockIdx.x * 4 + (tid >> 6), nw = gridDim.x * 4;
     const V* xv = reinterpret_cast<const V*>(x);
-    V xr[NI];
+    V xr[XREG ? NI : 1];
+    if (XREG) {
 #pragma unroll
-    for (int it = 0; it < NI; ++it) {
-        const int idx = it * 64 + lane;
-        xr[it] = (idx < nvec) ? xv[idx] : V(0);
+        for (int it = 0; it < NI; ++it) {
+            const int idx = it * 64 + lane;
+            xr[it] = (idx < nvec) ? xv[idx] : V(0);
+        }
+    } else {
+        for (int i = tid; i < batch * nvec; i += 256) xs[i] = xv[i];
+        __syncthreads();
     }
     if (st->error) return;
     const double th = (double)theta;
+    const int mask_stride = F >> 3;
     for (int grp = gw; grp * 8 < F; grp += nw) {
-        unsigned byte = 0;
-        float keep_act = 0.f;
+        unsigned long long bits = 0;                 // bit 8 * token + e: neuron grp * 8 + e fires for that token
 #pragma unroll 2
         for (int e = 0; e < 8; ++e) {
             const int i = grp * 8 + e;
@@ -239,22 +261,36 @@ __global__ __launch_bounds__(256) void k_predict_gate(const T* __restrict__ Wg, 
                 const int idx = it * 64 + lane;
                 g[it] = (idx < nvec) ? row[idx] : V(0);
             }
-            double acc = 0.0;
+            const double bi = (double)b[i];
+            for (int t = 0; t < (XREG ? 1 : batch); ++t) {
+                double acc = 0.0;
 #pragma unroll
-            for (int it = 0; it < NI; ++it)
+                for (int it = 0; it < NI; ++it) {
+                    const int idx = it * 64 + lane;
+                    if (XREG) acc = dot_f64(g[it], xr[it], acc);          // both are 0 past the end of the vector
+                    else if (idx < nvec) acc = dot_f64(g[it], xs[t * nvec + idx], acc);
+                }
 #pragma unroll
-                for (int q = 0; q < VE; ++q) acc = __builtin_fma((double)g[it][q], (double)xr[it][q], acc);
-#pragma unroll
-            for (int msk = 32; msk >= 1; msk >>= 1) acc += __shfl_xor(acc, msk, kWave);
-            const double a = acc + (double)b[i];
-            if (a > th) byte |= 1u << e;
-            if (lane == e) keep_act = (float)(a > 0.0 ? a : 0.0);
+                for (int msk = 32; msk >= 1; msk >>= 1) acc += __shfl_xor(acc, msk, kWave);
+                const double a = acc + bi;
+                if (a > th) bits |= 1ull << (8 * t + e);
+                if (lane == 0) gact[(size_t)t * F + i] = (float)(a > 0.0 ? a : 0.0);
+            }
         }
-        if (lane == 0) {
-            mask[grp] = (uint8_t)byte;
-            if (step_mask != mask) step_mask[grp] = (uint8_t)byte;   // one token: the step mask is the mask
+        if (XREG) {
+            if (lane == 0) {
+                mask[grp] = (uint8_t)bits;
+                if (step_mask != mask) step_mask[grp] = (uint8_t)bits;   // one token: the step mask is the mask
+            }
+        } else {
+            if (lane < batch) mask[(size_t)lane * mask_stride + grp] = (uint8_t)(bits >> (8 * lane));
+            if (lane == 0) {
+                unsigned long long o = bits | (bits >> 32);
+                o |= o >> 16;
+                o |= o >> 8;
+                step_mask[grp] = (uint8_t)o;
+            }
         }
-        if (lane < 8) gact[grp * 8 + lane] = keep_act;
     }
 }
 

@@ -548,17 +548,78 @@ def test_n4_llama_shape_gate_predictor():
     print("N4 max rel-L2 %.2e, rows %.0f" % (max(s["err"] for s in stats), np.mean([s["n"] for s in stats[10:]])))
 
 
-def test_gate_predictor_rejects_batches_and_gated_bundles():
-    import paper_2312_11514_amd as lif
+def test_gate_predictor_rejects_gated_bundles():
     from tests.harness import GpuLayer
     w = wl.scaled(wl.WORKLOADS["C1"], name="gate", glu=True, gate_resident=True, tokens=2)
     L = wl.make_layer(w)
-    with pytest.raises(Exception):
-        GpuLayer(w, L, max_batch=2)
+    import paper_2312_11514_amd as lif
+    with pytest.raises(lif.LifError):
+        lif.Layer(d_model=w.d_model, d_ffn=w.d_ffn, rank=8, window_k=2, capacity_rows=64, glu=True, dtype="f32",
+                  predictor=lif.PRED_GATE, A=torch.zeros(8, device="cuda"), B=None, c=None,
+                  b=torch.zeros(8, device="cuda"), host_bundles=torch.zeros(8).pin_memory())
     gpu = GpuLayer(w, L)
     x2 = gpu.upload_x(np.stack([wl.make_inputs(w)[0]] * 2))
-    with pytest.raises(Exception):
-        gpu.layer.predict(x2, 2)
+    with pytest.raises(lif.LifError):
+        gpu.layer.predict(x2, 2)                      # max_batch is 1
+
+
+@pytest.mark.parametrize("api", ["calls", "step"])
+@pytest.mark.parametrize("batch", [2, 5, 8])
+@pytest.mark.parametrize("dtype,d_model", [("f16", 608), ("f16", 568), ("f32", 256)])
+def test_gate_predictor_batched_tokens(dtype, d_model, batch, api):
+    """The resident gate as predictor for batches of tokens: per-token masks and gate activations, step mask = OR,
+    one row of y per token over the shared cache (fp16, d % 32 == 0: MFMA activation stage; otherwise the streaming
+    kernel).  Exact predictor: every row of y is also the dense gated FFN of its token."""
+    from tests.harness import GpuLayer, compare_step, rel_l2
+    w = wl.scaled(wl.WORKLOADS["C1"], name="gateb", d_model=d_model, d_ffn=1096, rank=8, window_k=3, p_active=0.05,
+                  dtype=dtype, glu=True, gate_resident=True, tokens=10, batch=batch, capacity_rows=1003)
+    L = wl.make_layer(w)
+    X = wl.make_batch_inputs(w)
+    stats = run_stream(w, L, X, api=api)
+    assert np.mean([s["n"] for s in stats]) > 80 and any(s["moved"] > 0 for s in stats)
+    gpu = GpuLayer(w, L)
+    gpu.layer.set_expected_rows(4096)                 # fp16, d % 32 == 0: the shared load + activation launch of lif_step
+    ora = make_oracle(w, L)
+    for t in range(4):
+        compare_step(gpu, ora, X[t], w, t, api=api)
+        for bt in range(batch):
+            dense = O.dense_ffn(L.w_up, L.w_down, L.b, X[t][bt], w_gate=L.w_gate)
+            assert rel_l2(gpu.y[bt].cpu().numpy(), dense) <= 1e-3
+
+
+@pytest.mark.parametrize("api", ["calls", "step"])
+def test_gate_predictor_speculative_passes(api):
+    """Passes of five consecutive tokens with the resident gate as predictor (Section 4.3 with the Appendix's
+    alternative predictor): token-granular window, transient masks, FFN rows for all five tokens."""
+    from tests.harness import GpuLayer, rel_l2, REL_L2_TOL
+    w = wl.scaled(wl.WORKLOADS["C1"], name="gatespec", d_model=608, d_ffn=1024, rank=8, window_k=4, dtype="f16",
+                  glu=True, gate_resident=True, tokens=45, batch=5, capacity_rows=1024, p_active=0.05)
+    L = wl.make_layer(w)
+    X = wl.make_inputs(w)
+    gpu = GpuLayer(w, L, max_batch=5)
+    lay = gpu.layer
+    ora = make_oracle(w, L)
+    for p, keep in enumerate([5, 3, 0, 1, 5, 2, 4, 0, 5]):
+        xb = X[5 * p:5 * p + 5]
+        ref = ora.step_tokens(xb, keep)
+        xd = gpu.upload_x(xb)
+        if api == "step":
+            lay.step_tokens(xd, gpu.y, 5, keep)
+        else:
+            lay.predict(xd, 5)
+            lay.update_window_tokens(5, keep)
+            lay.load_bundles()
+            lay.sparse_ffn(xd, gpu.y, 5)
+        na, nr = int(lay.n_added.item()), int(lay.n_removed.item())
+        assert lay.added[:na].cpu().numpy().tolist() == ref["added"].tolist(), f"pass {p}"
+        assert lay.removed[:nr].cpu().numpy().tolist() == ref["removed"].tolist(), f"pass {p}"
+        n = ref["num_used"]
+        st = lay.state()
+        assert st["error"] == 0 and st["num_used"] == n and st["window_len"] == len(ora.window.masks)
+        assert (lay.masks[:5].cpu().numpy() == O.pack_mask(ref["masks"])).all()
+        assert (lay.pointers[:n].cpu().numpy() == ora.cache.pointers[:n]).all()
+        assert rel_l2(gpu.y[:5].cpu().numpy(), ref["y"]) <= REL_L2_TOL
+    assert ora.min_margin > 1e-9 and lay.counters()["h2d_bytes"] == ora.bytes_loaded
 
 
 # ----------------------------------------------------------------------------- seeded random configurations

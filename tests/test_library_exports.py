@@ -41,7 +41,7 @@ def test_workspace_size_and_config_validation_without_gpu():
     assert n >= 8192 * 4 * 3 and n % 256 == 0
     bad_shapes = [
         dict(d_model=4090), dict(d_ffn=16385), dict(d_ffn=1 << 20), dict(rank=100), dict(window_k=0),
-        dict(capacity_rows=0), dict(max_batch=9), dict(dtype=7), dict(glu=2), dict(ffn_mode=5), dict(shrink_window=3), dict(predictor=2), dict(predictor=1, glu=1), dict(predictor=1, max_batch=2),
+        dict(capacity_rows=0), dict(max_batch=9), dict(dtype=7), dict(glu=2), dict(ffn_mode=5), dict(shrink_window=3), dict(predictor=2), dict(predictor=1, glu=1),
     ]
     for ch in bad_shapes:
         cfg = b.LifConfig(4096, 16384, 128, 5, 8192, 1, 0, b.LIF_F16, 0, 0, 0, 0.0)
