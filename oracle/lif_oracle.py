@@ -98,11 +98,16 @@ class SlidingWindow:
             s |= m
         return s
 
-    def push_tokens(self, masks, keep, capacity=None):
+    def push_tokens(self, masks, keep, capacity=None, shrink=False):
         """One verification pass of speculative decoding (Section 4.3): `masks` [n_tokens, F] are the
         per-token masks of the pass; the first `keep` tokens enter the window one by one; every
         mask of the pass is held for this pass (all its tokens are computed), those that are not
-        in the window afterwards leave with the next update.  Returns (added, removed) against what was held before."""
+        in the window afterwards leave with the next update.  Returns (added, removed) against what was held before.
+
+        If what has to be held would exceed `capacity` rows: with shrink=False the state is left unchanged and
+        OverflowError is raised; with shrink=True (dynamic window, Appendix, Persimmon / Phi-2 window
+        configuration, applied to a pass of tokens) the oldest window masks leave for good, one at a time, until
+        the masks of the pass together with the remaining window fit; only a pass whose own masks do not fit raises."""
         masks = np.asarray(masks, dtype=bool)
         before = self.active_set()
         new_masks = list(self.masks)
@@ -112,11 +117,22 @@ class SlidingWindow:
         transient = np.zeros(self.F, dtype=bool)       # every token of the pass is computed in this pass,
         for i in range(len(masks)):                    # also one that enters and leaves the window at once
             transient |= masks[i]
-        after = transient.copy()
-        for m in new_masks:
-            after |= m
+
+        def held(ms):
+            u = transient.copy()
+            for m in ms:
+                u |= m
+            return u
+
+        after = held(new_masks)
         if capacity is not None and int(after.sum()) > capacity:
-            raise OverflowError("active set exceeds the neuron cache capacity")
+            if not shrink:
+                raise OverflowError("active set exceeds the neuron cache capacity")
+            while new_masks and int(held(new_masks).sum()) > capacity:
+                new_masks.pop(0)
+            after = held(new_masks)
+            if int(after.sum()) > capacity:
+                raise OverflowError("the masks of the pass alone exceed the neuron cache capacity")
         self.masks, self.transient = new_masks, transient
         added = np.flatnonzero(after & ~before).astype(np.int32)
         removed = np.flatnonzero(before & ~after).astype(np.int32)
@@ -344,7 +360,7 @@ class OracleLayer:
     def step_tokens(self, x, keep):
         """One speculative verification pass: x [n_tokens, d]; the first `keep` tokens enter the window."""
         masks = self.predict(x)
-        added, removed = self.window.push_tokens(masks, keep, self.cache.capacity)
+        added, removed = self.window.push_tokens(masks, keep, self.cache.capacity, self.shrink)
         loaded = self.load_bundles(added, removed)
         y = self.sparse_ffn(x)
         return dict(masks=masks, added=added, removed=removed, loaded=loaded, y=y,

@@ -22,8 +22,10 @@ MUTATIONS = [
      "kept = self.masks[-self.k:]", "test_window_hand_worked", ()),
     ("window: one mask too few", "kept = self.masks[-(self.k - 1):] if self.k > 1 else []",
      "kept = self.masks[-(self.k - 2):] if self.k > 2 else []", "test_window_equals_bruteforce_union_of_last_k", (5,)),
-    ("dynamic window: drops a newer mask", "                new_masks.pop(0)",
-     "                new_masks.pop(-2 if len(new_masks) > 1 else 0)", "test_dynamic_window_hand_worked", ()),
+    ("dynamic window: drops a newer mask",
+     "int(union(new_masks).sum()) > capacity:\n                new_masks.pop(0)",
+     "int(union(new_masks).sum()) > capacity:\n                new_masks.pop(-2 if len(new_masks) > 1 else 0)",
+     "test_dynamic_window_hand_worked", ()),
     ("dynamic window: shrinks once too often",
      "while len(new_masks) > 1 and int(union(new_masks).sum()) > capacity:",
      "while len(new_masks) > 1 and int(union(new_masks).sum()) >= capacity:",
@@ -60,6 +62,14 @@ MUTATIONS = [
     ("pass of tokens: transient masks forgotten", "        for i in range(len(masks)):                    # also one that enters and leaves the window at once\n            transient |= masks[i]",
      "        for i in range(keep, keep):\n            transient |= masks[i]",
      "test_layer_pass_of_tokens_equals_the_dense_ffn_restricted_to_the_held_set", ()),
+    ("dynamic window, pass of tokens: the newest mask leaves first",
+     "            while new_masks and int(held(new_masks).sum()) > capacity:\n                new_masks.pop(0)",
+     "            while new_masks and int(held(new_masks).sum()) > capacity:\n                new_masks.pop(-1)",
+     "test_window_tokens_dynamic_hand_worked", ()),
+    ("dynamic window, pass of tokens: the masks of the pass are not counted",
+     "            while new_masks and int(held(new_masks).sum()) > capacity:",
+     "            while new_masks and int(np.logical_or.reduce(new_masks).sum()) > capacity:",
+     "test_window_tokens_dynamic_is_the_longest_suffix_that_fits", ()),
     ("gate ffn, batch: every token takes the first token's gate activations",
      "np.asarray(gate_act, np.float64)[..., cache.pointers[:n]]",
      "np.atleast_2d(np.asarray(gate_act, np.float64))[0, cache.pointers[:n]]",

@@ -498,6 +498,73 @@ def test_window_tokens_reduces_to_single_pushes():
     assert (c.active_set() == np.logical_or.reduce(held)).all()
 
 
+def test_window_tokens_dynamic_hand_worked():
+    g = golden("window_tokens_shrink.json")
+    F = g["d_ffn"]
+    win = O.SlidingWindow(F, g["k"])
+    for p in g["passes"]:
+        M = np.zeros((len(p["masks"]), F), bool)
+        for i, ids in enumerate(p["masks"]):
+            M[i, ids] = True
+        if p.get("overflow"):
+            with pytest.raises(OverflowError):
+                win.push_tokens(M, p["keep"], g["capacity"], shrink=True)
+        else:
+            added, removed = win.push_tokens(M, p["keep"], g["capacity"], shrink=True)
+            assert list(added) == p["added"] and list(removed) == p["removed"]
+        assert list(np.flatnonzero(win.active_set())) == p["active"]
+        assert len(win.masks) == p["window_len"]
+
+
+def test_window_tokens_dynamic_is_the_longest_suffix_that_fits():
+    """Brute force with Python sets: after a pass the window is the longest suffix of (old window, kept tokens), at
+    most k masks, whose union with the masks of the pass fits; dropped masks never return; with room to spare
+    the dynamic form is the fixed one; a pass of one kept token is the single-token dynamic push."""
+    rng = np.random.default_rng(11)
+    F, k, cap = 96, 5, 30
+    win, fixed, big = O.SlidingWindow(F, k), O.SlidingWindow(F, k), O.SlidingWindow(F, k)
+    ref = []                                            # list of sets, oldest first
+    held_before = set()
+    shrunk = 0
+    for p in range(60):
+        ntok = int(rng.integers(1, 5))
+        keep = int(rng.integers(0, ntok + 1))
+        M = rng.random((ntok, F)) < 0.07
+        sets = [set(np.flatnonzero(m).tolist()) for m in M]
+        T = set().union(*sets)
+        cand = (ref + sets[:keep])[-k:]
+        best = None
+        for a in range(len(cand), -1, -1):              # longest suffix first
+            u = set(T)
+            for sset in cand[len(cand) - a:]:
+                u |= sset
+            if len(u) <= cap:
+                best = (cand[len(cand) - a:], u)
+                break
+        if best is None:
+            with pytest.raises(OverflowError):
+                win.push_tokens(M, keep, cap, shrink=True)
+            continue
+        shrunk += len(best[0]) < len(cand)
+        added, removed = win.push_tokens(M, keep, cap, shrink=True)
+        ref = best[0]
+        assert set(np.flatnonzero(win.active_set()).tolist()) == best[1]
+        assert len(win.masks) == len(ref)
+        assert all(set(np.flatnonzero(m).tolist()) == sset for m, sset in zip(win.masks, ref))
+        assert list(added) == sorted(best[1] - held_before) and list(removed) == sorted(held_before - best[1])
+        held_before = best[1]
+        a1 = fixed.push_tokens(M, keep)
+        a2 = big.push_tokens(M, keep, F, shrink=True)
+        assert list(a1[0]) == list(a2[0]) and list(a1[1]) == list(a2[1])
+    assert shrunk > 5, "the capacity never bound"
+    a, b = O.SlidingWindow(F, k), O.SlidingWindow(F, k)
+    for p in range(30):
+        m = rng.random(F) < 0.12
+        r1 = a.push_tokens(m[None, :], 1, cap, shrink=True)
+        r2 = b.push(m, cap, shrink=True)
+        assert list(r1[0]) == list(r2[0]) and list(r1[1]) == list(r2[1]) and len(a.masks) == len(b.masks)
+
+
 # ----------------------------------------------------------------------------- resident gate as predictor
 def _gate_layer(g, theta, k=2):
     gate, up, down = (np.array(g[n], np.float32) for n in ("gate", "up", "down"))
