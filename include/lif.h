@@ -203,8 +203,10 @@ int lif_update_window(lif_layer* layer, const uint8_t* step_mask_dev,
  *              one entry per token, exactly as if pushed one after the other; the masks of the
  *              remaining tokens are needed for this pass only and leave with the next update.
  * The cache must hold, for this pass, the union of the last window_k kept token masks and of
- * the transient masks: added / removed are the difference to what it holds now.  Capacity
- * overflow is a LIF_CAPACITY error (no dynamic shrink on this path).  Alternates with
+ * the transient masks: added / removed are the difference to what it holds now.  If that exceeds
+ * capacity_rows: with shrink_window = 0 a LIF_CAPACITY error; with shrink_window = 1 the oldest window
+ * masks leave for good, one by one, until the masks of the pass and the remaining window fit (only a
+ * pass whose own masks do not fit is a LIF_CAPACITY error).  Alternates with
  * lif_load_bundles like lif_update_window; follow with lif_sparse_ffn(batch = n_tokens).
  */
 int lif_update_window_tokens(lif_layer* layer, const uint8_t* masks_dev, int32_t n_tokens, int32_t keep,

@@ -530,7 +530,6 @@ static int check_window_tokens(lif_layer* L, int32_t n_tokens, int32_t keep) {
     if (n_tokens < 1 || n_tokens > L->cfg.max_batch) return fail(LIF_INVALID_ARG, "n_tokens out of range");
     if (keep < 0 || keep > n_tokens) return fail(LIF_INVALID_ARG, "keep must be in 0..n_tokens");
     if (L->cfg.d_ffn % 64) return fail(LIF_INVALID_ARG, "token-granular window updates need d_ffn % 64 == 0");
-    if (L->cfg.shrink_window) return fail(LIF_INVALID_ARG, "token-granular window updates do not combine with shrink_window");
     return LIF_OK;
 }
 

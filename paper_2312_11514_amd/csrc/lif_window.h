@@ -85,7 +85,7 @@ __global__ __launch_bounds__(kScanThreads) void k_window_plan(
     __shared__ unsigned long long rem64[kScanThreads];
     __shared__ int hole_lds[kHoleLds];
     __shared__ int blk_h[kScanThreads], blk_f[kScanThreads];      // per 64-slot block: counts, then exclusive prefixes
-    __shared__ int cnt_age[256];                                  // dynamic window: |union of the newest a masks|
+    __shared__ int cnt_age[264];                                  // dynamic window: |union of the newest a masks| (a <= 256)
     const int tid = threadIdx.x, lane = tid & (kWave - 1), w = tid >> 6;
     const unsigned long long lt = (1ull << lane) - 1ull;
     const int nwords = (F + 63) >> 6, nbytes = F >> 3;
@@ -152,6 +152,46 @@ __global__ __launch_bounds__(kScanThreads) void k_window_plan(
                 if (since >= keep_tok) now |= ring[(size_t)j * ring_words + tid];
             }
         }
+    }
+    if (shrink && multi) {
+        // Dynamic window for a pass of several tokens (Section 4.3 with the Appendix's dynamic window): T = all
+        // masks of the pass is held in any case; the window after the pass - its masks by age a = 1 (newest)
+        // .. k: the kept tokens, newest first, then the ring entries the pass does not overwrite - keeps the
+        // newest k_eff masks, k_eff the largest count for which |T u U_a| fits the capacity (cnt_age[a], a = 0
+        // .. k; the counts grow with a).  The kept tokens are subsets of T, so they always stay.
+        auto age_mask = [&](int a) -> unsigned long long {        // mask of age a (1 <= a <= k), word of this lane
+            if (a <= keep_tok) return load_mask_word(step_mask + (size_t)(keep_tok - a) * nbytes, tid, nbytes);
+            const int m_old = a - keep_tok;                        // m_old-th most recent entry written before this pass
+            return ring[(size_t)(((pos - m_old) % k + k) % k) * ring_words + tid];
+        };
+        for (int a = tid; a <= k; a += kScanThreads) cnt_age[a] = 0;
+        __syncthreads();
+        unsigned long long u = 0ull;
+        if (have)
+            for (int i = 0; i < ntok; ++i) u |= load_mask_word(step_mask + (size_t)i * nbytes, tid, nbytes);
+        const unsigned long long pass_all = u;
+        if (u) atomicAdd(&cnt_age[0], __popcll(u));
+        for (int a = 1; a <= k; ++a) {
+            if (have) u |= age_mask(a);
+            if (u) atomicAdd(&cnt_age[a], __popcll(u));
+        }
+        __syncthreads();
+        k_eff = -1;
+        for (int a = 0; a <= k; ++a)
+            if (cnt_age[a] <= capacity) k_eff = a;
+        if (k_eff < 0) {                                     // uniform: the masks of the pass alone do not fit
+            if (tid == 0) {
+                st->error = 3;                               // LIF_CAPACITY
+                *n_added = 0;
+                *n_removed = 0;
+                st->n_added = 0;
+                st->n_removed = 0;
+            }
+            return;
+        }
+        now = pass_all;
+        if (have)
+            for (int a = 1; a <= k_eff; ++a) now |= age_mask(a);
     }
     if (shrink && !multi) {
         // Dynamic window (Appendix, Persimmon / Phi-2: the window is reduced whenever the cache would
@@ -255,6 +295,9 @@ __global__ __launch_bounds__(kScanThreads) void k_window_plan(
             for (int i = max(0, keep_tok - k); i < keep_tok; ++i)
                 ring[(size_t)((pos + i) % k) * ring_words + tid] =
                     load_mask_word(step_mask + (size_t)i * nbytes, tid, nbytes);
+            // entries written before this pass that the dynamic window dropped (ages above k_eff) leave for good
+            for (int m_old = max(k_eff - keep_tok, 0) + 1; m_old <= k - keep_tok; ++m_old)
+                ring[(size_t)(((pos - m_old) % k + k) % k) * ring_words + tid] = 0ull;
         }
     }
     while (abits) {
@@ -337,7 +380,7 @@ __global__ __launch_bounds__(kScanThreads) void k_window_plan(
         st->n_removed = tot_r;
         st->n_base = n2;
         st->n_moved = H;
-        st->window_len = multi ? min(wl_prev + keep_tok, k) : min(min(wl_prev + 1, k), k_eff);
+        st->window_len = multi ? min(min(wl_prev + keep_tok, k), k_eff) : min(min(wl_prev + 1, k), k_eff);
         st->ring_pos = (pos + (multi ? keep_tok : 1)) % k;
         st->step = t + 1;
         st->c_steps += 1;

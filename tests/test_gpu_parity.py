@@ -518,6 +518,69 @@ def test_speculative_verify_passes_token_granular_window(glu, dtype, d_model, ap
         assert rel_l2(gpu.y[0].cpu().numpy(), ref["y"]) <= REL_L2_TOL
 
 
+@pytest.mark.parametrize("api", ["calls", "step"])
+@pytest.mark.parametrize("k,dtype,d_model,glu,cap", [(4, "f16", 256, False, 145), (6, "f16", 608, True, 135),
+                                                     (12, "f32", 132, False, 230)])
+def test_dynamic_window_with_speculative_passes(k, dtype, d_model, glu, cap, api):
+    """Passes of several tokens with shrink_window = 1 and a capacity that the fixed window overflows: the oldest
+    window masks leave until the masks of the pass and the rest fit; a pass whose own masks do not fit sets the
+    error on both sides and leaves everything unchanged."""
+    from tests.harness import GpuLayer, rel_l2, REL_L2_TOL
+    import paper_2312_11514_amd as lif
+    w = wl.scaled(wl.WORKLOADS["C1"], name="specshrink", d_model=d_model, d_ffn=1024, rank=32, window_k=k,
+                  dtype=dtype, glu=glu, tokens=80, batch=5, capacity_rows=cap, p_active=0.05)
+    L = wl.make_layer(w)
+    X = wl.make_inputs(w)
+    gpu = GpuLayer(w, L, max_batch=5, shrink=True)
+    lay = gpu.layer
+    ora = O.OracleLayer(w.d_model, w.d_ffn, w.window_k, w.capacity_rows, w.glu, L.A, L.B, L.c, L.theta, L.b,
+                        L.bundles, shrink=True)
+    keeps = [5, 4, 5, 3, 0, 1, 5, 5, 2, 4, 5, 0, 5, 5, 3, 5]
+    lens, pos = [], 0
+    for p, keep in enumerate(keeps):
+        ntok = 5 if p % 4 != 3 else 2                            # passes of different lengths
+        keep = min(keep, ntok)
+        xb = X[pos:pos + ntok]
+        pos += ntok
+        ref = ora.step_tokens(xb, keep)
+        xd = gpu.upload_x(xb)
+        if api == "step":
+            lay.step_tokens(xd, gpu.y, ntok, keep)
+        else:
+            lay.predict(xd, ntok)
+            lay.update_window_tokens(ntok, keep)
+            lay.load_bundles()
+            lay.sparse_ffn(xd, gpu.y, ntok)
+        na, nr = int(lay.n_added.item()), int(lay.n_removed.item())
+        assert lay.added[:na].cpu().numpy().tolist() == ref["added"].tolist(), f"pass {p}"
+        assert lay.removed[:nr].cpu().numpy().tolist() == ref["removed"].tolist(), f"pass {p}"
+        n = ref["num_used"]
+        st = lay.state()
+        assert st["error"] == 0 and st["num_used"] == n <= w.capacity_rows
+        assert st["window_len"] == len(ora.window.masks), f"pass {p}"
+        assert (lay.pointers[:n].cpu().numpy() == ora.cache.pointers[:n]).all()
+        assert lay.matrix[:n].cpu().numpy().tobytes() == ora.cache.matrix[:n].tobytes()
+        assert rel_l2(gpu.y[:ntok].cpu().numpy(), ref["y"]) <= REL_L2_TOL
+        lens.append((st["window_len"], min(k, sum(min(q, 5) for q in keeps[:p + 1]))))
+    assert any(a < b for a, b in lens[3:]), "capacity never bound: the test does not exercise the shrink"
+    assert lay.counters()["h2d_bytes"] == ora.bytes_loaded and ora.min_margin > 1e-9
+    # a pass whose own masks exceed the capacity: error, nothing changes (theta = -inf is not available per call, so
+    # a second layer with a tiny capacity takes the same pass)
+    w2 = wl.scaled(w, capacity_rows=40)
+    gpu2 = GpuLayer(w2, L, max_batch=5, shrink=True)
+    ora2 = O.OracleLayer(w.d_model, w.d_ffn, w.window_k, 40, w.glu, L.A, L.B, L.c, L.theta, L.b, L.bundles, shrink=True)
+    with pytest.raises(OverflowError):
+        ora2.step_tokens(X[:5], 5)
+    xd = gpu2.upload_x(X[:5])
+    if api == "step":
+        gpu2.layer.step_tokens(xd, gpu2.y, 5, 5)
+    else:
+        gpu2.layer.predict(xd, 5)
+        gpu2.layer.update_window_tokens(5, 5)
+    st = gpu2.layer.state()
+    assert st["error"] == lif.LIF_CAPACITY and st["num_used"] == 0 and st["step"] == 0 and st["window_len"] == 0
+
+
 # ----------------------------------------------------------------------------- resident gate as predictor
 @pytest.mark.parametrize("api", ["calls", "step"])
 @pytest.mark.parametrize("ffn_mode", [0, 1])
@@ -678,18 +741,26 @@ def test_seeded_random_speculative_passes(i):
                   d_ffn=int(rng.integers(2, 40)) * 64, rank=2 * ve, window_k=int(rng.integers(1, 8)),
                   p_active=float(rng.uniform(0.02, 0.12)), dtype=dtype, glu=bool(rng.integers(2)),
                   tokens=ntok * 10, batch=ntok)
-    w = wl.scaled(w, capacity_rows=w.d_ffn)
+    shrink = i % 2 == 1                                  # odd cases: dynamic window with a capacity that binds
+    w = wl.scaled(w, capacity_rows=max(16, int(w.d_ffn * w.p_active * (ntok + 1.5))) if shrink else w.d_ffn)
     L = wl.make_layer(w)
     X = wl.make_inputs(w)
     keeps = [int(rng.integers(0, ntok + 1)) for _ in range(10)]
     for api in ("calls", "step"):
-        gpu = GpuLayer(w, L, max_batch=ntok)
+        gpu = GpuLayer(w, L, max_batch=ntok, shrink=shrink)
         lay = gpu.layer
-        ora = make_oracle(w, L)
+        ora = O.OracleLayer(w.d_model, w.d_ffn, w.window_k, w.capacity_rows, w.glu, L.A, L.B, L.c, L.theta, L.b,
+                            L.bundles, shrink=shrink)
         for p, keep in enumerate(keeps):
             xb = X[ntok * p:ntok * (p + 1)]
-            ref = ora.step_tokens(xb, keep)
             xd = gpu.upload_x(xb)
+            try:
+                ref = ora.step_tokens(xb, keep)
+            except OverflowError:
+                # the masks of the pass alone exceed the capacity: the device reports the same and stops
+                lay.step_tokens(xd, gpu.y, ntok, keep)
+                assert lay.state()["error"] == 3
+                break
             if api == "step":
                 lay.step_tokens(xd, gpu.y, ntok, keep)
             else:
