@@ -21,6 +21,8 @@ struct DevState {
     int32_t window_len;   // step masks currently in the window (<= k; smaller after a dynamic shrink)
     int32_t ring_pos;     // ring entry the next mask goes to
     int32_t pad;
+    // counters: only ever updated with atomic adds whose result is not used (a load-add-store at the end of a kernel
+    // would keep its last wave waiting for a memory round trip)
     unsigned long long c_steps, c_added, c_removed, c_rows_moved, c_h2d_bytes;
     unsigned long long c_ffn_calls, c_ffn_rows, c_ffn_active;   // FFN calls, rows in use, rows with a non-zero activation
 };

@@ -246,14 +246,17 @@ __global__ __launch_bounds__(256) void k_ffn_down(const T* __restrict__ matrix, 
     // (the activation array spans the whole capacity, so the addresses are valid; values past
     // num_used are masked below): one memory round trip less on the critical path
     const bool first_row = blockIdx.y == 0;
-    float hfirst[PER][BT];
+    float hfirst[PER][BT], hnfirst[PER][BT];
     int sfirst[PER];
 #pragma unroll
     for (int q = 0; q < PER; ++q) {
         const int s = q * 256 + tid;
 #pragma unroll
-        for (int b = 0; b < BT; ++b)
+        for (int b = 0; b < BT; ++b) {
             hfirst[q][b] = (first_row && s < capacity && b < batch) ? h[(size_t)b * capacity + s] : 0.f;
+            // the loader-written activations travel in the same round trip as h and the stamps
+            hnfirst[q][b] = (first_row && stamp && s < capacity && b < batch) ? h_new[(size_t)b * capacity + s] : 0.f;
+        }
         sfirst[q] = (first_row && stamp && s < capacity) ? stamp[s] : -1;
     }
     const int err = st->error;
@@ -268,8 +271,7 @@ __global__ __launch_bounds__(256) void k_ffn_down(const T* __restrict__ matrix, 
         for (int q = 0; q < PER; ++q)
             if (sfirst[q] == cur_step) {
 #pragma unroll
-                for (int b = 0; b < BT; ++b)
-                    if (b < batch) hfirst[q][b] = h_new[(size_t)b * capacity + q * 256 + tid];
+                for (int b = 0; b < BT; ++b) hfirst[q][b] = hnfirst[q][b];
             }
     }
     const int ob = tid / LANES, ol = tid - ob * LANES;            // (token, lane) whose 16-byte piece this thread writes
@@ -380,8 +382,8 @@ __global__ __launch_bounds__(256) void k_ffn_down(const T* __restrict__ matrix, 
     }
     if (slice == 0 && tid == 0) {
         if (first_row) {
-            st->c_ffn_calls += 1;
-            st->c_ffn_rows += (unsigned long long)n;
+            atomicAdd(&st->c_ffn_calls, 1ull);
+            atomicAdd(&st->c_ffn_rows, (unsigned long long)n);
         }
         if (n_active) atomicAdd(&st->c_ffn_active, (unsigned long long)n_active);
     }

@@ -226,7 +226,7 @@ __device__ __forceinline__ void load_role(T* __restrict__ matrix, int32_t* __res
     }
     if (wave_id == 0 && lane == 0) {
         st->num_used = n2 + a;
-        st->c_h2d_bytes += (unsigned long long)a * row_elems * sizeof(T);
+        atomicAdd(&st->c_h2d_bytes, (unsigned long long)a * row_elems * sizeof(T));
     }
 }
 

@@ -10,7 +10,8 @@
 
 namespace lif {
 
-constexpr int kScanThreads = 1024;   // single-workgroup kernels: 16 waves; one 64-neuron word or one slot per lane
+constexpr int kScanThreads = 1024;   // single-workgroup kernels: up to 16 waves; one 64-neuron word or one 64-slot block per lane
+constexpr int kScanThreadsSmall = 256; // ... 4 waves when d_ffn and capacity_rows are at most 256 x 64 = 16384 (fewer waves at every barrier)
 constexpr int kMaxSpan = 64;         // d_ffn <= 1024 * 64; capacity <= 1024 * 64
 constexpr int kHoleLds = 4096;       // holes kept in LDS; longer lists spill to the global scratch list
 constexpr int kRingRegs = 8;         // window masks a lane keeps in registers (larger k takes a second pass)
@@ -74,17 +75,19 @@ __device__ __forceinline__ void block_exclusive_scan2(int va, int vb, unsigned l
 //
 // The loads that do not depend on the state (mask word, ring words, first block of pointers)
 // are issued together with the state itself.
-__global__ __launch_bounds__(kScanThreads) void k_window_plan(
+// THREADS: workgroup size; needs ceil(F / 64) <= THREADS and capacity <= 64 * THREADS.  The results do not depend on it.
+template <int THREADS>
+__global__ __launch_bounds__(THREADS) void k_window_plan(
     const uint8_t* __restrict__ step_mask, int ntok, int keep_tok, unsigned long long* __restrict__ ring,
     unsigned long long* __restrict__ cur_set, int ring_words, const int32_t* __restrict__ pointers, int F, int k,
     int capacity, int shrink, int32_t* __restrict__ added,
     int32_t* __restrict__ n_added, int32_t* __restrict__ removed, int32_t* __restrict__ n_removed,
     int32_t* __restrict__ move_dst, int32_t* __restrict__ hole_list, DevState* st) {
-    constexpr int NW = kScanThreads / kWave;
+    constexpr int NW = THREADS / kWave;
     __shared__ unsigned long long wave_tot[NW];
-    __shared__ unsigned long long rem64[kScanThreads];
+    __shared__ unsigned long long rem64[THREADS];
     __shared__ int hole_lds[kHoleLds];
-    __shared__ int blk_h[kScanThreads], blk_f[kScanThreads];      // per 64-slot block: counts, then exclusive prefixes
+    __shared__ int blk_h[THREADS], blk_f[THREADS];                // per 64-slot block: counts, then exclusive prefixes
     __shared__ int cnt_age[264];                                  // dynamic window: |union of the newest a masks| (a <= 256)
     const int tid = threadIdx.x, lane = tid & (kWave - 1), w = tid >> 6;
     const unsigned long long lt = (1ull << lane) - 1ull;
@@ -97,9 +100,9 @@ __global__ __launch_bounds__(kScanThreads) void k_window_plan(
     unsigned long long rv[kRingRegs];
 #pragma unroll
     for (int j = 0; j < kRingRegs; ++j) rv[j] = (have && j < k) ? ring[(size_t)j * ring_words + tid] : 0ull;
-    // slot owners of the first four blocks of this wave (4 x 1024 slots), for the deletion plan below; the
+    // slot owners of the first blocks of this wave (4096 slots over the workgroup), for the deletion plan below; the
     // array spans the capacity, entries past num_used are masked when used
-    constexpr int kPtrPre = 4;
+    constexpr int kPtrPre = 64 / NW;
     int idpre[kPtrPre];
 #pragma unroll
     for (int it = 0; it < kPtrPre; ++it) {
@@ -164,7 +167,7 @@ __global__ __launch_bounds__(kScanThreads) void k_window_plan(
             const int m_old = a - keep_tok;                        // m_old-th most recent entry written before this pass
             return ring[(size_t)(((pos - m_old) % k + k) % k) * ring_words + tid];
         };
-        for (int a = tid; a <= k; a += kScanThreads) cnt_age[a] = 0;
+        for (int a = tid; a <= k; a += THREADS) cnt_age[a] = 0;
         __syncthreads();
         unsigned long long u = 0ull;
         if (have)
@@ -197,7 +200,7 @@ __global__ __launch_bounds__(kScanThreads) void k_window_plan(
         // Dynamic window (Appendix, Persimmon / Phi-2: the window is reduced whenever the cache would
         // pass its memory limit): keep the newest k_eff <= k masks, k_eff the largest count whose
         // union fits the capacity.  U_a = union of the newest a masks (a = 1: this step's mask).
-        for (int a = tid; a < k; a += kScanThreads) cnt_age[a] = 0;
+        for (int a = tid; a < k; a += THREADS) cnt_age[a] = 0;
         __syncthreads();
         unsigned long long ua[kRingRegs];                // ua[a - 1] = U_a, a = 1 .. min(k, kRingRegs)
         if (k <= kRingRegs && tid >= ((nwords + kWave - 1) & ~(kWave - 1))) {
@@ -383,10 +386,10 @@ __global__ __launch_bounds__(kScanThreads) void k_window_plan(
         st->window_len = multi ? min(min(wl_prev + keep_tok, k), k_eff) : min(min(wl_prev + 1, k), k_eff);
         st->ring_pos = (pos + (multi ? keep_tok : 1)) % k;
         st->step = t + 1;
-        st->c_steps += 1;
-        st->c_added += (unsigned long long)tot_a;
-        st->c_removed += (unsigned long long)tot_r;
-        st->c_rows_moved += (unsigned long long)H;
+        atomicAdd(&st->c_steps, 1ull);
+        atomicAdd(&st->c_added, (unsigned long long)tot_a);
+        atomicAdd(&st->c_removed, (unsigned long long)tot_r);
+        atomicAdd(&st->c_rows_moved, (unsigned long long)H);
     }
 }
 
@@ -462,7 +465,7 @@ __device__ __forceinline__ void load_rows_role(char* __restrict__ matrix, int32_
     }
     if (block == 0 && tid == 0) {
         st->num_used = n2 + a;
-        st->c_h2d_bytes += (unsigned long long)a * row_bytes;
+        atomicAdd(&st->c_h2d_bytes, (unsigned long long)a * row_bytes);
     }
 }
 
