@@ -173,32 +173,33 @@ def sweep_window(args):
     print(json.dumps({"sweep": "window size k", "workload": describe(base_w), "rows": rows}))
 
 
-def sweep_chunk(args):
-    """Host-to-device throughput of the bundle gather against the chunk size (the analogue of the paper's
-    Fig. 2b and of Table 1's bundling row: one read of 2*d*E bytes per neuron instead of two reads of d*E).
-    Same bytes per step (about 2.4 MB of new bundles) at every chunk size; masks are forced through the
-    predictor offset so that exactly `rows` new neurons appear per step."""
+def _forced_gather(d, F, rows, unbundled, pairs_list, rng, steps=14):
+    """Event-timed load kernel of lif_step when exactly `rows` new neurons appear per step (masks forced through the
+    predictor offset).  Returns {pairs: median us}."""
     import numpy as np
     import torch
     import paper_2312_11514_amd as lif
     dev = torch.device("cuda:0")
-    F, r = 16384, 32
-    rng = np.random.default_rng(0)
-    out = []
-    for d in (256, 512, 1024, 2048, 4096, 8192):
-        bundle = 2 * d * 2
-        rows = max(1, int(round(2.4e6 / bundle)))
-        host = torch.from_numpy(rng.standard_normal((F, 2 * d), dtype=np.float32).astype(np.float16)).pin_memory()
-        A = torch.zeros((r, d), dtype=torch.float16, device=dev)
-        B = torch.zeros((r, F), dtype=torch.float16, device=dev)
-        c = torch.zeros(F, device=dev)
-        b = torch.zeros(F, device=dev)
-        x = torch.zeros(d, dtype=torch.float16, device=dev)
-        y = torch.zeros(d, dtype=torch.float16, device=dev)
-        lay = lif.Layer(d_model=d, d_ffn=F, rank=r, window_k=1, capacity_rows=F, dtype="f16", A=A, B=B, c=c, b=b,
-                        host_bundles=host)
+    r = 32
+    store = rng.standard_normal((F, 2 * d), dtype=np.float32).astype(np.float16)
+    if unbundled:
+        host = torch.from_numpy(np.ascontiguousarray(store[:, :d])).pin_memory()
+        host_down = torch.from_numpy(np.ascontiguousarray(store[:, d:])).pin_memory()
+    else:
+        host, host_down = torch.from_numpy(store).pin_memory(), None
+    A = torch.zeros((r, d), dtype=torch.float16, device=dev)
+    B = torch.zeros((r, F), dtype=torch.float16, device=dev)
+    c = torch.zeros(F, device=dev)
+    b = torch.zeros(F, device=dev)
+    x = torch.zeros(d, dtype=torch.float16, device=dev)
+    y = torch.zeros(d, dtype=torch.float16, device=dev)
+    lay = lif.Layer(d_model=d, d_ffn=F, rank=r, window_k=1, capacity_rows=F, dtype="f16", A=A, B=B, c=c, b=b,
+                    host_bundles=host, host_down=host_down)
+    out = {}
+    for pairs in pairs_list:
+        lay.set_loader_pairs(pairs)
         ts = []
-        for it in range(14):
+        for it in range(steps):
             m = np.full(F, -1.0, np.float32)
             m[rng.choice(F, rows, replace=False)] = 1.0
             c.copy_(torch.from_numpy(m))
@@ -206,11 +207,41 @@ def sweep_chunk(args):
             lay.profile_begin(16)
             lay.step(x, y)
             ts.append(lay.profile_collect()["load"][0] * 1e3)
-        t = float(np.median(ts[4:]))
+        out[pairs] = float(np.median(ts[4:]))
+    lay.close()
+    return out
+
+
+def sweep_chunk(args):
+    """Host-to-device throughput of the bundle gather against the chunk size (the analogue of the paper's
+    Fig. 2b and of Table 1's bundling row: one read of 2*d*E bytes per neuron instead of two reads of d*E from two
+    arrays).  Same bytes per step (about 2.4 MB of new bundles) at every chunk size; both layouts are measured."""
+    import numpy as np
+    F = 16384
+    rng = np.random.default_rng(0)
+    out = []
+    for d in (256, 512, 1024, 2048, 4096, 8192):
+        bundle = 2 * d * 2
+        rows = max(1, int(round(2.4e6 / bundle)))
+        tb = _forced_gather(d, F, rows, False, [0], rng)[0]
+        tu = _forced_gather(d, F, rows, True, [0], rng)[0]
         out.append({"d_model": d, "chunk_bytes": bundle, "unbundled_chunk_bytes": bundle // 2, "rows_per_step": rows,
-                    "load_kernel_us_event_timed": t, "GBs": rows * bundle / t / 1e3})
-        lay.close()
-    print(json.dumps({"sweep": "chunk size (bundle bytes) at ~2.4 MB per step", "rows": out}))
+                    "load_kernel_us_event_timed": tb, "GBs": rows * bundle / tb / 1e3,
+                    "unbundled_load_kernel_us_event_timed": tu, "unbundled_GBs": rows * bundle / tu / 1e3})
+    print(json.dumps({"sweep": "chunk size (bundle bytes) at ~2.4 MB per step, bundled and not bundled", "rows": out}))
+
+
+def sweep_loaders(args):
+    """Host-link throughput of lif_step's gather against the number of loader wave pairs (bundles in flight), at the
+    OPT shape: 146 new bundles of 16 KiB per step.  Shows the ceiling of a shader-driven gather on this link."""
+    import numpy as np
+    rng = np.random.default_rng(0)
+    d, F, rows = 4096, 16384, 146
+    pairs = [2, 4, 6, 8, 10, 12, 16, 20, 24, 32, 48, 64]
+    t = _forced_gather(d, F, rows, False, pairs, rng)
+    out = [{"loader_pairs": p, "KiB_in_flight": p * 16, "load_kernel_us_event_timed": t[p],
+            "GBs": rows * 4 * d / t[p] / 1e3} for p in pairs]
+    print(json.dumps({"sweep": "loader wave pairs of lif_step at 146 bundles of 16 KiB per step", "rows": out}))
 
 
 def sweep_rows(args):
@@ -526,7 +557,7 @@ def main():
                          "is accurate (labelled in the output; never mixed with the default)")
     ap.add_argument("--overpredict", type=float, default=1.0,
                     help="predictor calibrated to fire on overpredict * p_active of the neurons")
-    ap.add_argument("--sweep", default=None, choices=["k", "chunk", "rows"],
+    ap.add_argument("--sweep", default=None, choices=["k", "chunk", "rows", "loaders"],
                     help="instead of the bench line: window-size sweep or chunk-size sweep (one JSON line each)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -540,6 +571,8 @@ def main():
         return sweep_chunk(args)
     if args.sweep == "rows":
         return sweep_rows(args)
+    if args.sweep == "loaders":
+        return sweep_loaders(args)
 
     import numpy as np
     import torch

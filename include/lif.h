@@ -104,6 +104,12 @@ typedef struct lif_buffers {
      * device-resident counts                                                             */
     void* workspace;
     size_t workspace_bytes;
+    /* optional second part of the bundle store (PINNED HOST memory, read-only), normally NULL.  If set, the store is
+     * NOT bundled (the layout that Section 3.2's bundling replaces, kept for measuring what bundling buys):
+     * host_bundles then holds only the activation vectors, [d_ffn x (G-1)*d_model] E (row i = (gate_i |) up_i), and
+     * host_down the down columns, [d_ffn x d_model] E; every new neuron costs two reads.  The cache rows, and so
+     * every result, are the same as with the bundled store. */
+    const void* host_down;
 } lif_buffers;
 
 typedef struct lif_state {
@@ -292,6 +298,13 @@ int lif_step_tokens(lif_layer* layer, const void* x_dev, int32_t n_tokens, int32
  * count has arrived.  0 removes the hint.  Results never depend on it.
  */
 int lif_set_expected_rows(lif_layer* layer, int32_t rows);
+
+/*
+ * Performance knob of lif_step's bundle gather (Section 3.3 item 2): the number of loader wave pairs (one bundle in
+ * flight per pair), 1..64; 0 restores the default, which is chosen from the bundle size (256 KiB of reads
+ * outstanding, within 5..32 pairs).  Results never depend on it.
+ */
+int lif_set_loader_pairs(lif_layer* layer, int32_t pairs);
 
 /* Synchronises `stream`, then copies the device-side state / counters to the host. */
 int lif_get_state(lif_layer* layer, lif_state* out, void* stream);

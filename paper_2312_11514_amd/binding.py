@@ -30,7 +30,7 @@ class LifBuffers(C.Structure):
     _fields_ = [("A", C.c_void_p), ("B", C.c_void_p), ("c", C.c_void_p), ("b", C.c_void_p),
                 ("host_bundles", C.c_void_p), ("matrix", C.c_void_p), ("pointers", C.c_void_p),
                 ("bias", C.c_void_p), ("workspace", C.c_void_p),
-                ("workspace_bytes", C.c_size_t)]
+                ("workspace_bytes", C.c_size_t), ("host_down", C.c_void_p)]
 
 
 class LifState(C.Structure):
@@ -61,6 +61,7 @@ EXPORTS = {
     "lif_step_tokens": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p] + [C.c_void_p] * 6 +
                         [C.c_void_p]),
     "lif_set_expected_rows": (C.c_int, [C.c_void_p, C.c_int32]),
+    "lif_set_loader_pairs": (C.c_int, [C.c_void_p, C.c_int32]),
     "lif_get_state": (C.c_int, [C.c_void_p, C.POINTER(LifState), C.c_void_p]),
     "lif_get_counters": (C.c_int, [C.c_void_p, C.POINTER(LifCounters), C.c_void_p]),
     "lif_profile_read": (C.c_int, [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]),
@@ -122,7 +123,7 @@ class Layer:
 
     def __init__(self, *, d_model, d_ffn, rank, window_k, capacity_rows, max_batch=1, glu=False,
                  dtype="f16", ffn_mode=FFN_SKIP_DEAD, shrink_window=False, predictor=PRED_LOWRANK, threshold=0.0, A, B, c, b,
-                 host_bundles):
+                 host_bundles, host_down=None):
         import torch
         self.lib = load_library()
         self.torch = torch
@@ -135,9 +136,9 @@ class Layer:
         ws_bytes = self.lib.lif_workspace_bytes(C.byref(self.cfg))
         if ws_bytes == 0:
             raise LifError(LIF_INVALID_ARG, "configuration rejected by lif_workspace_bytes")
-        if not host_bundles.is_pinned():
-            raise LifError(LIF_INVALID_ARG, "host_bundles must be pinned host memory")
-        self.A, self.B, self.c, self.b, self.host_bundles = A, B, c, b, host_bundles
+        if not host_bundles.is_pinned() or (host_down is not None and not host_down.is_pinned()):
+            raise LifError(LIF_INVALID_ARG, "host_bundles (and host_down) must be pinned host memory")
+        self.A, self.B, self.c, self.b, self.host_bundles, self.host_down = A, B, c, b, host_bundles, host_down
         self.matrix = torch.empty((capacity_rows, G * d_model), dtype=self.tdtype, device=dev)
         self.pointers = torch.empty(capacity_rows, dtype=torch.int32, device=dev)
         self.bias = torch.empty(capacity_rows, dtype=torch.float32, device=dev)
@@ -152,7 +153,8 @@ class Layer:
                               c.data_ptr() if c is not None else None,
                               b.data_ptr(), host_bundles.data_ptr(), self.matrix.data_ptr(),
                               self.pointers.data_ptr(), self.bias.data_ptr(),
-                              self.workspace.data_ptr(), ws_bytes)
+                              self.workspace.data_ptr(), ws_bytes,
+                              host_down.data_ptr() if host_down is not None else None)
         h = C.c_void_p()
         _check(self.lib.lif_create(C.byref(self.cfg), C.byref(self.buf), C.byref(h)))
         self.handle = h
@@ -223,6 +225,9 @@ class Layer:
 
     def set_expected_rows(self, rows: int):
         _check(self.lib.lif_set_expected_rows(self.handle, int(rows)))
+
+    def set_loader_pairs(self, pairs: int):
+        _check(self.lib.lif_set_loader_pairs(self.handle, int(pairs)))
 
     # ---- introspection ---------------------------------------------------------------
     def state(self) -> dict:

@@ -105,7 +105,8 @@ struct lif_layer {
     lif_config cfg;
     lif_buffers buf;
     Layout lay;
-    const char* host_alias;     // device-visible address of the pinned bundle store
+    HostStore host;             // device-visible addresses of the pinned bundle store (bundled or in two parts)
+    int loader_pairs;           // loader wave pairs of the fused step, 0 = chosen from the bundle size
     DevState* st;
     unsigned long long* ring;
     double* tpart;
@@ -276,10 +277,11 @@ void launch_load_up(lif_layer* L, const void* x, const int32_t* added, hipStream
     const int up_blocks = spec ? std::min(kUpMaxWgs, std::max(1, std::min(L->expected_rows, c.capacity_rows) / 4))
                                : std::min((c.capacity_rows + 3) / 4, 512);
     // loader waves come in pairs (activation vectors | down vector of one bundle), one wave per workgroup
-    const int load_wgs = 2 * (int)std::min<size_t>(32, std::max<size_t>(5, kStepInflightBytes / L->row_bytes));
+    const int load_wgs = 2 * (L->loader_pairs > 0 ? L->loader_pairs
+                                                   : (int)std::min<size_t>(32, std::max<size_t>(5, kStepInflightBytes / L->row_bytes)));
 #define LIF_LU(NI)                                                                                            \
     hipLaunchKernelGGL((k_load_up<T, NI, GLU>), dim3(load_wgs + up_blocks), dim3(256), 0, s,                      \
-                       (T*)L->buf.matrix, L->buf.pointers, L->buf.bias, (const T*)L->host_alias, L->buf.b, added, \
+                       (T*)L->buf.matrix, L->buf.pointers, L->buf.bias, L->host, L->buf.b, added, \
                        L->move_dst, L->row_elems, c.d_ffn, c.d_model, c.capacity_rows, (const T*)x, L->h,         \
                        L->h_new, L->stamp, spec, load_wgs, L->gact, L->st)
     if (ni <= 1) LIF_LU(1);
@@ -323,12 +325,12 @@ void launch_load_up_mfma(lif_layer* L, const void* x, int batch, const int32_t* 
     static_assert(kMfmaWaves == 4, "the fused kernel runs both roles with 256 threads");
     if (c.glu)
         hipLaunchKernelGGL((k_load_up_mfma<true>), dim3(kLoadGrid + tiles), dim3(256), 0, s, (_Float16*)L->buf.matrix,
-                           L->buf.pointers, L->buf.bias, L->host_alias, L->buf.b, added, L->move_dst, L->row_bytes,
+                           L->buf.pointers, L->buf.bias, L->host, L->buf.b, added, L->move_dst, L->row_bytes,
                            c.d_ffn, (const _Float16*)x, L->h, c.d_model, batch, c.capacity_rows, kLoadGrid, L->gact,
                            L->st);
     else
         hipLaunchKernelGGL((k_load_up_mfma<false>), dim3(kLoadGrid + tiles), dim3(256), 0, s, (_Float16*)L->buf.matrix,
-                           L->buf.pointers, L->buf.bias, L->host_alias, L->buf.b, added, L->move_dst, L->row_bytes,
+                           L->buf.pointers, L->buf.bias, L->host, L->buf.b, added, L->move_dst, L->row_bytes,
                            c.d_ffn, (const _Float16*)x, L->h, c.d_model, batch, c.capacity_rows, kLoadGrid, L->gact,
                            L->st);
 }
@@ -423,13 +425,22 @@ int lif_create(const lif_config* cfg, const lif_buffers* buf, lif_layer** out) {
     void* alias = nullptr;
     LIF_HIP(hipHostGetDevicePointer(&alias, const_cast<void*>(buf->host_bundles), 0));
     if (!alias) return fail(LIF_HIP_ERROR, "bundle store has no device alias");
+    void* alias_down = nullptr;
+    if (buf->host_down) {
+        if ((uintptr_t)buf->host_down % 16) return fail(LIF_INVALID_ARG, "host_down must be 16-byte aligned");
+        LIF_HIP(hipHostGetDevicePointer(&alias_down, const_cast<void*>(buf->host_down), 0));
+        if (!alias_down) return fail(LIF_HIP_ERROR, "down-column store has no device alias");
+    }
 
     lif_layer* L = new (std::nothrow) lif_layer();
     if (!L) return fail(LIF_INVALID_ARG, "out of host memory");
     L->cfg = *cfg;
     L->buf = *buf;
     L->lay = lay;
-    L->host_alias = (const char*)alias;
+    L->host.rows = (const char*)alias;
+    L->host.down = (const char*)alias_down;
+    L->host.act_bytes = (size_t)(cfg->glu ? 2 : 1) * cfg->d_model * elem_bytes(*cfg);
+    L->loader_pairs = 0;
     char* ws = (char*)buf->workspace;
     L->st = (DevState*)(ws + lay.state);
     L->ring = (unsigned long long*)(ws + lay.ring);
@@ -584,7 +595,7 @@ int lif_load_bundles(lif_layer* L, const int32_t* added_dev, const int32_t* n_ad
         const int grid = (int)std::min<long long>(worst, kLoadGrid);
         Timed t(L, LIF_K_LOAD, s);
         hipLaunchKernelGGL(k_load, dim3(grid), dim3(256), 0, s, (char*)L->buf.matrix, L->buf.pointers, L->buf.bias,
-                           L->host_alias, L->buf.b, added_dev, L->move_dst, L->row_bytes, c.d_ffn, L->st);
+                           L->host, L->buf.b, added_dev, L->move_dst, L->row_bytes, c.d_ffn, L->st);
     }
     L->window_pending = false;
     return check_launch();
@@ -722,6 +733,12 @@ int lif_step_tokens(lif_layer* L, const void* x_dev, int32_t n_tokens, int32_t k
     if (keep_tokens < 0) return fail(LIF_INVALID_ARG, "keep must be in 0..n_tokens");
     return step_impl(L, x_dev, n_tokens, keep_tokens, y_dev, masks_dev, step_mask_dev, added_dev, n_added_dev,
                      removed_dev, n_removed_dev, stream);
+}
+
+int lif_set_loader_pairs(lif_layer* L, int32_t pairs) {
+    if (!L || pairs < 0 || pairs > 64) return fail(LIF_INVALID_ARG, "loader pairs must be in 0..64");
+    L->loader_pairs = pairs;
+    return LIF_OK;
 }
 
 int lif_set_expected_rows(lif_layer* L, int32_t rows) {

@@ -27,6 +27,21 @@ struct DevState {
     unsigned long long c_ffn_calls, c_ffn_rows, c_ffn_active;   // FFN calls, rows in use, rows with a non-zero activation
 };
 
+// Where the bundle of neuron i lives in pinned host memory (Section 3.2, Fig. 5).  Bundled (down == null): one
+// contiguous chunk of row_bytes at rows + i * row_bytes.  Not bundled: the activation vectors ((gate |) up row,
+// act_bytes) at rows + i * act_bytes and the down column at down + i * (row_bytes - act_bytes): two reads per
+// neuron, the layout that bundling replaces.  All sizes are multiples of 16 bytes.
+struct HostStore {
+    const char* rows;
+    const char* down;
+    size_t act_bytes;
+};
+// address of byte `off` (a multiple of 16, < row_bytes) of the bundle of neuron i
+__device__ __forceinline__ const char* host_piece(const HostStore& hs, int i, size_t off, size_t row_bytes) {
+    if (hs.down && off >= hs.act_bytes) return hs.down + (size_t)i * (row_bytes - hs.act_bytes) + (off - hs.act_bytes);
+    return hs.rows + (size_t)i * (hs.down ? hs.act_bytes : row_bytes) + off;
+}
+
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));

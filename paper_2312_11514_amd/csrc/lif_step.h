@@ -39,7 +39,7 @@ constexpr int kStepLoadWaves = 1;                     // waves of a loader workg
 // are not split: one wave takes the whole bundle.
 template <typename T, int NI, bool GLU>
 __device__ __forceinline__ void load_role(T* __restrict__ matrix, int32_t* __restrict__ pointers,
-                                          float* __restrict__ bias, const T* __restrict__ host,
+                                          float* __restrict__ bias, const HostStore host,
                                           const float* __restrict__ b, const int32_t* __restrict__ added,
                                           const int32_t* __restrict__ move_dst, size_t row_elems, int F, int d,
                                           int capacity, const T* __restrict__ x, float* __restrict__ h_new,
@@ -57,6 +57,7 @@ __device__ __forceinline__ void load_role(T* __restrict__ matrix, int32_t* __res
     const int g0 = part ? GA : 0;                        // first vector of this wave's part
     const int gn = part ? 1 : GA;                        // number of vectors in it
     const bool act_wave = part == 0;
+    const size_t row_bytes = row_elems * sizeof(T);
     const V* xv = reinterpret_cast<const V*>(x);
     V xr[NI];
 #pragma unroll
@@ -104,7 +105,6 @@ __device__ __forceinline__ void load_role(T* __restrict__ matrix, int32_t* __res
       int dst = __shfl(dst_l, 0, kWave), nid = __shfl(nid_l, 0, kWave);
       V hv[GA][NI], mv[GA][NI];
       {
-          const V* hrow = reinterpret_cast<const V*>(host + (size_t)max(nid, 0) * row_elems) + (size_t)g0 * nvec;
           const V* srow = reinterpret_cast<const V*>(matrix + (size_t)(n2 + q0) * row_elems) + (size_t)g0 * nvec;
 #pragma unroll
           for (int g = 0; g < GA; ++g)
@@ -118,7 +118,9 @@ __device__ __forceinline__ void load_role(T* __restrict__ matrix, int32_t* __res
 #pragma unroll
               for (int it = 0; it < NI; ++it) {
                   const int idx = it * 64 + lane;
-                  hv[g][it] = (nid >= 0 && g < gn && idx < nvec) ? hrow[g * nvec + idx] : V(0);
+                  hv[g][it] = (nid >= 0 && g < gn && idx < nvec)
+                                  ? *reinterpret_cast<const V*>(host_piece(host, nid, ((size_t)(g0 + g) * nvec + idx) * 16, row_bytes))
+                                  : V(0);
               }
       }
       for (int j = 0; j < nitems; ++j) {
@@ -166,7 +168,6 @@ __device__ __forceinline__ void load_role(T* __restrict__ matrix, int32_t* __res
         const int dst_n = (j + 1 < nitems) ? __shfl(dst_l, j + 1, kWave) : -1;
         const int nid_n = (j + 1 < nitems) ? __shfl(nid_l, j + 1, kWave) : -1;
         if (j + 1 < nitems) {
-            const V* hrow = reinterpret_cast<const V*>(host + (size_t)max(nid_n, 0) * row_elems) + (size_t)g0 * nvec;
             const V* nrow = reinterpret_cast<const V*>(matrix + (size_t)(s + pairs) * row_elems) + (size_t)g0 * nvec;
 #pragma unroll
             for (int g = 0; g < GA; ++g)
@@ -180,7 +181,9 @@ __device__ __forceinline__ void load_role(T* __restrict__ matrix, int32_t* __res
 #pragma unroll
                 for (int it = 0; it < NI; ++it) {
                     const int idx = it * 64 + lane;
-                    hv[g][it] = (nid_n >= 0 && g < gn && idx < nvec) ? hrow[g * nvec + idx] : V(0);
+                    hv[g][it] = (nid_n >= 0 && g < gn && idx < nvec)
+                                    ? *reinterpret_cast<const V*>(host_piece(host, nid_n, ((size_t)(g0 + g) * nvec + idx) * 16, row_bytes))
+                                    : V(0);
                 }
         }
         // finish item j: same order of operations as the activation kernel
@@ -233,7 +236,7 @@ __device__ __forceinline__ void load_role(T* __restrict__ matrix, int32_t* __res
 // grid = load_wgs + up_blocks, block = 256.  Batch 1 only.
 template <typename T, int NI, bool GLU>
 __global__ __launch_bounds__(256) void k_load_up(T* __restrict__ matrix, int32_t* __restrict__ pointers,
-                                                 float* __restrict__ bias, const T* __restrict__ host,
+                                                 float* __restrict__ bias, const HostStore host,
                                                  const float* __restrict__ b, const int32_t* __restrict__ added,
                                                  const int32_t* __restrict__ move_dst, size_t row_elems, int F, int d,
                                                  int capacity, const T* __restrict__ x, float* __restrict__ h,
@@ -256,7 +259,7 @@ __global__ __launch_bounds__(256) void k_load_up(T* __restrict__ matrix, int32_t
 // grid = load_wgs + ceil(capacity / 16), block = 256.
 template <bool GLU>
 __global__ __launch_bounds__(256) void k_load_up_mfma(_Float16* __restrict__ matrix, int32_t* __restrict__ pointers,
-                                                      float* __restrict__ bias, const char* __restrict__ host,
+                                                      float* __restrict__ bias, const HostStore host,
                                                       const float* __restrict__ b, const int32_t* __restrict__ added,
                                                       const int32_t* __restrict__ move_dst, size_t row_bytes, int F,
                                                       const _Float16* __restrict__ x, float* __restrict__ h, int d,

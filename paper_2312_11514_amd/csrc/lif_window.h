@@ -409,7 +409,7 @@ constexpr int kLoadGrid = 32;
 
 // `block` / `nblocks`: index and count of the workgroups that share this role.
 __device__ __forceinline__ void load_rows_role(char* __restrict__ matrix, int32_t* __restrict__ pointers,
-                                               float* __restrict__ bias, const char* __restrict__ host,
+                                               float* __restrict__ bias, const HostStore host,
                                                const float* __restrict__ b, const int32_t* __restrict__ added,
                                                const int32_t* __restrict__ move_dst, size_t row_bytes, int F,
                                                int block, int nblocks, DevState* st) {
@@ -426,7 +426,6 @@ __device__ __forceinline__ void load_rows_role(char* __restrict__ matrix, int32_
         int nid = (q < a) ? added[q] : -1;
         if (nid >= F) nid = -1;
         const size_t off0 = (size_t)ch * kLoadChunk + (size_t)tid * 16;
-        const char* hsrc = host + (size_t)max(nid, 0) * row_bytes + off0;
         const char* msrc = matrix + (size_t)s * row_bytes + off0;
         char* mdst = matrix + (size_t)max(dst, 0) * row_bytes + off0;
         char* adst = matrix + (size_t)s * row_bytes + off0;
@@ -440,7 +439,8 @@ __device__ __forceinline__ void load_rows_role(char* __restrict__ matrix, int32_
         }
 #pragma unroll
         for (int p = 0; p < kLoadPer; ++p)
-            if (ok[p] && nid >= 0) hv[p] = *reinterpret_cast<const uint4*>(hsrc + (size_t)p * 4096);
+            if (ok[p] && nid >= 0)
+                hv[p] = *reinterpret_cast<const uint4*>(host_piece(host, nid, off0 + (size_t)p * 4096, row_bytes));
 #pragma unroll
         for (int p = 0; p < kLoadPer; ++p)
             if (ok[p] && dst >= 0) mv[p] = *reinterpret_cast<const uint4*>(msrc + (size_t)p * 4096);
@@ -470,7 +470,7 @@ __device__ __forceinline__ void load_rows_role(char* __restrict__ matrix, int32_
 }
 
 __global__ __launch_bounds__(256) void k_load(char* __restrict__ matrix, int32_t* __restrict__ pointers,
-                                              float* __restrict__ bias, const char* __restrict__ host,
+                                              float* __restrict__ bias, const HostStore host,
                                               const float* __restrict__ b, const int32_t* __restrict__ added,
                                               const int32_t* __restrict__ move_dst, size_t row_bytes, int F,
                                               DevState* st) {

@@ -19,9 +19,9 @@ def make_oracle(w, L, capacity=None, k=None):
                          L.A, L.B, L.c, L.theta, L.b, L.bundles, w_gate=L.w_gate if gate else None)
 
 
-def run_stream(w, L, X, ffn_mode=0, check_every=1, api="calls"):
+def run_stream(w, L, X, ffn_mode=0, check_every=1, api="calls", **gpu_args):
     from tests.harness import GpuLayer, compare_step
-    gpu = GpuLayer(w, L, ffn_mode=ffn_mode)
+    gpu = GpuLayer(w, L, ffn_mode=ffn_mode, **gpu_args)
     ora = make_oracle(w, L)
     stats = []
     for t in range(len(X)):
@@ -900,3 +900,39 @@ def test_rejected_step_leaves_device_buffers_untouched():
     lay.load_bundles()
     lay.sparse_ffn(X[1], gpu.y)
     assert lay.state()["error"] == 0
+
+
+@pytest.mark.parametrize("api", ["calls", "step"])
+@pytest.mark.parametrize("glu,dtype,d_model,batch", [(False, "f16", 568, 1), (True, "f16", 568, 1), (False, "f32", 264, 1),
+                                                     (False, "f16", 4096, 1), (True, "f16", 608, 5), (True, "f32", 132, 3)])
+def test_store_that_is_not_bundled_gives_the_same_cache(glu, dtype, d_model, batch, api):
+    """host_down set: up (and gate) rows and down columns sit in two separate pinned arrays and every new neuron
+    costs two reads (the layout Section 3.2 replaces).  Cache rows, ids and outputs are those of the bundled store."""
+    w = wl.scaled(wl.WORKLOADS["C1"], name="unbundled", d_model=d_model, d_ffn=1096 if d_model < 4096 else 512, rank=40,
+                  window_k=3, p_active=0.08, dtype=dtype, glu=glu, tokens=10, batch=batch, capacity_rows=700)
+    L = wl.make_layer(w) if d_model < 4096 else _random_predictor_layer(w, seed=3)
+    X = wl.make_inputs(w) if batch == 1 else wl.make_batch_inputs(w)
+    stats = run_stream(w, L, X, api=api, unbundled=True)
+    assert any(s["moved"] > 0 for s in stats)
+
+
+@pytest.mark.parametrize("pairs", [1, 7, 64])
+def test_loader_pairs_never_change_results(pairs):
+    from tests.harness import GpuLayer
+    w = wl.WORKLOADS["C2"]
+    L = wl.cached_layer("C2")
+    X = wl.make_inputs(w, tokens=10)
+    out = []
+    for p in (0, pairs):
+        gpu = GpuLayer(w, L)
+        gpu.layer.set_loader_pairs(p)
+        xd = gpu.upload_x(X)
+        y = torch.zeros_like(xd)
+        for t in range(len(X)):
+            gpu.layer.step(xd[t], y[t])
+        n = gpu.layer.state()["num_used"]
+        out.append((y.cpu().numpy().tobytes(), gpu.layer.matrix[:n].cpu().numpy().tobytes(),
+                    gpu.layer.pointers[:n].cpu().numpy().tobytes()))
+    assert out[0] == out[1]
+    with pytest.raises(Exception):
+        gpu.layer.set_loader_pairs(65)
