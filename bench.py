@@ -137,7 +137,7 @@ def sweep_window(args):
     X = wl.make_inputs(base_w)
     T = len(X)
     rows = []
-    for k in (1, 2, 3, 4, 5, 6, 8, 12, 16):
+    for k in range(1, 17):
         w = wl.scaled(base_w, window_k=k, capacity_rows=base_w.d_ffn)
         gpu = GpuLayer(w, L)
         lay = gpu.layer
@@ -410,8 +410,29 @@ def ffn_over_states(w, gpu0, L0, states, xd, mode, hint, no_graph):
     cold = fig(*measure(all_layers, 8 * len(lays), 5, lays))
     cold["caches"] = len(lays)
     cold["bytes_cycled"] = sum(len(ids) for _, ids in states) * G * d * E
+    cold["address_span_bytes"] = len(lays) * w.capacity_rows * G * d * E
     for _, g in lays:
         g.layer.close()
+    del lays
+    # the same states in caches preallocated for 2048 rows only: a quarter of the address span, same bytes read -
+    # separates the reach of the address translation from the latency of HBM itself
+    small_cap = 2048
+    if max(len(ids) for _, ids in states) <= small_cap < w.capacity_rows:
+        lays = []
+        for t, ids in states:
+            g = GpuLayer(w, L0, ffn_mode=mode, share=gpu0, capacity=small_cap)
+            g.fill_cache(ids, L0)
+            if hint:
+                g.layer.set_expected_rows(hint)
+            if w.gate_resident:
+                g.layer.predict(xd[t], w.batch)
+            lays.append((t, g))
+        torch.cuda.synchronize()
+        c2 = fig(*measure(all_layers, 8 * len(lays), 5, lays))
+        cold["compact_caches"] = {"capacity_rows": small_cap, "address_span_bytes": len(lays) * small_cap * G * d * E,
+                                  "avg_launch_us": c2["avg_launch_us"], "achieved": c2["achieved"]}
+        for _, g in lays:
+            g.layer.close()
     return per_state, cold
 
 
@@ -784,7 +805,9 @@ def main():
             "floor": floor})
         out["roofline_cold"] = roofline_object(ffn_cold, kernel_name, {
             "memory": f"HBM: {ffn_cold['caches']} caches of this layer ({ffn_cold['bytes_cycled'] / 1e6:.0f} MB of "
-                      "bundles) called in turn, so no call finds its rows in the Infinity Cache"})
+                      "bundles) called in turn, so no call finds its rows in the Infinity Cache",
+            "address_span_bytes": ffn_cold["address_span_bytes"],
+            "compact_caches": ffn_cold.get("compact_caches")})
     elif ffn:
         up_bytes = ffn["rows"] * (G - 1) * d * E
         down_bytes = (ffn["rows"] if reads_all else ffn["active"]) * d * E

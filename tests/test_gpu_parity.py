@@ -288,23 +288,35 @@ def test_hip_graph_replay_matches_eager():
 
 
 def test_c5_stacked_layers_share_the_stream_not_the_state():
-    """Stacked OPT-shaped layers (three of the 32), token-major order as bench.py runs them: every layer
-    has its own predictor, window and cache; bytes loaded per token = sum over layers of |added| x bundle."""
+    """Stacked OPT-shaped layers (five of the 32, spread over the stack), token-major order as bench.py runs them:
+    every layer has its own predictor, window and cache; bytes loaded per token = sum over layers of |added| x
+    bundle.  24 tokens: the window is full from the fifth on, so most steps delete, move and append."""
     from tests.harness import GpuLayer, compare_step
     w = wl.WORKLOADS["C5"]
     base = wl.cached_layer("C2")                      # C5 layers have the C2 shape; layer 0 is the C2 layer
-    Ls = [wl.make_layer_variant(base, w, l) for l in (0, 1, 31)]
+    ids = (0, 1, 7, 16, 31)
+    Ls = [wl.make_layer_variant(base, w, l) for l in ids]
     assert not np.array_equal(Ls[0].bundles[:64], Ls[1].bundles[:64])
-    X = wl.make_inputs(w, tokens=8)
+    X = wl.make_inputs(w, tokens=24)
     gpus = [GpuLayer(w, L) for L in Ls]
     oras = [make_oracle(w, L) for L in Ls]
+    per_token = []
     for t in range(len(X)):
+        print(f"[C5] token {t}", flush=True) if t % 8 == 0 else None
+        loaded = 0
         for gpu, ora in zip(gpus, oras):
-            compare_step(gpu, ora, X[t], w, t, check_cache=(t % 4 == 3))
+            before = ora.bytes_loaded
+            r = compare_step(gpu, ora, X[t], w, t, check_cache=(t % 4 == 3), api="step")
+            loaded += ora.bytes_loaded - before
+            assert r["n"] <= w.capacity_rows // 2          # the cache stays far below its cap (half of the FFN rows)
+        per_token.append(loaded)
     for gpu, ora in zip(gpus, oras):
-        assert gpu.layer.counters()["h2d_bytes"] == ora.bytes_loaded
+        cnt = gpu.layer.counters()
+        assert cnt["h2d_bytes"] == ora.bytes_loaded and cnt["rows_moved"] == ora.rows_moved and ora.rows_moved > 0
+    assert sum(per_token) == sum(o.bytes_loaded for o in oras)
+    assert np.mean(per_token[10:]) < 0.25 * per_token[0]   # steady state loads a small part of what the first token did
     m = [g.layer.step_mask.cpu().numpy() for g in gpus]
-    assert not np.array_equal(m[0], m[1]) and not np.array_equal(m[1], m[2])
+    assert all(not np.array_equal(m[i], m[j]) for i in range(len(m)) for j in range(i))
 
 
 @pytest.mark.parametrize("hint", [16, 900, 5000])
