@@ -552,16 +552,10 @@ static int update_window_impl(lif_layer* L, const uint8_t* masks_dev, int ntok, 
     const lif_config& c = L->cfg;
     {
         Timed t(L, LIF_K_WINDOW, s);
-        // four waves do when every 64-neuron word and every 64-slot block has a lane of its own
-        const bool small = ring_words(c) <= kScanThreadsSmall && c.capacity_rows <= kScanThreadsSmall * 64;
-#define LIF_PLAN(THREADS)                                                                                      \
-    hipLaunchKernelGGL((k_window_plan<THREADS>), dim3(1), dim3(THREADS), 0, s, masks_dev, ntok, keep, L->ring,     \
-                       L->ring + (size_t)c.window_k * ring_words(c), ring_words(c), L->buf.pointers, c.d_ffn,      \
-                       c.window_k, c.capacity_rows, c.shrink_window, added_dev, n_added_dev, removed_dev,          \
-                       n_removed_dev, L->move_dst, L->hole_list, L->st)
-        if (small) LIF_PLAN(kScanThreadsSmall);
-        else LIF_PLAN(kScanThreads);
-#undef LIF_PLAN
+        hipLaunchKernelGGL(k_window_plan, dim3(1), dim3(kScanThreads), 0, s, masks_dev, ntok, keep, L->ring,
+                           L->ring + (size_t)c.window_k * ring_words(c), ring_words(c), L->buf.pointers, c.d_ffn,
+                           c.window_k, c.capacity_rows, c.shrink_window, added_dev, n_added_dev, removed_dev,
+                           n_removed_dev, L->move_dst, L->hole_list, L->st);
     }
     L->window_pending = true;
     return check_launch();

@@ -10,8 +10,7 @@
 
 namespace lif {
 
-constexpr int kScanThreads = 1024;   // single-workgroup kernels: up to 16 waves; one 64-neuron word or one 64-slot block per lane
-constexpr int kScanThreadsSmall = 256; // ... 4 waves when d_ffn and capacity_rows are at most 256 x 64 = 16384 (fewer waves at every barrier)
+constexpr int kScanThreads = 1024;   // single-workgroup kernels: 16 waves; one 64-neuron word or one 64-slot block per lane
 constexpr int kMaxSpan = 64;         // d_ffn <= 1024 * 64; capacity <= 1024 * 64
 constexpr int kHoleLds = 4096;       // holes kept in LDS; longer lists spill to the global scratch list
 constexpr int kRingRegs = 8;         // window masks a lane keeps in registers (larger k takes a second pass)
@@ -75,14 +74,13 @@ __device__ __forceinline__ void block_exclusive_scan2(int va, int vb, unsigned l
 //
 // The loads that do not depend on the state (mask word, ring words, first block of pointers)
 // are issued together with the state itself.
-// THREADS: workgroup size; needs ceil(F / 64) <= THREADS and capacity <= 64 * THREADS.  The results do not depend on it.
-template <int THREADS>
-__global__ __launch_bounds__(THREADS) void k_window_plan(
+__global__ __launch_bounds__(kScanThreads) void k_window_plan(
     const uint8_t* __restrict__ step_mask, int ntok, int keep_tok, unsigned long long* __restrict__ ring,
     unsigned long long* __restrict__ cur_set, int ring_words, const int32_t* __restrict__ pointers, int F, int k,
     int capacity, int shrink, int32_t* __restrict__ added,
     int32_t* __restrict__ n_added, int32_t* __restrict__ removed, int32_t* __restrict__ n_removed,
     int32_t* __restrict__ move_dst, int32_t* __restrict__ hole_list, DevState* st) {
+    constexpr int THREADS = kScanThreads;
     constexpr int NW = THREADS / kWave;
     __shared__ unsigned long long wave_tot[NW];
     __shared__ unsigned long long rem64[THREADS];
