@@ -256,20 +256,34 @@ def test_reset_reproduces_the_run_bit_for_bit():
     assert outs[0][2]["h2d_bytes"] == outs[1][2]["h2d_bytes"]
 
 
-def test_hip_graph_replay_matches_eager():
-    """The whole token stream captured once and replayed: every replay equals the eager result."""
+@pytest.mark.parametrize("kind", ["single", "batch8-shared-launch", "passes"])
+def test_hip_graph_replay_matches_eager(kind):
+    """The whole token stream captured once and replayed: every replay equals the eager result (single tokens; batches
+    of 8 through the shared load + MFMA launch; speculative passes of 4 tokens with 3 kept)."""
     from tests.harness import GpuLayer
-    w = wl.WORKLOADS["C1"]
+    if kind == "single":
+        w = wl.WORKLOADS["C1"]
+        X = wl.make_inputs(w)
+    elif kind == "batch8-shared-launch":
+        w = wl.scaled(wl.WORKLOADS["C1"], name="g8", d_model=608, d_ffn=2200, rank=40, window_k=3, p_active=0.06,
+                      dtype="f16", glu=True, tokens=12, batch=8, capacity_rows=2100)
+        X = wl.make_batch_inputs(w)
+    else:
+        w = wl.scaled(wl.WORKLOADS["C1"], name="gp", d_model=256, dtype="f16", tokens=48, batch=4, window_k=5)
+        X = wl.make_inputs(w).reshape(12, 4, -1)
     L = wl.make_layer(w)
     gpu = GpuLayer(w, L)
     lay = gpu.layer
-    xd = gpu.upload_x(wl.make_inputs(w))
+    xd = gpu.upload_x(X)
     ys = torch.zeros_like(xd)
 
     def run():
         lay.reset()
-        for t in range(w.tokens):
-            lay.step(xd[t], ys[t])
+        for t in range(len(X)):
+            if kind == "passes":
+                lay.step_tokens(xd[t], ys[t], 4, 3)
+            else:
+                lay.step(xd[t], ys[t], w.batch)
     run()
     torch.cuda.synchronize()
     y_eager, ptr_eager = ys.clone(), lay.pointers.clone()

@@ -63,6 +63,37 @@ def test_static_scratch_ffn_equals_workspace_ffn(dtype, glu, d_model, rows, ffn_
         assert rel_l2(y_st[:batch].cpu().numpy(), ref) <= (1e-5 if dtype == "f32" else REL_L2_TOL)
 
 
+def test_static_scratch_ffn_under_graph_capture():
+    """The callers the entry point is for: captured once in a HIP graph (no allocation may happen there), replayed
+    three times with eager work in between, every replay equal to the eager workspace call."""
+    from tests.harness import GpuLayer
+    F, d = 4096, 1024
+    w = wl.scaled(wl.WORKLOADS["C1"], name="static", d_model=d, d_ffn=F, rank=8, dtype="f16", glu=False, batch=4,
+                  capacity_rows=F)
+    L = _layer(w, seed=9)
+    gpu = GpuLayer(w, L)
+    lay = gpu.layer
+    rng = np.random.default_rng(4)
+    ids = np.sort(rng.choice(F, 3000, replace=False))
+    gpu.fill_cache(ids, L)
+    xd = gpu.upload_x(rng.standard_normal((4, d)).astype(np.float16))
+    y_ref = torch.zeros((4, d), dtype=torch.float16, device=gpu.dev)
+    y = torch.zeros_like(y_ref)
+    lay.sparse_ffn(xd, y_ref, 4)
+    lay.sparse_ffn_static(xd, y, 4)                    # warm-up outside the capture
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        lay.sparse_ffn_static(xd, y, 4)
+    for rep in range(3):
+        y.fill_(9.0)
+        lay.sparse_ffn(xd, gpu.y, 4)                   # eager work between the replays
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y, y_ref), f"replay {rep}"
+
+
 def test_static_scratch_limit_is_an_error():
     import paper_2312_11514_amd as lif
     from tests.harness import GpuLayer
