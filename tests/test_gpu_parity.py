@@ -57,10 +57,10 @@ def test_ragged_shapes_whole_path(glu, dtype, ffn_mode, api):
 
 
 def test_c2_opt_shape_fp16_whole_path():
-    """OPT-6.7B FFN shape at full size, the launch configuration bench.py times (96 tokens)."""
+    """OPT-6.7B FFN shape at full size, the launch configuration bench.py times, the whole stream of 256 tokens."""
     w = wl.WORKLOADS["C2"]
     L = wl.cached_layer("C2")
-    X = wl.make_inputs(w, tokens=96)
+    X = wl.make_inputs(w)
     stats = run_stream(w, L, X, ffn_mode=0, check_every=8, api="step")
     assert np.mean([s["n"] for s in stats[10:]]) > 800         # window union of ~3 % active masks
     print("C2 max rel-L2 %.2e" % max(s["err"] for s in stats))
@@ -78,7 +78,7 @@ def test_c3_falcon_shape_fp16_whole_path():
     """Falcon-7B FFN shape: d = 4544 = 71 x 64 (ragged 16-byte tail), F = 18176 = 284 x 64."""
     w = wl.WORKLOADS["C3"]
     L = wl.cached_layer("C3")
-    X = wl.make_inputs(w, tokens=40)
+    X = wl.make_inputs(w, tokens=96)
     stats = run_stream(w, L, X, check_every=8, api="step")
     print("C3 max rel-L2 %.2e, rows %.0f" % (max(s["err"] for s in stats), np.mean([s["n"] for s in stats[10:]])))
 
@@ -86,7 +86,7 @@ def test_c3_falcon_shape_fp16_whole_path():
 def test_c4_llama_shape_gated_batch1():
     w = wl.WORKLOADS["C4"]
     L = wl.cached_layer("C4")
-    X = wl.make_inputs(w, tokens=32)
+    X = wl.make_inputs(w, tokens=64)
     stats = run_stream(w, L, X, check_every=8, api="step")
     print("C4 max rel-L2 %.2e, rows %.0f" % (max(s["err"] for s in stats), np.mean([s["n"] for s in stats[10:]])))
 
@@ -962,3 +962,62 @@ def test_loader_pairs_never_change_results(pairs):
     assert out[0] == out[1]
     with pytest.raises(Exception):
         gpu.layer.set_loader_pairs(65)
+
+
+# ----------------------------------------------------------------------------- degenerate sizes and inputs
+@pytest.mark.parametrize("api", ["calls", "step"])
+@pytest.mark.parametrize("dtype", ["f16", "f32"])
+def test_smallest_shapes(dtype, api):
+    """The smallest layer the ABI takes: one 16-byte vector per row, eight neurons, a predictor of one vector, a cache
+    of a single row (the predictor offset lets exactly one neuron fire), window 1."""
+    from tests.harness import GpuLayer, compare_step
+    ve = 8 if dtype == "f16" else 4
+    w = wl.scaled(wl.WORKLOADS["C1"], name="min", d_model=ve, d_ffn=8, rank=ve, window_k=1, dtype=dtype, tokens=6,
+                  capacity_rows=1)
+    L = _random_predictor_layer(w, seed=2)
+    X = wl.make_inputs(w)
+    L.c = np.full(8, -1e6, np.float32)
+    gpu = GpuLayer(w, L)
+    ora = make_oracle(w, L)
+    for t in range(w.tokens):
+        L.c[:] = -1e6
+        L.c[t % 8] = 1e6                               # neuron t fires, whatever x is: one row in, one row out per step
+        gpu.layer.c.copy_(torch.from_numpy(L.c))
+        r = compare_step(gpu, ora, X[t], w, t, api=api)
+        assert r["n"] == 1 and r["added"] == 1 and r["removed"] == (1 if t else 0)
+
+
+def test_longest_window_and_largest_batch():
+    """window_k = 256 (the largest the ABI takes) on a short stream: nothing ever leaves; max_batch = 8 with steps of
+    every batch size from 1 to 8 on the same layer."""
+    from tests.harness import GpuLayer, compare_step
+    w = wl.scaled(wl.WORKLOADS["C1"], name="k256", d_model=264, d_ffn=1096, rank=24, window_k=256, dtype="f16",
+                  tokens=40, batch=8, p_active=0.01, capacity_rows=1096)
+    L = wl.make_layer(w)
+    X = wl.make_batch_inputs(w)
+    gpu = GpuLayer(w, L)
+    ora = make_oracle(w, L)
+    for t in range(16):
+        b = 1 + t % 8
+        r = compare_step(gpu, ora, X[t][0] if b == 1 else X[t][:b], w, t, api="step" if t % 2 else "calls")
+        assert r["removed"] == 0
+    assert gpu.layer.state()["window_len"] == 16
+
+
+def test_non_finite_input_predicts_nothing():
+    """A NaN in x makes every logit NaN, and NaN > theta is false: no neuron is predicted, the window only ages.
+    (The FFN over rows cached earlier would propagate the NaN; with an empty cache y is zero.)"""
+    from tests.harness import GpuLayer
+    w = wl.scaled(wl.WORKLOADS["C1"], tokens=4, window_k=1)
+    L = wl.make_layer(w)
+    X = wl.make_inputs(w).copy()
+    X[1, 5] = np.nan
+    gpu = GpuLayer(w, L)
+    ora = make_oracle(w, L)
+    lay = gpu.layer
+    for t in range(2):
+        ref = ora.step(X[t])
+        lay.step(gpu.upload_x(X[t]), gpu.y)
+        assert (lay.masks[:1].cpu().numpy() == O.pack_mask(np.atleast_2d(ref["masks"]))).all()
+        assert lay.state()["num_used"] == ref["num_used"] and lay.state()["error"] == 0
+    assert ref["num_used"] == 0 and not ref["masks"].any() and not gpu.y.cpu().numpy().any()
