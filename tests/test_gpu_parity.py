@@ -333,6 +333,31 @@ def test_c5_stacked_layers_share_the_stream_not_the_state():
     assert all(not np.array_equal(m[i], m[j]) for i in range(len(m)) for j in range(i))
 
 
+def test_c5_all_32_layers_token_major():
+    """All 32 stacked layers (32 handles, 32 pinned stores, 8.6 GB) for the first tokens of the stream, token-major as
+    bench.py runs configuration 5, every layer against its own oracle; host-to-device bytes per token = sum over the
+    layers of |added| x bundle bytes."""
+    from tests.harness import GpuLayer, compare_step
+    w = wl.WORKLOADS["C5"]
+    base = wl.cached_layer("C2")
+    gpus, oras = [], []
+    for l in range(w.layers):
+        Ll = wl.make_layer_variant(base, w, l)
+        gpus.append(GpuLayer(w, Ll))
+        oras.append(make_oracle(w, Ll))
+        print(f"[C5 x32] layer {l} uploaded", flush=True) if l % 8 == 7 else None
+    X = wl.make_inputs(w, tokens=7)
+    for t in range(len(X)):
+        print(f"[C5 x32] token {t}", flush=True)
+        for gpu, ora in zip(gpus, oras):
+            compare_step(gpu, ora, X[t], w, t, check_cache=(t == len(X) - 1), api="step")
+    h2d = sum(g.layer.counters()["h2d_bytes"] for g in gpus)
+    assert h2d == sum(o.bytes_loaded for o in oras) == sum(g.layer.counters()["added"] for g in gpus) * w.bundle_bytes
+    assert sum(o.rows_moved for o in oras) == sum(g.layer.counters()["rows_moved"] for g in gpus) > 0
+    sizes = [g.layer.state()["num_used"] for g in gpus]
+    assert len(set(sizes)) > 8 and max(sizes) <= w.capacity_rows // 2       # every layer its own set, far below the cap
+
+
 @pytest.mark.parametrize("hint", [16, 900, 5000])
 def test_row_count_hint_never_changes_results(hint):
     """The speculative first pass of the FFN (hint below, near and above the rows in use) gives the same bytes."""
