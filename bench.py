@@ -344,6 +344,23 @@ def read_floor(dev, sizes):
         out[name] = {"bytes": nbytes, "us_per_launch": us, "GBs": nbytes / us / 1e3 if nbytes else None,
                      "source": "Infinity-Cache warm" if warm else "HBM (2 GiB cycled)"}
     del big
+    # what a hand-off inside one kernel (fence + ticket, last workgroup reads the others' results) costs against a
+    # second launch: lif_profile_handoff with and without the fenced tail, 200 launches back to back in a graph
+    scratch = torch.zeros(lif.profile_handoff_bytes(), dtype=torch.uint8, device=dev)
+    ho = {}
+    for fenced in (0, 1):
+        lif.profile_handoff(scratch, fenced)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for _ in range(200):
+                lif.profile_handoff(scratch, fenced)
+        g.replay()
+        torch.cuda.synchronize()
+        ho["fenced_tail_us_per_launch" if fenced else "plain_us_per_launch"] = _timed_replays(g, 5) * 1e3 / (5 * 200)
+    ho["what"] = ("256 workgroups read 16 KiB and write 8 bytes each (the mask kernel's shape); fenced tail: every "
+                  "workgroup passes __threadfence and a ticket, the last one reads the 2 KiB back")
+    out["handoff_inside_a_kernel"] = ho
     return out
 
 

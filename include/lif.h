@@ -329,6 +329,17 @@ int lif_profile_collect(lif_layer* layer, double* ms, int64_t* launches, void* s
  */
 int lif_profile_read(const void* src_dev, size_t bytes, void* sink_dev, void* stream);
 
+/*
+ * Cost reference of the box for a benchmark (not part of the method): what it costs to hand a result from all
+ * workgroups of a kernel to its last workgroup instead of to a second launch.  One launch of 256 workgroups that read
+ * 16 KiB each and write 8 bytes (the shape of the mask kernel of lif_predict); with fenced != 0 every workgroup then
+ * passes a device-scope fence and takes a ticket, and the last to arrive reads the 2 KiB back.  No workgroup waits.
+ *   scratch_dev  device memory, 256-byte aligned, lif_profile_handoff_bytes() bytes, zeroed once before the first call
+ *                (the launch leaves its ticket counter at zero again); calls on one scratch must not overlap.
+ */
+int lif_profile_handoff(void* scratch_dev, int32_t fenced, void* stream);
+size_t lif_profile_handoff_bytes(void);
+
 /* Message of the last LIF_HIP_ERROR / LIF_INVALID_ARG on the calling thread. */
 const char* lif_last_error_string(void);
 

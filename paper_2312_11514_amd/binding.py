@@ -65,6 +65,8 @@ EXPORTS = {
     "lif_get_state": (C.c_int, [C.c_void_p, C.POINTER(LifState), C.c_void_p]),
     "lif_get_counters": (C.c_int, [C.c_void_p, C.POINTER(LifCounters), C.c_void_p]),
     "lif_profile_read": (C.c_int, [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]),
+    "lif_profile_handoff": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p]),
+    "lif_profile_handoff_bytes": (C.c_size_t, []),
     "lif_profile_begin": (C.c_int, [C.c_void_p, C.c_int32]),
     "lif_profile_collect": (C.c_int, [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.c_void_p]),
 }
@@ -111,6 +113,15 @@ def _stream():
 def profile_read(src, nbytes, sink):
     """lif_profile_read: one plain streaming read of the first nbytes bytes of the device tensor src."""
     _check(load_library().lif_profile_read(_ptr(src), int(nbytes), _ptr(sink), _stream()))
+
+
+def profile_handoff(scratch, fenced):
+    """lif_profile_handoff: one launch of the hand-off cost probe over a zero-initialised device byte tensor."""
+    _check(load_library().lif_profile_handoff(_ptr(scratch), int(bool(fenced)), _stream()))
+
+
+def profile_handoff_bytes():
+    return load_library().lif_profile_handoff_bytes()
 
 
 class Layer:

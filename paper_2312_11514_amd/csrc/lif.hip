@@ -386,6 +386,47 @@ __global__ __launch_bounds__(256) void k_probe_read(const uint4* __restrict__ sr
     if ((threadIdx.x & 63) == 0 && acc == 0x9e3779b9u) sink[0] = acc;      // practically never: keeps the loads alive
 }
 
+// Cost reference for merging two dependent kernels without a second launch: 256 workgroups read 16 KiB each and write
+// 8 bytes (the shape of the mask kernel); with `fenced` every workgroup then passes a fence and takes a ticket, and the
+// last one to arrive reads the 2 KiB the others wrote - the hand-off a fused "mask kernel + window kernel" would need.
+// Nothing waits for anything: a workgroup that is not last simply ends.
+constexpr int kHandoffWgs = 256;
+__global__ __launch_bounds__(256) void k_probe_handoff(const uint4* __restrict__ src, unsigned long long* __restrict__ words,
+                                                       unsigned* __restrict__ counter, unsigned long long* __restrict__ out,
+                                                       int fenced) {
+    __shared__ unsigned ticket;
+    __shared__ unsigned long long part[4];
+    const int tid = threadIdx.x;
+    uint4 v[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) v[i] = src[(size_t)blockIdx.x * 1024 + i * 256 + tid];
+    unsigned long long bits = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) bits ^= ((unsigned long long)(v[i].x ^ v[i].z) << 32) | (v[i].y ^ v[i].w);
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) bits ^= __shfl_xor(bits, m, kWave);
+    if ((tid & 63) == 0) part[tid >> 6] = bits;
+    __syncthreads();
+    if (tid == 0) words[blockIdx.x] = part[0] ^ part[1] ^ part[2] ^ part[3];
+    if (!fenced) return;
+    if (tid == 0) {
+        __threadfence();
+        ticket = atomicAdd(counter, 1u);
+    }
+    __syncthreads();
+    if (ticket != gridDim.x - 1) return;
+    __threadfence();
+    unsigned long long m = words[tid];                // gridDim.x == 256 == blockDim.x
+#pragma unroll
+    for (int sft = 32; sft >= 1; sft >>= 1) m ^= __shfl_xor(m, sft, kWave);
+    if ((tid & 63) == 0) part[tid >> 6] = m;
+    __syncthreads();
+    if (tid == 0) {
+        out[0] = part[0] ^ part[1] ^ part[2] ^ part[3];
+        *counter = 0;                                 // ready for the next launch on this stream
+    }
+}
+
 int check_launch() {
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(LIF_HIP_ERROR, "kernel launch: %s", hipGetErrorString(e));
@@ -788,6 +829,18 @@ int lif_profile_read(const void* src_dev, size_t bytes, void* sink_dev, void* st
     const int grid = (int)std::min<size_t>(std::max<size_t>(wgs, 1), 4096);
     hipLaunchKernelGGL(k_probe_read, dim3(grid), dim3(256), 0, (hipStream_t)stream, (const uint4*)src_dev, pieces,
                        (unsigned*)sink_dev);
+    return check_launch();
+}
+
+size_t lif_profile_handoff_bytes(void) { return (size_t)kHandoffWgs * 16384 + 4096; }
+
+int lif_profile_handoff(void* scratch_dev, int32_t fenced, void* stream) {
+    if (!scratch_dev || (uintptr_t)scratch_dev % 256) return fail(LIF_INVALID_ARG, "scratch must be a 256-byte aligned device pointer");
+    char* p = (char*)scratch_dev;
+    char* tail = p + (size_t)kHandoffWgs * 16384;      // 2 KiB of words, then the ticket counter and the result
+    hipLaunchKernelGGL(k_probe_handoff, dim3(kHandoffWgs), dim3(256), 0, (hipStream_t)stream, (const uint4*)p,
+                       (unsigned long long*)tail, (unsigned*)(tail + 2048), (unsigned long long*)(tail + 2048 + 64),
+                       fenced ? 1 : 0);
     return check_launch();
 }
 
