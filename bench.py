@@ -344,22 +344,29 @@ def read_floor(dev, sizes):
         out[name] = {"bytes": nbytes, "us_per_launch": us, "GBs": nbytes / us / 1e3 if nbytes else None,
                      "source": "Infinity-Cache warm" if warm else "HBM (2 GiB cycled)"}
     del big
-    # what a hand-off inside one kernel (fence + ticket, last workgroup reads the others' results) costs against a
-    # second launch: lif_profile_handoff with and without the fenced tail, 200 launches back to back in a graph
+    # what a hand-off inside one kernel costs against a second launch: lif_profile_handoff plain, with a fence +
+    # ticket tail, and with stamped words polled by one workgroup; 200 launches back to back in a graph.  Every
+    # launch of the stamped form needs a fresh stamp, so its graph is replayed once only, three graphs.
     scratch = torch.zeros(lif.profile_handoff_bytes(), dtype=torch.uint8, device=dev)
-    ho = {}
-    for fenced in (0, 1):
-        lif.profile_handoff(scratch, fenced)
+    ho, stamp = {}, 1
+    for mode, key in ((0, "plain_us_per_launch"), (1, "fenced_tail_us_per_launch"), (2, "stamped_words_polled_us_per_launch")):
+        lif.profile_handoff(scratch, mode, stamp)
+        stamp += 1
         torch.cuda.synchronize()
-        g = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(g):
-            for _ in range(200):
-                lif.profile_handoff(scratch, fenced)
-        g.replay()
-        torch.cuda.synchronize()
-        ho["fenced_tail_us_per_launch" if fenced else "plain_us_per_launch"] = _timed_replays(g, 5) * 1e3 / (5 * 200)
-    ho["what"] = ("256 workgroups read 16 KiB and write 8 bytes each (the mask kernel's shape); fenced tail: every "
-                  "workgroup passes __threadfence and a ticket, the last one reads the 2 KiB back")
+        times = []
+        for rep in range(3):
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                for _ in range(200):
+                    lif.profile_handoff(scratch, mode, stamp)
+                    stamp += 1
+            torch.cuda.synchronize()
+            times.append(_timed_replays(g, 1) * 1e3 / 200)
+        ho[key] = min(times)
+    ho["stamped_words_give_ups"] = int(scratch[256 * 16384 + 4100:256 * 16384 + 4104].view(torch.int32).item())
+    ho["what"] = ("256 workgroups read 16 KiB and produce 8 bytes each (the mask kernel's shape); fenced tail: every "
+                  "workgroup passes __threadfence and a ticket, the last one reads the 2 KiB back; stamped words: "
+                  "relaxed device-scope atomic stores of (payload, stamp) words that workgroup 0 polls, bounded")
     out["handoff_inside_a_kernel"] = ho
     return out
 

@@ -330,14 +330,20 @@ int lif_profile_collect(lif_layer* layer, double* ms, int64_t* launches, void* s
 int lif_profile_read(const void* src_dev, size_t bytes, void* sink_dev, void* stream);
 
 /*
- * Cost reference of the box for a benchmark (not part of the method): what it costs to hand a result from all
- * workgroups of a kernel to its last workgroup instead of to a second launch.  One launch of 256 workgroups that read
- * 16 KiB each and write 8 bytes (the shape of the mask kernel of lif_predict); with fenced != 0 every workgroup then
- * passes a device-scope fence and takes a ticket, and the last to arrive reads the 2 KiB back.  No workgroup waits.
- *   scratch_dev  device memory, 256-byte aligned, lif_profile_handoff_bytes() bytes, zeroed once before the first call
- *                (the launch leaves its ticket counter at zero again); calls on one scratch must not overlap.
+ * Cost reference of the box for a benchmark (not part of the method): what it costs to hand the results of all
+ * workgroups of a kernel to one workgroup of the same launch instead of to a second launch.  One launch of 256
+ * workgroups that read 16 KiB each and produce 8 bytes (the shape of the mask kernel of lif_predict).
+ *   mode 0  no hand-off (the plain kernel)
+ *   mode 1  every workgroup passes a device-scope fence and takes a ticket, the last to arrive reads the 2 KiB back;
+ *           no workgroup waits
+ *   mode 2  no fences: results go out as 64-bit words carrying `stamp`, by relaxed device-scope atomic stores, and
+ *           workgroup 0 polls them with relaxed device-scope atomic loads; the wait is bounded (it gives up after
+ *           20000 polls per word and counts that in the 32-bit word at scratch + 256 * 16384 + 4100)
+ *   scratch_dev  device memory, 256-byte aligned, lif_profile_handoff_bytes() bytes, zeroed once before the first call;
+ *                calls on one scratch must not overlap
+ *   stamp        mode 2: a value no earlier launch on this scratch has used (and not 0)
  */
-int lif_profile_handoff(void* scratch_dev, int32_t fenced, void* stream);
+int lif_profile_handoff(void* scratch_dev, int32_t mode, uint32_t stamp, void* stream);
 size_t lif_profile_handoff_bytes(void);
 
 /* Message of the last LIF_HIP_ERROR / LIF_INVALID_ARG on the calling thread. */

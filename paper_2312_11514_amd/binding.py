@@ -65,7 +65,7 @@ EXPORTS = {
     "lif_get_state": (C.c_int, [C.c_void_p, C.POINTER(LifState), C.c_void_p]),
     "lif_get_counters": (C.c_int, [C.c_void_p, C.POINTER(LifCounters), C.c_void_p]),
     "lif_profile_read": (C.c_int, [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]),
-    "lif_profile_handoff": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p]),
+    "lif_profile_handoff": (C.c_int, [C.c_void_p, C.c_int32, C.c_uint32, C.c_void_p]),
     "lif_profile_handoff_bytes": (C.c_size_t, []),
     "lif_profile_begin": (C.c_int, [C.c_void_p, C.c_int32]),
     "lif_profile_collect": (C.c_int, [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.c_void_p]),
@@ -115,9 +115,9 @@ def profile_read(src, nbytes, sink):
     _check(load_library().lif_profile_read(_ptr(src), int(nbytes), _ptr(sink), _stream()))
 
 
-def profile_handoff(scratch, fenced):
+def profile_handoff(scratch, mode, stamp=0):
     """lif_profile_handoff: one launch of the hand-off cost probe over a zero-initialised device byte tensor."""
-    _check(load_library().lif_profile_handoff(_ptr(scratch), int(bool(fenced)), _stream()))
+    _check(load_library().lif_profile_handoff(_ptr(scratch), int(mode), int(stamp), _stream()))
 
 
 def profile_handoff_bytes():

@@ -386,14 +386,20 @@ __global__ __launch_bounds__(256) void k_probe_read(const uint4* __restrict__ sr
     if ((threadIdx.x & 63) == 0 && acc == 0x9e3779b9u) sink[0] = acc;      // practically never: keeps the loads alive
 }
 
-// Cost reference for merging two dependent kernels without a second launch: 256 workgroups read 16 KiB each and write
-// 8 bytes (the shape of the mask kernel); with `fenced` every workgroup then passes a fence and takes a ticket, and the
-// last one to arrive reads the 2 KiB the others wrote - the hand-off a fused "mask kernel + window kernel" would need.
-// Nothing waits for anything: a workgroup that is not last simply ends.
+// Cost reference for merging two dependent kernels without a second launch: 256 workgroups read 16 KiB each and
+// produce 8 bytes (the shape of the mask kernel), then hand them to one workgroup of the same launch.
+//   mode 0  no hand-off: every workgroup writes its 8 bytes and ends
+//   mode 1  fence + ticket: every workgroup passes a device-scope fence and takes a ticket; the last to arrive reads
+//           the 2 KiB the others wrote.  No workgroup waits.
+//   mode 2  no fences: the 8 bytes go out as two 64-bit words (32 bits of payload + the launch's 32-bit stamp) by
+//           relaxed device-scope atomic stores; workgroup 0 polls all 512 words with relaxed device-scope atomic loads
+//           until they carry this launch's stamp.  The wait is bounded (kHandoffPolls per word, then it gives up and
+//           counts the give-up) and the grid of 256 workgroups is resident as a whole on the 256 compute units.
 constexpr int kHandoffWgs = 256;
+constexpr int kHandoffPolls = 20000;
 __global__ __launch_bounds__(256) void k_probe_handoff(const uint4* __restrict__ src, unsigned long long* __restrict__ words,
                                                        unsigned* __restrict__ counter, unsigned long long* __restrict__ out,
-                                                       int fenced) {
+                                                       int mode, unsigned stamp) {
     __shared__ unsigned ticket;
     __shared__ unsigned long long part[4];
     const int tid = threadIdx.x;
@@ -407,8 +413,36 @@ __global__ __launch_bounds__(256) void k_probe_handoff(const uint4* __restrict__
     for (int m = 32; m >= 1; m >>= 1) bits ^= __shfl_xor(bits, m, kWave);
     if ((tid & 63) == 0) part[tid >> 6] = bits;
     __syncthreads();
-    if (tid == 0) words[blockIdx.x] = part[0] ^ part[1] ^ part[2] ^ part[3];
-    if (!fenced) return;
+    const unsigned long long mine = part[0] ^ part[1] ^ part[2] ^ part[3];
+    if (mode == 2) {
+        if (tid < 2) {
+            const unsigned long long w = ((unsigned long long)stamp << 32) | (unsigned)(tid ? (mine >> 32) : mine);
+            __hip_atomic_store(&words[blockIdx.x * 2 + tid], w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        if (blockIdx.x != 0) return;
+        unsigned long long acc = 0;
+        bool ok = true;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            unsigned long long w = 0;
+            int polls = 0;
+            do {
+                w = __hip_atomic_load(&words[tid * 2 + j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            } while ((unsigned)(w >> 32) != stamp && ++polls < kHandoffPolls);
+            ok = ok && (unsigned)(w >> 32) == stamp;
+            acc ^= w & 0xffffffffull;
+        }
+        if (!ok) atomicAdd(counter + 1, 1u);           // give-ups, reported by the caller
+#pragma unroll
+        for (int sft = 32; sft >= 1; sft >>= 1) acc ^= __shfl_xor(acc, sft, kWave);
+        __syncthreads();
+        if ((tid & 63) == 0) part[tid >> 6] = acc;
+        __syncthreads();
+        if (tid == 0) out[0] = part[0] ^ part[1] ^ part[2] ^ part[3];
+        return;
+    }
+    if (tid == 0) words[blockIdx.x] = mine;
+    if (mode == 0) return;
     if (tid == 0) {
         __threadfence();
         ticket = atomicAdd(counter, 1u);
@@ -832,15 +866,16 @@ int lif_profile_read(const void* src_dev, size_t bytes, void* sink_dev, void* st
     return check_launch();
 }
 
-size_t lif_profile_handoff_bytes(void) { return (size_t)kHandoffWgs * 16384 + 4096; }
+size_t lif_profile_handoff_bytes(void) { return (size_t)kHandoffWgs * 16384 + 8192; }
 
-int lif_profile_handoff(void* scratch_dev, int32_t fenced, void* stream) {
+int lif_profile_handoff(void* scratch_dev, int32_t mode, uint32_t stamp, void* stream) {
     if (!scratch_dev || (uintptr_t)scratch_dev % 256) return fail(LIF_INVALID_ARG, "scratch must be a 256-byte aligned device pointer");
+    if (mode < 0 || mode > 2) return fail(LIF_INVALID_ARG, "mode must be 0, 1 or 2");
     char* p = (char*)scratch_dev;
-    char* tail = p + (size_t)kHandoffWgs * 16384;      // 2 KiB of words, then the ticket counter and the result
+    char* tail = p + (size_t)kHandoffWgs * 16384;      // 4 KiB of words, then the ticket counter, the give-up count, the result
     hipLaunchKernelGGL(k_probe_handoff, dim3(kHandoffWgs), dim3(256), 0, (hipStream_t)stream, (const uint4*)p,
-                       (unsigned long long*)tail, (unsigned*)(tail + 2048), (unsigned long long*)(tail + 2048 + 64),
-                       fenced ? 1 : 0);
+                       (unsigned long long*)tail, (unsigned*)(tail + 4096), (unsigned long long*)(tail + 4096 + 64), mode,
+                       stamp);
     return check_launch();
 }
 
