@@ -525,7 +525,7 @@ def bench_stacked(w, base, mode, steps, warmup, no_graph=False, hint=True, ffn_r
     rows_per_call = tot["ffn_rows"] / tot["ffn_calls"]
     if hint:
         for lay in layers:
-            lay.set_expected_rows(int(0.9 * rows_per_call))
+            lay.set_expected_rows(int(1.15 * rows_per_call))
         tok = capture()
     for _ in range(warmup):
         step()
@@ -699,7 +699,7 @@ def main():
         rows_per_call = tot["ffn_rows"] / tot["ffn_calls"]
         active_per_call = tot["ffn_active"] / tot["ffn_calls"]
         added_per_call = tot["added"] / tot["steps"]
-        hint = 0 if args.no_hint else int(0.9 * rows_per_call)   # launch geometry only: 90 % of the mean rows in use
+        hint = 0 if args.no_hint else int(1.15 * rows_per_call)  # launch geometry only: a wave for every row of nearly every step
         lay0.set_expected_rows(hint)
 
         progress("validation pass done; capturing and timing the token stream")
