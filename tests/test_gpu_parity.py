@@ -95,9 +95,9 @@ def test_c4_llama_shape_gated_batch8():
     """Eight independent streams share one cache: step mask = OR of the eight masks."""
     w = wl.WORKLOADS["C4b8"]
     L = wl.cached_layer("C4")            # same layer as the batch-1 run
-    X = wl.make_batch_inputs(w, tokens=10)
-    stats = run_stream(w, L, X, check_every=3)
-    run_stream(w, L, X, check_every=3, api="step")
+    X = wl.make_batch_inputs(w, tokens=20)
+    stats = run_stream(w, L, X, check_every=5)
+    run_stream(w, L, X, check_every=5, api="step")
     print("C4b8 max rel-L2 %.2e, rows %.0f" % (max(s["err"] for s in stats), np.mean([s["n"] for s in stats[4:]])))
 
 
@@ -493,7 +493,7 @@ def test_n1_dynamic_window_at_opt_shape():
     from tests.harness import GpuLayer, compare_step
     w = wl.WORKLOADS["N1"]
     L = wl.make_layer(w)
-    X = wl.make_inputs(w, tokens=16)
+    X = wl.make_inputs(w, tokens=48)
     gpu = GpuLayer(w, L)
     ora = O.OracleLayer(w.d_model, w.d_ffn, w.window_k, w.capacity_rows, w.glu, L.A, L.B, L.c, L.theta, L.b,
                         L.bundles, shrink=True)
@@ -632,6 +632,35 @@ def test_dynamic_window_with_speculative_passes(k, dtype, d_model, glu, cap, api
     assert st["error"] == lif.LIF_CAPACITY and st["num_used"] == 0 and st["step"] == 0 and st["window_len"] == 0
 
 
+def test_n2_speculative_passes_at_opt_shape():
+    """The speculative workload bench.py can run (OPT shape; passes of 5 consecutive tokens, 4 kept, the next pass starts
+    after the kept ones), in its launch configuration (lif_step_tokens)."""
+    from tests.harness import GpuLayer, rel_l2, max_abs_excess, REL_L2_TOL, MAX_ABS_TOL
+    w = wl.WORKLOADS["N2"]
+    L = wl.cached_layer("C2")                               # N2 runs on the C2 layer
+    X = wl.make_inputs(w, tokens=4 * 16 + 5)
+    gpu = GpuLayer(w, L)
+    lay = gpu.layer
+    ora = make_oracle(w, L)
+    for p in range(16):
+        xb = X[p * w.spec_keep:p * w.spec_keep + w.batch]
+        ref = ora.step_tokens(xb, w.spec_keep)
+        lay.step_tokens(gpu.upload_x(xb), gpu.y, w.batch, w.spec_keep)
+        na, nr = int(lay.n_added.item()), int(lay.n_removed.item())
+        assert lay.added[:na].cpu().numpy().tolist() == ref["added"].tolist(), f"pass {p}"
+        assert lay.removed[:nr].cpu().numpy().tolist() == ref["removed"].tolist(), f"pass {p}"
+        n = ref["num_used"]
+        st = lay.state()
+        assert st["error"] == 0 and st["num_used"] == n and st["window_len"] == len(ora.window.masks)
+        assert (lay.masks[:w.batch].cpu().numpy() == O.pack_mask(ref["masks"])).all()
+        if p % 4 == 3:
+            assert (lay.pointers[:n].cpu().numpy() == ora.cache.pointers[:n]).all()
+            assert lay.matrix[:n].cpu().numpy().tobytes() == ora.cache.matrix[:n].tobytes()
+        y = gpu.y[:w.batch].cpu().numpy()
+        assert rel_l2(y, ref["y"]) <= REL_L2_TOL and max_abs_excess(y, ref["y"])[0] <= MAX_ABS_TOL
+    assert lay.counters()["h2d_bytes"] == ora.bytes_loaded and ora.min_margin > 1e-9 and n > 1000
+
+
 # ----------------------------------------------------------------------------- resident gate as predictor
 @pytest.mark.parametrize("api", ["calls", "step"])
 @pytest.mark.parametrize("ffn_mode", [0, 1])
@@ -657,7 +686,7 @@ def test_n4_llama_shape_gate_predictor():
     """Llama-2-7B FFN shape with the gate resident, the launch configuration bench.py times for N4."""
     w = wl.WORKLOADS["N4"]
     L = wl.cached_layer("N4")
-    X = wl.make_inputs(w, tokens=32)
+    X = wl.make_inputs(w, tokens=64)
     stats = run_stream(w, L, X, check_every=8, api="step")
     print("N4 max rel-L2 %.2e, rows %.0f" % (max(s["err"] for s in stats), np.mean([s["n"] for s in stats[10:]])))
 
