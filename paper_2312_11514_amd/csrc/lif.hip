@@ -301,21 +301,30 @@ bool mfma_path(const lif_config& c, int batch) {
     return c.dtype == LIF_F16 && batch > 1 && c.d_model % 32 == 0;
 }
 
+// 16-row tiles a row-count hint covers (at least one, at most all)
+int mfma_hint_tiles(const lif_layer* L) {
+    const int tiles = (L->cfg.capacity_rows + 15) / 16;
+    return std::max(1, std::min(tiles, (L->expected_rows + 15) / 16));
+}
+
 template <int MODE>
 void launch_ffn_up_mfma(lif_layer* L, const void* x, int batch, float* h, hipStream_t s) {
     const lif_config& c = L->cfg;
     constexpr int W = (MODE == kRowsChanged) ? kMfmaWavesFix : kMfmaWaves;
     // the rows a load wrote are few: a small grid strides over their tiles
     const int tiles = (c.capacity_rows + 15) / 16;
-    const int grid = (MODE == kRowsChanged) ? std::min(tiles, 64) : tiles;
+    // all rows: with a row-count hint the grid is sized to it (a workgroup strides on if more rows are in use)
+    // and every workgroup asks for its first rows before the count arrives
+    const int spec = (MODE == kRowsAll && L->expected_rows > 0) ? 1 : 0;
+    const int grid = (MODE == kRowsChanged) ? std::min(tiles, 64) : spec ? mfma_hint_tiles(L) : tiles;
     if (c.glu)
         hipLaunchKernelGGL((k_ffn_up_mfma<true, MODE, W>), dim3(grid), dim3(W * 64), 0, s,
                            (const _Float16*)L->buf.matrix, L->buf.bias, (const _Float16*)x, h, c.d_model, batch,
-                           c.capacity_rows, L->row_elems, L->move_dst, L->buf.pointers, L->gact, c.d_ffn, L->st);
+                           c.capacity_rows, L->row_elems, L->move_dst, L->buf.pointers, L->gact, c.d_ffn, spec, L->st);
     else
         hipLaunchKernelGGL((k_ffn_up_mfma<false, MODE, W>), dim3(grid), dim3(W * 64), 0, s,
                            (const _Float16*)L->buf.matrix, L->buf.bias, (const _Float16*)x, h, c.d_model, batch,
-                           c.capacity_rows, L->row_elems, L->move_dst, L->buf.pointers, L->gact, c.d_ffn, L->st);
+                           c.capacity_rows, L->row_elems, L->move_dst, L->buf.pointers, L->gact, c.d_ffn, spec, L->st);
 }
 
 // batch > 1, fp16: bundle load next to the activation stage of the surviving rows, then the rows the load wrote
@@ -323,16 +332,17 @@ void launch_load_up_mfma(lif_layer* L, const void* x, int batch, const int32_t* 
     const lif_config& c = L->cfg;
     const int tiles = (c.capacity_rows + 15) / 16;
     static_assert(kMfmaWaves == 4, "the fused kernel runs both roles with 256 threads");
+    const int spec_tiles = L->expected_rows > 0 ? mfma_hint_tiles(L) : 0;
     if (c.glu)
         hipLaunchKernelGGL((k_load_up_mfma<true>), dim3(kLoadGrid + tiles), dim3(256), 0, s, (_Float16*)L->buf.matrix,
                            L->buf.pointers, L->buf.bias, L->host, L->buf.b, added, L->move_dst, L->row_bytes,
-                           c.d_ffn, (const _Float16*)x, L->h, c.d_model, batch, c.capacity_rows, kLoadGrid, L->gact,
-                           L->st);
+                           c.d_ffn, (const _Float16*)x, L->h, c.d_model, batch, c.capacity_rows, kLoadGrid, spec_tiles,
+                           L->gact, L->st);
     else
         hipLaunchKernelGGL((k_load_up_mfma<false>), dim3(kLoadGrid + tiles), dim3(256), 0, s, (_Float16*)L->buf.matrix,
                            L->buf.pointers, L->buf.bias, L->host, L->buf.b, added, L->move_dst, L->row_bytes,
-                           c.d_ffn, (const _Float16*)x, L->h, c.d_model, batch, c.capacity_rows, kLoadGrid, L->gact,
-                           L->st);
+                           c.d_ffn, (const _Float16*)x, L->h, c.d_model, batch, c.capacity_rows, kLoadGrid, spec_tiles,
+                           L->gact, L->st);
 }
 
 // LDS a workgroup of k_predict_mask<T, BT> needs for a predictor of rank r: its static arrays plus BT * r doubles.

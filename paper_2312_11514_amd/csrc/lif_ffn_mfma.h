@@ -145,20 +145,178 @@ __device__ __forceinline__ bool ffn_up_mfma_tile(const _Float16* __restrict__ ma
     return true;
 }
 
+// The same tile for 4 waves with the rows read row-contiguously and staged in LDS (kRowsAll and kRowsKept only).
+// The fragment pattern above asks for 64 bytes of 16 different rows per wave instruction; measured at the
+// Llama-2 shape with 8700 rows in use that pattern streams at 4.2 TB/s where whole 256-byte pieces of a row
+// (4 rows per wave instruction) reach 5.4 TB/s.  Here a wave reads a stage of kStageSteps k-steps of its 16 rows
+// that way, writes it to its own LDS area (rows padded by 16 bytes: the b128 reads of 16 lanes then fall on 16
+// distinct bank groups) and reads the fragments back from there; the registers are refilled with the next stage
+// as soon as they are written out, across part boundaries too.  The MFMA operands, the k order inside a part and
+// the order in which the parts are added are those of ffn_up_mfma_tile, so both give the same bits.
+// `spec`: the first stage is requested before the row count arrives (the addresses of slots [0, capacity) are
+// always valid); the host sets it for the tiles a row-count hint covers.
+constexpr int kStageSteps = 4;                           // k-steps per stage: 256 bytes of a row
+constexpr int kStagePitch = kStageSteps * 64 + 16;       // bytes between the staged rows of a wave
+
+template <bool GLU>
+struct StageRegs {
+    f16x8 u[4], g[GLU ? 4 : 1];
+};
+
+template <bool GLU, int MODE>
+__device__ __forceinline__ bool ffn_up_mfma_tile_staged(const _Float16* __restrict__ matrix,
+                                                        const float* __restrict__ bias,
+                                                        const _Float16* __restrict__ x, float* __restrict__ h, int d,
+                                                        int batch, int capacity, size_t row_elems, int tile,
+                                                        bool spec, const int32_t* __restrict__ pointers,
+                                                        const float* __restrict__ gact, int gact_n,
+                                                        const DevState* __restrict__ st) {
+    static_assert(MODE == kRowsAll || MODE == kRowsKept, "list entry e must be slot e");
+    static_assert(kMfmaWaves == 4 && kStageSteps == 4, "a wave instruction covers 4 rows x 16 units of 16 bytes");
+    constexpr int NG = GLU ? 2 : 1;
+    constexpr int PPW = kMfmaParts / kMfmaWaves;
+    constexpr int kStageBytes = kMfmaWaves * NG * 16 * kStagePitch;
+    constexpr int kRedBytes = NG * kMfmaParts * 64 * 4 * (int)sizeof(float);
+    // the staging areas during the k loop, the table of partial tiles after it
+    __shared__ __align__(16) unsigned char lds[kStageBytes > kRedBytes ? kStageBytes : kRedBytes];
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int i = lane & 15, q = lane >> 4;
+    const int s0 = tile * 16;
+    // loader view of a lane: instruction j reads unit i (16 bytes) of tile row 4 j + q
+    const _Float16* lrow[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) lrow[j] = matrix + (size_t)min(s0 + 4 * j + q, capacity - 1) * row_elems;
+    const int nks = d >> 5;
+    const int per = (nks + kMfmaParts - 1) / kMfmaParts;
+    const int S = (per + kStageSteps - 1) / kStageSteps;      // stages per part
+    StageRegs<GLU> R;
+    // stage s of a part: k-steps [part * per + s * kStageSteps, + kStageSteps), cut at the end of the part
+    auto issue = [&](int part, int s) {
+        const int ks0 = part * per + s * kStageSteps, ks_end = min(nks, part * per + per);
+        const bool in = ks0 + (i >> 2) < ks_end;
+        const int off = (ks0 << 5) + (i << 3);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            R.u[j] = in ? *reinterpret_cast<const f16x8*>(lrow[j] + (GLU ? d : 0) + off) : f16x8(0);
+            if (GLU) R.g[j] = in ? *reinterpret_cast<const f16x8*>(lrow[j] + off) : f16x8(0);
+        }
+    };
+    if (spec) issue(w * PPW, 0);
+    const int err = st->error;
+    const int n = (MODE == kRowsAll) ? st->num_used : st->n_base;
+    if (err || s0 >= n) return false;                             // uniform
+    if (!spec) issue(w * PPW, 0);
+
+    int srow = s0 + i;
+    if (srow >= n) srow = -1;
+    int orow[4];
+    float obias[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        orow[r] = __shfl(srow, 4 * q + r, kWave);
+        obias[r] = 0.f;
+        if (w == 0 && orow[r] >= 0) {
+            if (GLU || !gact) obias[r] = bias[orow[r]];
+            else if (i < batch) obias[r] = gact[(size_t)i * gact_n + min(max(pointers[orow[r]], 0), gact_n - 1)];
+        }
+    }
+    const bool xok = i < batch;
+    const _Float16* xrow = x + (size_t)(xok ? i : 0) * d;
+    unsigned char* mine = lds + w * (NG * 16 * kStagePitch);
+    float (*red)[kMfmaParts][64][4] = reinterpret_cast<float (*)[kMfmaParts][64][4]>(lds);
+
+    f32x4 cu[PPW], cg[PPW];
+#pragma unroll
+    for (int pp = 0; pp < PPW; ++pp) {
+        const int part = w * PPW + pp;
+        const int ks_end = min(nks, part * per + per);
+        f32x4 au = {0.f, 0.f, 0.f, 0.f}, ag = {0.f, 0.f, 0.f, 0.f};
+        for (int s = 0; s < S; ++s) {
+            const int ks0 = part * per + s * kStageSteps;
+            f16x8 xf[kStageSteps];
+#pragma unroll
+            for (int u = 0; u < kStageSteps; ++u)
+                xf[u] = (ks0 + u < ks_end && xok)
+                            ? *reinterpret_cast<const f16x8*>(xrow + ((ks0 + u) << 5) + (q << 3)) : f16x8(0);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                *reinterpret_cast<f16x8*>(mine + (4 * j + q) * kStagePitch + i * 16) = R.u[j];
+                if (GLU) *reinterpret_cast<f16x8*>(mine + (16 + 4 * j + q) * kStagePitch + i * 16) = R.g[j];
+            }
+            if (s + 1 < S) issue(part, s + 1);
+            else if (pp + 1 < PPW) issue(part + 1, 0);
+            // the area is this wave's alone and a wave's LDS operations complete in order: no barrier instruction
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int u = 0; u < kStageSteps; ++u) {
+                const f16x8 uf = *reinterpret_cast<const f16x8*>(mine + i * kStagePitch + (u * 4 + q) * 16);
+                au = __builtin_amdgcn_mfma_f32_16x16x32_f16(uf, xf[u], au, 0, 0, 0);
+                if (GLU) {
+                    const f16x8 gf = *reinterpret_cast<const f16x8*>(mine + (16 + i) * kStagePitch + (u * 4 + q) * 16);
+                    ag = __builtin_amdgcn_mfma_f32_16x16x32_f16(gf, xf[u], ag, 0, 0, 0);
+                }
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
+        cu[pp] = au;
+        cg[pp] = ag;
+    }
+    __syncthreads();                                              // every wave is done with its staging area
+#pragma unroll
+    for (int pp = 0; pp < PPW; ++pp)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            red[0][w * PPW + pp][lane][r] = cu[pp][r];
+            if (GLU) red[NG - 1][w * PPW + pp][lane][r] = cg[pp][r];
+        }
+    __syncthreads();
+    if (w == 0 && xok) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int row = orow[r];
+            if (row >= 0) {
+                float su = 0.f;
+#pragma unroll
+                for (int ww = 0; ww < kMfmaParts; ++ww) su += red[0][ww][lane][r];
+                const float bs = obias[r];
+                float act;
+                if (GLU) {
+                    float sg = 0.f;
+#pragma unroll
+                    for (int ww = 0; ww < kMfmaParts; ++ww) sg += red[NG - 1][ww][lane][r];
+                    act = fmaxf(sg + bs, 0.f) * su;
+                } else if (gact) {
+                    act = bs * su;
+                } else {
+                    act = fmaxf(su + bs, 0.f);
+                }
+                h[(size_t)i * capacity + row] = act;
+            }
+        }
+    }
+    return true;
+}
+
 template <bool GLU, int MODE, int WAVES>
-__global__ __launch_bounds__(WAVES * 64) void k_ffn_up_mfma(const _Float16* __restrict__ matrix,
+__global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 3 : 1) void k_ffn_up_mfma(const _Float16* __restrict__ matrix,
                                                                  const float* __restrict__ bias,
                                                                  const _Float16* __restrict__ x, float* __restrict__ h,
                                                                  int d, int batch, int capacity, size_t row_elems,
                                                                  const int32_t* __restrict__ move_dst,
                                                                  const int32_t* __restrict__ pointers,
                                                                  const float* __restrict__ gact, int gact_n,
-                                                                 const DevState* __restrict__ st) {
+                                                                 int spec, const DevState* __restrict__ st) {
+    // `spec`: the grid was sized from a row-count hint, the first tile of a workgroup is requested ahead of the state
     // grid-stride over tiles (the grid may be smaller than the tile count; LDS is reused between tiles)
     for (int tile = blockIdx.x;; tile += gridDim.x) {
-        if (!ffn_up_mfma_tile<GLU, MODE, WAVES>(matrix, bias, x, h, d, batch, capacity, row_elems, move_dst, tile,
-                                                pointers, gact, gact_n, st))
-            break;
+        bool more;
+        if constexpr (MODE == kRowsChanged)
+            more = ffn_up_mfma_tile<GLU, MODE, WAVES>(matrix, bias, x, h, d, batch, capacity, row_elems, move_dst, tile,
+                                                      pointers, gact, gact_n, st);
+        else
+            more = ffn_up_mfma_tile_staged<GLU, MODE>(matrix, bias, x, h, d, batch, capacity, row_elems, tile,
+                                                      spec != 0 && tile == (int)blockIdx.x, pointers, gact, gact_n, st);
+        if (!more) break;
         __syncthreads();
     }
 }

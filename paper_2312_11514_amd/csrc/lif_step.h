@@ -263,7 +263,7 @@ __global__ __launch_bounds__(256) void k_load_up_mfma(_Float16* __restrict__ mat
                                                       const float* __restrict__ b, const int32_t* __restrict__ added,
                                                       const int32_t* __restrict__ move_dst, size_t row_bytes, int F,
                                                       const _Float16* __restrict__ x, float* __restrict__ h, int d,
-                                                      int batch, int capacity, int load_wgs,
+                                                      int batch, int capacity, int load_wgs, int spec_tiles,
                                                       const float* __restrict__ gact, DevState* st) {
     if ((int)blockIdx.x < load_wgs)
         load_rows_role(reinterpret_cast<char*>(matrix), pointers, bias, host, b, added, move_dst, row_bytes, F,
@@ -271,8 +271,10 @@ __global__ __launch_bounds__(256) void k_load_up_mfma(_Float16* __restrict__ mat
     else
         // (with the gate predictor a hole's pointer may change under this role: the lookup is clamped and the
         // slot's activation is recomputed by the pass over the written slots)
-        ffn_up_mfma_tile<GLU, kRowsKept, 4>(matrix, bias, x, h, d, batch, capacity, row_bytes / sizeof(_Float16), move_dst,
-                                         blockIdx.x - load_wgs, pointers, gact, F, st);
+        // (tiles below spec_tiles - those a row-count hint covers - ask for their first rows ahead of the state)
+        ffn_up_mfma_tile_staged<GLU, kRowsKept>(matrix, bias, x, h, d, batch, capacity, row_bytes / sizeof(_Float16),
+                                                blockIdx.x - load_wgs, (int)blockIdx.x - load_wgs < spec_tiles, pointers,
+                                                gact, F, st);
 }
 
 }  // namespace lif
