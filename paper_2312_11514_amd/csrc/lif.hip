@@ -310,7 +310,7 @@ int mfma_hint_tiles(const lif_layer* L) {
 template <int MODE>
 void launch_ffn_up_mfma(lif_layer* L, const void* x, int batch, float* h, hipStream_t s) {
     const lif_config& c = L->cfg;
-    constexpr int W = (MODE == kRowsChanged) ? kMfmaWavesFix : kMfmaWaves;
+    constexpr int W = (MODE == kRowsChanged) ? kMfmaWavesFix : kMfmaWavesAll;
     // the rows a load wrote are few: a small grid strides over their tiles
     const int tiles = (c.capacity_rows + 15) / 16;
     // all rows: with a row-count hint the grid is sized to it (a workgroup strides on if more rows are in use)

@@ -26,6 +26,28 @@ constexpr int kMfmaWaves = 4;       // waves per 16-row tile (each takes a conti
 constexpr int kMfmaWavesFix = 16; // ... for the short pass over the rows a load wrote: few tiles, so a
                                                   // tile is spread over 16 waves (one round of loads each)
 
+// How the 16 partial tiles of a row tile are added: as a balanced binary tree in part order,
+//   ((p0 + p1) + (p2 + p3)) + ((p4 + p5) + (p6 + p7)) + ...
+// so a wave that owns 1, 2 or 4 consecutive parts adds its own subtree in registers and the subtrees of the waves are
+// added the same way: the result does not depend on how many waves share a tile.
+// tree_push: part number pp (0, 1, 2, ... in order) of a wave arrives; lvl[b] holds a finished subtree of 2^b parts.
+template <int PP>
+__device__ __forceinline__ void tree_push(f32x4 (&lvl)[3], f32x4 v) {
+    static_assert(PP >= 0 && PP < 4, "at most four parts per wave");
+    if constexpr ((PP & 1) == 0) lvl[0] = v;                       // p0, p2
+    else if constexpr ((PP & 2) == 0) lvl[1] = lvl[0] + v;         // p0 + p1
+    else lvl[2] = lvl[1] + (lvl[0] + v);                           // (p0 + p1) + (p2 + p3)
+}
+// tree over the WAVES subtrees of one output, in wave order
+template <int WAVES>
+__device__ __forceinline__ float tree_sum(float (&v)[WAVES]) {
+#pragma unroll
+    for (int stride = 1; stride < WAVES; stride *= 2)
+#pragma unroll
+        for (int k = 0; k < WAVES; k += 2 * stride) v[k] = v[k] + v[k + stride];
+    return v[0];
+}
+
 // Which rows a launch of the MFMA activation stage covers.
 enum MfmaRows {
     kRowsAll = 0,     // slots [0, num_used)
@@ -47,7 +69,7 @@ __device__ __forceinline__ bool ffn_up_mfma_tile(const _Float16* __restrict__ ma
                                                  const int32_t* __restrict__ move_dst, int tile,
                                                  const int32_t* __restrict__ pointers, const float* __restrict__ gact,
                                                  int gact_n, const DevState* __restrict__ st) {
-    __shared__ float red[GLU ? 2 : 1][kMfmaParts][64][4];
+    __shared__ float red[GLU ? 2 : 1][WAVES][64][4];
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int i = lane & 15, q = lane >> 4;
     const int s0 = tile * 16;
@@ -85,10 +107,12 @@ __device__ __forceinline__ bool ffn_up_mfma_tile(const _Float16* __restrict__ ma
     const int nks = d >> 5;
 
     // The k-steps are cut into kMfmaParts contiguous parts, each accumulated from zero; wave w takes the parts
-    // w * PPW .. w * PPW + PPW - 1.  The parts are added in order below, so the result does not depend on
-    // how many waves share a tile.
+    // w * PPW .. w * PPW + PPW - 1 and adds them as its subtree (tree_push).
     constexpr int PPW = kMfmaParts / WAVES;
+    constexpr int kTop = PPW == 1 ? 0 : PPW == 2 ? 1 : 2;
+    static_assert(PPW == 1 || PPW == 2 || PPW == 4, "a wave owns a subtree of the parts");
     const int per = (nks + kMfmaParts - 1) / kMfmaParts;
+    f32x4 lu[3], lg[3];
 #pragma unroll
     for (int pp = 0; pp < PPW; ++pp) {
         const int part = w * PPW + pp;
@@ -111,11 +135,15 @@ __device__ __forceinline__ bool ffn_up_mfma_tile(const _Float16* __restrict__ ma
                 if (GLU) cg = __builtin_amdgcn_mfma_f32_16x16x32_f16(gf[u], xf[u], cg, 0, 0, 0);
             }
         }
+        if (pp == 0) { tree_push<0>(lu, cu); if (GLU) tree_push<0>(lg, cg); }
+        if (pp == 1) { tree_push<1>(lu, cu); if (GLU) tree_push<1>(lg, cg); }
+        if (pp == 2) { tree_push<2>(lu, cu); if (GLU) tree_push<2>(lg, cg); }
+        if (pp == 3) { tree_push<3>(lu, cu); if (GLU) tree_push<3>(lg, cg); }
+    }
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            red[0][part][lane][r] = cu[r];
-            if (GLU) red[GLU ? 1 : 0][part][lane][r] = cg[r];
-        }
+    for (int r = 0; r < 4; ++r) {
+        red[0][w][lane][r] = lu[kTop][r];
+        if (GLU) red[GLU ? 1 : 0][w][lane][r] = lg[kTop][r];
     }
     __syncthreads();
     if (w == 0 && xok) {
@@ -123,15 +151,16 @@ __device__ __forceinline__ bool ffn_up_mfma_tile(const _Float16* __restrict__ ma
         for (int r = 0; r < 4; ++r) {
             const int row = orow[r];
             if (row >= 0) {
-                float su = 0.f;
+                float v[WAVES];
 #pragma unroll
-                for (int ww = 0; ww < kMfmaParts; ++ww) su += red[0][ww][lane][r];
+                for (int ww = 0; ww < WAVES; ++ww) v[ww] = red[0][ww][lane][r];
+                const float su = tree_sum<WAVES>(v);
                 const float bs = obias[r];
                 float act;
                 if (GLU) {
-                    float sg = 0.f;
 #pragma unroll
-                    for (int ww = 0; ww < kMfmaParts; ++ww) sg += red[GLU ? 1 : 0][ww][lane][r];
+                    for (int ww = 0; ww < WAVES; ++ww) v[ww] = red[GLU ? 1 : 0][ww][lane][r];
+                    const float sg = tree_sum<WAVES>(v);
                     act = fmaxf(sg + bs, 0.f) * su;
                 } else if (gact) {
                     act = bs * su;                    // bs = this token's gate activation of the row's neuron
@@ -145,25 +174,28 @@ __device__ __forceinline__ bool ffn_up_mfma_tile(const _Float16* __restrict__ ma
     return true;
 }
 
-// The same tile for 4 waves with the rows read row-contiguously and staged in LDS (kRowsAll and kRowsKept only).
+// The same tile with the rows read row-contiguously and staged in LDS (kRowsAll and kRowsKept only).
 // The fragment pattern above asks for 64 bytes of 16 different rows per wave instruction; measured at the
 // Llama-2 shape with 8700 rows in use that pattern streams at 4.2 TB/s where whole 256-byte pieces of a row
 // (4 rows per wave instruction) reach 5.4 TB/s.  Here a wave reads a stage of kStageSteps k-steps of its 16 rows
-// that way, writes it to its own LDS area (rows padded by 16 bytes: the b128 reads of 16 lanes then fall on 16
-// distinct bank groups) and reads the fragments back from there; the registers are refilled with the next stage
-// as soon as they are written out, across part boundaries too.  The MFMA operands, the k order inside a part and
-// the order in which the parts are added are those of ffn_up_mfma_tile, so both give the same bits.
+// that way, passes the up rows and then the gate rows through its own LDS area (rows padded by 16 bytes: the
+// b128 reads of 16 lanes then fall on 16 distinct bank groups) and reads the fragments back from there; the
+// registers are refilled with the next stage as soon as they are written out, across part boundaries too.
+// The MFMA operands, the k order inside a part and the order in which the parts are added are those of
+// ffn_up_mfma_tile, so every number of waves and both functions give the same bits.  With 8 waves a tile takes
+// half the dependent stages per wave: 7.7 us against 10 us at 1400 rows, 26 us against 27 us at 8700.
 // `spec`: the first stage is requested before the row count arrives (the addresses of slots [0, capacity) are
 // always valid); the host sets it for the tiles a row-count hint covers.
 constexpr int kStageSteps = 4;                           // k-steps per stage: 256 bytes of a row
 constexpr int kStagePitch = kStageSteps * 64 + 16;       // bytes between the staged rows of a wave
+constexpr int kMfmaWavesAll = 8;                         // waves per tile of the stand-alone pass over all rows
 
 template <bool GLU>
 struct StageRegs {
     f16x8 u[4], g[GLU ? 4 : 1];
 };
 
-template <bool GLU, int MODE>
+template <bool GLU, int MODE, int WAVES>
 __device__ __forceinline__ bool ffn_up_mfma_tile_staged(const _Float16* __restrict__ matrix,
                                                         const float* __restrict__ bias,
                                                         const _Float16* __restrict__ x, float* __restrict__ h, int d,
@@ -172,20 +204,24 @@ __device__ __forceinline__ bool ffn_up_mfma_tile_staged(const _Float16* __restri
                                                         const float* __restrict__ gact, int gact_n,
                                                         const DevState* __restrict__ st) {
     static_assert(MODE == kRowsAll || MODE == kRowsKept, "list entry e must be slot e");
-    static_assert(kMfmaWaves == 4 && kStageSteps == 4, "a wave instruction covers 4 rows x 16 units of 16 bytes");
+    static_assert(kStageSteps == 4, "a wave instruction covers 4 rows x 16 units of 16 bytes");
+    static_assert(kMfmaParts % WAVES == 0, "whole parts per wave");
     constexpr int NG = GLU ? 2 : 1;
-    constexpr int PPW = kMfmaParts / kMfmaWaves;
-    constexpr int kStageBytes = kMfmaWaves * NG * 16 * kStagePitch;
-    constexpr int kRedBytes = NG * kMfmaParts * 64 * 4 * (int)sizeof(float);
-    // the staging areas during the k loop, the table of partial tiles after it
-    __shared__ __align__(16) unsigned char lds[kStageBytes > kRedBytes ? kStageBytes : kRedBytes];
+    constexpr int PPW = kMfmaParts / WAVES;
+    constexpr int kTop = PPW == 1 ? 0 : PPW == 2 ? 1 : 2;
+    static_assert(PPW == 1 || PPW == 2 || PPW == 4, "a wave owns a subtree of the parts");
+    __shared__ __align__(16) unsigned char lds[WAVES * 16 * kStagePitch];      // one staging area per wave
+    __shared__ float red[NG][WAVES][64][4];                                    // the waves' subtrees
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int i = lane & 15, q = lane >> 4;
     const int s0 = tile * 16;
     // loader view of a lane: instruction j reads unit i (16 bytes) of tile row 4 j + q
-    const _Float16* lrow[4];
+    // (kept as 32-bit offsets in units of 16 bytes: row_elems is a multiple of 8 when d is a multiple of 32)
+    const f16x8* mat8 = reinterpret_cast<const f16x8*>(matrix);
+    const unsigned row8 = (unsigned)(row_elems >> 3), d8 = (unsigned)(d >> 3);
+    unsigned lrow[4];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) lrow[j] = matrix + (size_t)min(s0 + 4 * j + q, capacity - 1) * row_elems;
+    for (int j = 0; j < 4; ++j) lrow[j] = (unsigned)min(s0 + 4 * j + q, capacity - 1) * row8;
     const int nks = d >> 5;
     const int per = (nks + kMfmaParts - 1) / kMfmaParts;
     const int S = (per + kStageSteps - 1) / kStageSteps;      // stages per part
@@ -194,11 +230,11 @@ __device__ __forceinline__ bool ffn_up_mfma_tile_staged(const _Float16* __restri
     auto issue = [&](int part, int s) {
         const int ks0 = part * per + s * kStageSteps, ks_end = min(nks, part * per + per);
         const bool in = ks0 + (i >> 2) < ks_end;
-        const int off = (ks0 << 5) + (i << 3);
+        const unsigned off = (unsigned)(ks0 << 2) + (unsigned)i;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            R.u[j] = in ? *reinterpret_cast<const f16x8*>(lrow[j] + (GLU ? d : 0) + off) : f16x8(0);
-            if (GLU) R.g[j] = in ? *reinterpret_cast<const f16x8*>(lrow[j] + off) : f16x8(0);
+            R.u[j] = in ? mat8[(size_t)(lrow[j] + (GLU ? d8 : 0u) + off)] : f16x8(0);
+            if (GLU) R.g[j] = in ? mat8[(size_t)(lrow[j] + off)] : f16x8(0);
         }
     };
     if (spec) issue(w * PPW, 0);
@@ -207,25 +243,25 @@ __device__ __forceinline__ bool ffn_up_mfma_tile_staged(const _Float16* __restri
     if (err || s0 >= n) return false;                             // uniform
     if (!spec) issue(w * PPW, 0);
 
-    int srow = s0 + i;
-    if (srow >= n) srow = -1;
-    int orow[4];
+    // the lane that finishes D rows 4q .. 4q + 3 for token i asks for their biases now, ahead of the row loads
     float obias[4];
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-        orow[r] = __shfl(srow, 4 * q + r, kWave);
+        const int row = s0 + 4 * q + r;
         obias[r] = 0.f;
-        if (w == 0 && orow[r] >= 0) {
-            if (GLU || !gact) obias[r] = bias[orow[r]];
-            else if (i < batch) obias[r] = gact[(size_t)i * gact_n + min(max(pointers[orow[r]], 0), gact_n - 1)];
+        if (w == 0 && row < n) {
+            if (GLU || !gact) obias[r] = bias[row];
+            else if (i < batch) obias[r] = gact[(size_t)i * gact_n + min(max(pointers[row], 0), gact_n - 1)];
         }
     }
     const bool xok = i < batch;
     const _Float16* xrow = x + (size_t)(xok ? i : 0) * d;
-    unsigned char* mine = lds + w * (NG * 16 * kStagePitch);
-    float (*red)[kMfmaParts][64][4] = reinterpret_cast<float (*)[kMfmaParts][64][4]>(lds);
+    // The area is this wave's alone and a wave's LDS operations complete in order, so the steps below need no
+    // barrier instruction (wave_barrier only keeps the compiler from moving LDS accesses across it).
+    unsigned char* wr = lds + w * (16 * kStagePitch) + q * kStagePitch + i * 16;      // + 4 j rows for instruction j
+    const unsigned char* rd = lds + w * (16 * kStagePitch) + i * kStagePitch + q * 16; // + 64 bytes per k-step
 
-    f32x4 cu[PPW], cg[PPW];
+    f32x4 lu[3], lg[3];
 #pragma unroll
     for (int pp = 0; pp < PPW; ++pp) {
         const int part = w * PPW + pp;
@@ -239,51 +275,56 @@ __device__ __forceinline__ bool ffn_up_mfma_tile_staged(const _Float16* __restri
                 xf[u] = (ks0 + u < ks_end && xok)
                             ? *reinterpret_cast<const f16x8*>(xrow + ((ks0 + u) << 5) + (q << 3)) : f16x8(0);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                *reinterpret_cast<f16x8*>(mine + (4 * j + q) * kStagePitch + i * 16) = R.u[j];
-                if (GLU) *reinterpret_cast<f16x8*>(mine + (16 + 4 * j + q) * kStagePitch + i * 16) = R.g[j];
-            }
-            if (s + 1 < S) issue(part, s + 1);
-            else if (pp + 1 < PPW) issue(part + 1, 0);
-            // the area is this wave's alone and a wave's LDS operations complete in order: no barrier instruction
+            for (int j = 0; j < 4; ++j) *reinterpret_cast<f16x8*>(wr + j * 4 * kStagePitch) = R.u[j];
             __builtin_amdgcn_wave_barrier();
 #pragma unroll
             for (int u = 0; u < kStageSteps; ++u) {
-                const f16x8 uf = *reinterpret_cast<const f16x8*>(mine + i * kStagePitch + (u * 4 + q) * 16);
+                const f16x8 uf = *reinterpret_cast<const f16x8*>(rd + u * 64);
                 au = __builtin_amdgcn_mfma_f32_16x16x32_f16(uf, xf[u], au, 0, 0, 0);
-                if (GLU) {
-                    const f16x8 gf = *reinterpret_cast<const f16x8*>(mine + (16 + i) * kStagePitch + (u * 4 + q) * 16);
+            }
+            __builtin_amdgcn_wave_barrier();
+            if (GLU) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) *reinterpret_cast<f16x8*>(wr + j * 4 * kStagePitch) = R.g[j];
+            }
+            if (s + 1 < S) issue(part, s + 1);
+            else if (pp + 1 < PPW) issue(part + 1, 0);
+            __builtin_amdgcn_wave_barrier();
+            if (GLU) {
+#pragma unroll
+                for (int u = 0; u < kStageSteps; ++u) {
+                    const f16x8 gf = *reinterpret_cast<const f16x8*>(rd + u * 64);
                     ag = __builtin_amdgcn_mfma_f32_16x16x32_f16(gf, xf[u], ag, 0, 0, 0);
                 }
             }
             __builtin_amdgcn_wave_barrier();
         }
-        cu[pp] = au;
-        cg[pp] = ag;
+        if (pp == 0) { tree_push<0>(lu, au); if (GLU) tree_push<0>(lg, ag); }
+        if (pp == 1) { tree_push<1>(lu, au); if (GLU) tree_push<1>(lg, ag); }
+        if (pp == 2) { tree_push<2>(lu, au); if (GLU) tree_push<2>(lg, ag); }
+        if (pp == 3) { tree_push<3>(lu, au); if (GLU) tree_push<3>(lg, ag); }
     }
-    __syncthreads();                                              // every wave is done with its staging area
 #pragma unroll
-    for (int pp = 0; pp < PPW; ++pp)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            red[0][w * PPW + pp][lane][r] = cu[pp][r];
-            if (GLU) red[NG - 1][w * PPW + pp][lane][r] = cg[pp][r];
-        }
+    for (int r = 0; r < 4; ++r) {
+        red[0][w][lane][r] = lu[kTop][r];
+        if (GLU) red[NG - 1][w][lane][r] = lg[kTop][r];
+    }
     __syncthreads();
     if (w == 0 && xok) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            const int row = orow[r];
-            if (row >= 0) {
-                float su = 0.f;
+            const int row = s0 + 4 * q + r;
+            if (row < n) {
+                float v[WAVES];
 #pragma unroll
-                for (int ww = 0; ww < kMfmaParts; ++ww) su += red[0][ww][lane][r];
+                for (int ww = 0; ww < WAVES; ++ww) v[ww] = red[0][ww][lane][r];
+                const float su = tree_sum<WAVES>(v);
                 const float bs = obias[r];
                 float act;
                 if (GLU) {
-                    float sg = 0.f;
 #pragma unroll
-                    for (int ww = 0; ww < kMfmaParts; ++ww) sg += red[NG - 1][ww][lane][r];
+                    for (int ww = 0; ww < WAVES; ++ww) v[ww] = red[NG - 1][ww][lane][r];
+                    const float sg = tree_sum<WAVES>(v);
                     act = fmaxf(sg + bs, 0.f) * su;
                 } else if (gact) {
                     act = bs * su;
@@ -298,7 +339,7 @@ __device__ __forceinline__ bool ffn_up_mfma_tile_staged(const _Float16* __restri
 }
 
 template <bool GLU, int MODE, int WAVES>
-__global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 3 : 1) void k_ffn_up_mfma(const _Float16* __restrict__ matrix,
+__global__ __launch_bounds__(WAVES * 64, WAVES == kMfmaWavesAll ? 4 : 1) void k_ffn_up_mfma(const _Float16* __restrict__ matrix,
                                                                  const float* __restrict__ bias,
                                                                  const _Float16* __restrict__ x, float* __restrict__ h,
                                                                  int d, int batch, int capacity, size_t row_elems,
@@ -314,7 +355,7 @@ __global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 3 : 1) void k_ffn_up_mfma(
             more = ffn_up_mfma_tile<GLU, MODE, WAVES>(matrix, bias, x, h, d, batch, capacity, row_elems, move_dst, tile,
                                                       pointers, gact, gact_n, st);
         else
-            more = ffn_up_mfma_tile_staged<GLU, MODE>(matrix, bias, x, h, d, batch, capacity, row_elems, tile,
+            more = ffn_up_mfma_tile_staged<GLU, MODE, WAVES>(matrix, bias, x, h, d, batch, capacity, row_elems, tile,
                                                       spec != 0 && tile == (int)blockIdx.x, pointers, gact, gact_n, st);
         if (!more) break;
         __syncthreads();

@@ -272,7 +272,7 @@ __global__ __launch_bounds__(256) void k_load_up_mfma(_Float16* __restrict__ mat
         // (with the gate predictor a hole's pointer may change under this role: the lookup is clamped and the
         // slot's activation is recomputed by the pass over the written slots)
         // (tiles below spec_tiles - those a row-count hint covers - ask for their first rows ahead of the state)
-        ffn_up_mfma_tile_staged<GLU, kRowsKept>(matrix, bias, x, h, d, batch, capacity, row_bytes / sizeof(_Float16),
+        ffn_up_mfma_tile_staged<GLU, kRowsKept, kMfmaWaves>(matrix, bias, x, h, d, batch, capacity, row_bytes / sizeof(_Float16),
                                                 blockIdx.x - load_wgs, (int)blockIdx.x - load_wgs < spec_tiles, pointers,
                                                 gact, F, st);
 }
