@@ -7,11 +7,13 @@
 #include <cstdio>
 #include <cstring>
 #include <new>
+#include <type_traits>
 #include <vector>
 
 #include "lif_common.h"
 #include "lif_ffn.h"
 #include "lif_ffn_mfma.h"
+#include "lif_ffn_down_mfma.h"
 #include "lif_predict.h"
 #include "lif_step.h"
 #include "lif_window.h"
@@ -253,9 +255,36 @@ void launch_ffn_down_as(lif_layer* L, int batch, void* y, float* h, float* ypart
                            ypart, (T*)y, c.d_model, batch, L->st);
 }
 
+// several tokens, fp16: the down projection on the matrix cores
+template <bool SKIP>
+void launch_ffn_down_mfma(lif_layer* L, int batch, void* y, float* h, float* ypart, hipStream_t s) {
+    const lif_config& c = L->cfg;
+    const int slices = (c.d_model + kDmCols - 1) / kDmCols;
+    const int chunk_rows = down_mfma_chunk_rows(c.capacity_rows);
+    // workgroup rows: enough for the chunks of the expected number of rows (with some slack), else of the
+    // capacity; fewer than the chunks in use is still correct (a workgroup row then takes several chunks)
+    const int rows_hint = L->expected_rows > 0 ? std::min(c.capacity_rows, L->expected_rows + L->expected_rows / 8)
+                                               : c.capacity_rows;
+    const int wg_rows = down_mfma_chunks(rows_hint, chunk_rows);
+    const int down_off = (c.glu ? 2 : 1) * c.d_model;
+    hipLaunchKernelGGL((k_ffn_down_mfma<SKIP, kDmWaves>), dim3(slices, wg_rows), dim3(kDmWaves * 64), 0, s,
+                       (const _Float16*)L->buf.matrix, h, (_Float16*)y, ypart, c.d_model, batch, c.capacity_rows,
+                       L->row_elems, down_off, chunk_rows, L->st);
+    if (wg_rows > 1)
+        hipLaunchKernelGGL(k_ffn_down_mfma_finish, dim3((batch * c.d_model + 255) / 256), dim3(256), 0, s, ypart,
+                           (_Float16*)y, c.d_model, batch, chunk_rows, L->st);
+}
+
 template <typename T>
 void launch_ffn_down(lif_layer* L, int batch, void* y, float* h, float* ypart, hipStream_t s, bool use_new = false) {
     const bool skip = L->cfg.ffn_mode == LIF_FFN_SKIP_DEAD;
+    if constexpr (std::is_same<T, _Float16>::value) {
+        if (batch > 1) {
+            if (skip) launch_ffn_down_mfma<true>(L, batch, y, h, ypart, s);
+            else launch_ffn_down_mfma<false>(L, batch, y, h, ypart, s);
+            return;
+        }
+    }
     if (batch == 1) {
         if (skip) launch_ffn_down_as<T, 1, true, kDownLanes1>(L, batch, y, h, ypart, s, use_new);
         else launch_ffn_down_as<T, 1, false, kDownLanesN>(L, batch, y, h, ypart, s, use_new);
