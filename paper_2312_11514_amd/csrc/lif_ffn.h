@@ -287,70 +287,130 @@ __global__ __launch_bounds__(256) void k_ffn_down(const T* __restrict__ matrix, 
 #pragma unroll
         for (int i = 0; i < BT * VE; ++i) acc[i] = 0.f;
         __syncthreads();
-        for (int s_base = r0; s_base < r1; s_base += TS) {
-            // compaction of the rows that contribute, in a fixed order (thread-major over slots q * 256 + tid)
-            float hloc[PER][BT];
-            unsigned flags = 0, nonzero = 0;
+        if constexpr (BT == 1) {
+            // One token: every wave compacts the slots of its own lanes with ballots into its own quarter of the
+            // list and then reads the rows of that quarter, so a pass needs no workgroup barrier and no scan through
+            // LDS (a wave's LDS operations complete in order).  Slots are dealt to threads round-robin, so the waves
+            // get even shares.  Order inside a wave: slot-major (q, then lane); the adds stay in list order.
+            constexpr int WL = TS / 4;                   // list entries per wave (PER slots x 64 lanes)
+            constexpr int RGW = 64 / LANES;              // row groups per wave
+            const int lane = tid & 63, wv = tid >> 6, rgw = lane / LANES;
+            int* wlist = list + wv * WL;
+            float* whv = hv[0] + wv * WL;
+            for (int s_base = r0; s_base < r1; s_base += TS) {
+                int cnt = 0, nz = 0;                     // uniform over the wave
 #pragma unroll
-            for (int q = 0; q < PER; ++q) {
-                const int s = s_base + q * 256 + tid;
-                bool any = false;
-#pragma unroll
-                for (int b = 0; b < BT; ++b) {
+                for (int q = 0; q < PER; ++q) {
+                    const int s = s_base + q * 256 + tid;
                     float v = 0.f;
-                    if (s < r1 && b < batch) {
-                        if (s_base == 0) v = hfirst[q][b];       // only chunk 0 (first workgroup row) starts at row 0
-                        else v = (stamp && stamp[s] == cur_step) ? h_new[(size_t)b * capacity + s]
-                                                                 : h[(size_t)b * capacity + s];
+                    if (s < r1) {
+                        if (s_base == 0) v = hfirst[q][0];           // only chunk 0 (first workgroup row) starts at row 0
+                        else v = (stamp && stamp[s] == cur_step) ? h_new[s] : h[s];
                     }
-                    hloc[q][b] = v;
-                    any |= (v != 0.f);
-                }
-                if (any) nonzero |= 1u << q;
-                if (!SKIP) any = s < r1;
-                if (any) flags |= 1u << q;
-            }
-            if (slice == 0 && nonzero) atomicAdd(&n_active, __popc(nonzero));   // statistics only
-            int cnt;
-            int off = block_exclusive_scan(__popc(flags), wave_tot, &cnt);
-#pragma unroll
-            for (int q = 0; q < PER; ++q) {
-                if (flags & (1u << q)) {
-                    list[off] = s_base + q * 256 + tid;
-#pragma unroll
-                    for (int b = 0; b < BT; ++b) hv[b][off] = hloc[q][b];
-                    ++off;
-                }
-            }
-            __syncthreads();
-            if (col_ok) {
-                // all row loads of a pass over kInFlight rows per thread are issued before the first use (a loop with a
-                // run-time trip count would wait for every load in turn); the adds stay in ascending row order
-                constexpr int kInFlight = (BT == 1) ? 8 : 4;
-                for (int i0 = rg; i0 < cnt; i0 += RG * kInFlight) {
-                    V v[kInFlight];
-#pragma unroll
-                    for (int u = 0; u < kInFlight; ++u) {
-                        const int i = i0 + u * RG;
-                        const int s = list[i < cnt ? i : i0];
-                        v[u] = (i < cnt) ? *reinterpret_cast<const V*>(base + (size_t)s * row_elems) : V(0);
+                    const bool nonzero = v != 0.f;
+                    const bool take = SKIP ? nonzero : s < r1;
+                    const unsigned long long m = __ballot(take);
+                    if (take) {
+                        const int pos = cnt + (int)__builtin_amdgcn_mbcnt_hi((unsigned)(m >> 32),
+                                                                              __builtin_amdgcn_mbcnt_lo((unsigned)m, 0u));
+                        wlist[pos] = s;
+                        whv[pos] = v;
                     }
+                    cnt += __popcll(m);
+                    nz += SKIP ? __popcll(m) : __popcll(__ballot(nonzero));
+                }
+                if (slice == 0 && lane == 0 && nz) atomicAdd(&n_active, nz);      // statistics only
+                __builtin_amdgcn_wave_barrier();
+                if (col_ok) {
+                    // all row loads of a pass over kInFlight rows per thread are issued before the first use
+                    constexpr int kInFlight = 8;
+                    for (int i0 = rgw; i0 < cnt; i0 += RGW * kInFlight) {
+                        V v[kInFlight];
 #pragma unroll
-                    for (int u = 0; u < kInFlight; ++u) {
-                        const int i = i0 + u * RG;
-                        if (i < cnt) {
+                        for (int u = 0; u < kInFlight; ++u) {
+                            const int i = i0 + u * RGW;
+                            const int sr = wlist[i < cnt ? i : i0];
+                            v[u] = (i < cnt) ? *reinterpret_cast<const V*>(base + (size_t)sr * row_elems) : V(0);
+                        }
 #pragma unroll
-                            for (int b = 0; b < BT; ++b) {
-                                const float hb = hv[b][i];
+                        for (int u = 0; u < kInFlight; ++u) {
+                            const int i = i0 + u * RGW;
+                            if (i < cnt) {
+                                const float hb = whv[i];
 #pragma unroll
-                                for (int e = 0; e < VE; ++e)
-                                    acc[b * VE + e] = __builtin_fmaf(hb, (float)v[u][e], acc[b * VE + e]);
+                                for (int e = 0; e < VE; ++e) acc[e] = __builtin_fmaf(hb, (float)v[u][e], acc[e]);
                             }
                         }
                     }
                 }
+                __builtin_amdgcn_wave_barrier();
             }
-            __syncthreads();
+        } else {
+            for (int s_base = r0; s_base < r1; s_base += TS) {
+                // compaction of the rows that contribute, in a fixed order (thread-major over slots q * 256 + tid)
+                float hloc[PER][BT];
+                unsigned flags = 0, nonzero = 0;
+#pragma unroll
+                for (int q = 0; q < PER; ++q) {
+                    const int s = s_base + q * 256 + tid;
+                    bool any = false;
+#pragma unroll
+                    for (int b = 0; b < BT; ++b) {
+                        float v = 0.f;
+                        if (s < r1 && b < batch) {
+                            if (s_base == 0) v = hfirst[q][b];       // only chunk 0 (first workgroup row) starts at row 0
+                            else v = (stamp && stamp[s] == cur_step) ? h_new[(size_t)b * capacity + s]
+                                                                     : h[(size_t)b * capacity + s];
+                        }
+                        hloc[q][b] = v;
+                        any |= (v != 0.f);
+                    }
+                    if (any) nonzero |= 1u << q;
+                    if (!SKIP) any = s < r1;
+                    if (any) flags |= 1u << q;
+                }
+                if (slice == 0 && nonzero) atomicAdd(&n_active, __popc(nonzero));   // statistics only
+                int cnt;
+                int off = block_exclusive_scan(__popc(flags), wave_tot, &cnt);
+#pragma unroll
+                for (int q = 0; q < PER; ++q) {
+                    if (flags & (1u << q)) {
+                        list[off] = s_base + q * 256 + tid;
+#pragma unroll
+                        for (int b = 0; b < BT; ++b) hv[b][off] = hloc[q][b];
+                        ++off;
+                    }
+                }
+                __syncthreads();
+                if (col_ok) {
+                    // all row loads of a pass over kInFlight rows per thread are issued before the first use (a loop with a
+                    // run-time trip count would wait for every load in turn); the adds stay in ascending row order
+                    constexpr int kInFlight = (BT == 1) ? 8 : 4;
+                    for (int i0 = rg; i0 < cnt; i0 += RG * kInFlight) {
+                        V v[kInFlight];
+#pragma unroll
+                        for (int u = 0; u < kInFlight; ++u) {
+                            const int i = i0 + u * RG;
+                            const int s = list[i < cnt ? i : i0];
+                            v[u] = (i < cnt) ? *reinterpret_cast<const V*>(base + (size_t)s * row_elems) : V(0);
+                        }
+#pragma unroll
+                        for (int u = 0; u < kInFlight; ++u) {
+                            const int i = i0 + u * RG;
+                            if (i < cnt) {
+#pragma unroll
+                                for (int b = 0; b < BT; ++b) {
+                                    const float hb = hv[b][i];
+#pragma unroll
+                                    for (int e = 0; e < VE; ++e)
+                                        acc[b * VE + e] = __builtin_fmaf(hb, (float)v[u][e], acc[b * VE + e]);
+                                }
+                            }
+                        }
+                    }
+                }
+                __syncthreads();
+            }
         }
         // the row groups of one wave sit LANES lanes apart: halving butterfly over the upper lane bits (a lane
         // ends with a few finished sums), then LDS over waves
