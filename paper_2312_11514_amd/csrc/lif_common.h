@@ -82,29 +82,43 @@ __device__ __forceinline__ float wave_sum(float v) {
     return v;
 }
 
+// Workgroup barrier that orders LDS accesses only: unlike __syncthreads() it does not wait for the global
+// stores a wave has in flight (their acknowledgement from the L2 costs several hundred nanoseconds).  Use it
+// where the data handed over lives in LDS and no thread reads global memory that another one has just written.
+__device__ __forceinline__ void lds_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 // Inclusive prefix sum over the lanes of a wave.
-__device__ __forceinline__ int wave_inclusive_scan(int v, int lane) {
-#pragma unroll
-    for (int o = 1; o < kWave; o <<= 1) {
-        int u = __shfl_up(v, o, kWave);
-        if (lane >= o) v += u;
-    }
+__device__ __forceinline__ int wave_inclusive_scan(int v, int /*lane*/) {
+    // data-parallel-primitive moves instead of six shuffles through the LDS crossbar: shifts by 1, 2, 4, 8 inside
+    // the rows of 16 lanes (lanes without a source add 0), then lane 15 of a row into the next row (rows 1 and 3)
+    // and lane 31 into rows 2 and 3
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, false);   // row_shr:1
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, false);   // row_shr:2
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, false);   // row_shr:4
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, false);   // row_shr:8
+    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);   // row_bcast:15
+    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);   // row_bcast:31
     return v;
 }
 
-// Exclusive prefix sum of one int per thread over a whole workgroup (thread order).
-// `wave_tot` is LDS scratch of at least blockDim.x / 64 ints.  Returns the exclusive
-// prefix; *total receives the workgroup sum.  Contains two barriers.
+// Exclusive prefix sum of one int per thread over a workgroup of NW waves (thread order).
+// `wave_tot` is LDS scratch of at least NW ints.  Returns the exclusive prefix; *total receives the
+// workgroup sum.  Contains two barriers (the first keeps a previous scan's readers of wave_tot ahead of the writes).
+template <int NW>
 __device__ __forceinline__ int block_exclusive_scan(int v, int* wave_tot, int* total) {
     const int tid = threadIdx.x, lane = tid & (kWave - 1), w = tid >> 6;
-    const int nw = (blockDim.x + kWave - 1) >> 6;
-    int inc = wave_inclusive_scan(v, lane);
-    __syncthreads();                       // wave_tot may still be read from a previous scan
+    const int inc = wave_inclusive_scan(v, lane);
+    __syncthreads();
     if (lane == kWave - 1) wave_tot[w] = inc;
     __syncthreads();
     int before = 0, all = 0;
-    for (int i = 0; i < nw; ++i) {
-        int t = wave_tot[i];
+#pragma unroll
+    for (int i = 0; i < NW; ++i) {
+        const int t = wave_tot[i];
         if (i < w) before += t;
         all += t;
     }

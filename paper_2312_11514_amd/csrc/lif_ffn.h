@@ -371,7 +371,7 @@ __global__ __launch_bounds__(256) void k_ffn_down(const T* __restrict__ matrix, 
                 }
                 if (slice == 0 && nonzero) atomicAdd(&n_active, __popc(nonzero));   // statistics only
                 int cnt;
-                int off = block_exclusive_scan(__popc(flags), wave_tot, &cnt);
+                int off = block_exclusive_scan<4>(__popc(flags), wave_tot, &cnt);
 #pragma unroll
                 for (int q = 0; q < PER; ++q) {
                     if (flags & (1u << q)) {

@@ -127,7 +127,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_ffn_down_mfma(const _Float16* __
             if (lane == 0) wave_max[w] = amax;       // (the barriers of the scan order this write and the reads below,
                                                      //  and keep the previous pass's readers of list / hv ahead of the writes)
             int cnt;
-            int off = block_exclusive_scan(__popc(flags), wave_tot, &cnt);
+            int off = block_exclusive_scan<WAVES>(__popc(flags), wave_tot, &cnt);
             float smax = wave_max[0];
 #pragma unroll
             for (int i = 1; i < WAVES; ++i) smax = fmaxf(smax, wave_max[i]);

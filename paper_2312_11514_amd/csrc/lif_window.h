@@ -25,31 +25,29 @@ __device__ __forceinline__ unsigned long long load_mask_word(const uint8_t* __re
     return v;
 }
 
-// Exclusive prefix sums of two counts per thread in one pass over a 1024-thread workgroup
-// (packed into one 64-bit lane value).  Contains two barriers.
+// Exclusive prefix sums of two counts per thread (each at most 64) in one pass over a workgroup of NW waves.
+// Inside a wave both counts travel in one 32-bit value (a wave sums to at most 4096 per count); the totals of
+// the waves are kept as two 32-bit halves of a 64-bit LDS word.  One barrier, two with GUARD (needed when
+// wave_tot may still be read from an earlier scan that no barrier separates from this one).
+template <int NW, bool GUARD>
 __device__ __forceinline__ void block_exclusive_scan2(int va, int vb, unsigned long long* wave_tot, int* off_a,
                                                       int* off_b, int* tot_a, int* tot_b) {
     const int tid = threadIdx.x, lane = tid & (kWave - 1), w = tid >> 6;
-    const int nw = (blockDim.x + kWave - 1) >> 6;
-    const unsigned long long v = ((unsigned long long)(unsigned)vb << 32) | (unsigned)va;
-    unsigned long long inc = v;
-#pragma unroll
-    for (int o = 1; o < kWave; o <<= 1) {
-        unsigned long long u = __shfl_up(inc, o, kWave);
-        if (lane >= o) inc += u;
-    }
-    __syncthreads();
-    if (lane == kWave - 1) wave_tot[w] = inc;
-    __syncthreads();
+    const int v = (vb << 16) | va;
+    const int inc = wave_inclusive_scan(v, lane);
+    if (GUARD) lds_barrier();
+    if (lane == kWave - 1) wave_tot[w] = ((unsigned long long)(unsigned)(inc >> 16) << 32) | (unsigned)(inc & 0xffff);
+    lds_barrier();
     unsigned long long before = 0, all = 0;
-    for (int i = 0; i < nw; ++i) {
+#pragma unroll
+    for (int i = 0; i < NW; ++i) {
         const unsigned long long t = wave_tot[i];
         if (i < w) before += t;
         all += t;
     }
-    const unsigned long long ex = before + inc - v;
-    *off_a = (int)(unsigned)(ex & 0xffffffffull);
-    *off_b = (int)(unsigned)(ex >> 32);
+    const int ex = inc - v;                                  // exclusive inside the wave, both halves at once
+    *off_a = (int)(unsigned)(before & 0xffffffffull) + (ex & 0xffff);
+    *off_b = (int)(unsigned)(before >> 32) + (ex >> 16);
     *tot_a = (int)(unsigned)(all & 0xffffffffull);
     *tot_b = (int)(unsigned)(all >> 32);
 }
@@ -272,7 +270,7 @@ __global__ __launch_bounds__(kScanThreads) void k_window_plan(
     unsigned long long abits = now & ~prev;
     unsigned long long rbits = prev & ~now;
     int off_a, off_r, tot_a, tot_r;
-    block_exclusive_scan2(__popcll(abits), __popcll(rbits), wave_tot, &off_a, &off_r, &tot_a, &tot_r);
+    block_exclusive_scan2<NW, false>(__popcll(abits), __popcll(rbits), wave_tot, &off_a, &off_r, &tot_a, &tot_r);
 
     const int n2 = n - tot_r;
     if (n2 < 0 || n2 + tot_a > capacity) {          // uniform: leave the window untouched
@@ -309,7 +307,7 @@ __global__ __launch_bounds__(kScanThreads) void k_window_plan(
         removed[off_r++] = tid * 64 + __ffsll((long long)rbits) - 1;
         rbits &= rbits - 1;
     }
-    __syncthreads();
+    lds_barrier();                                   // rem64 is read below; nothing stored to global memory above is read here
 
     // ---- deletion plan: classify the slots below n, block by block ----
     const int nblk = (n + kWave - 1) >> 6;           // <= 1024
@@ -340,16 +338,16 @@ __global__ __launch_bounds__(kScanThreads) void k_window_plan(
             blk_f[b] = cf;
         }
     }
-    __syncthreads();
+    lds_barrier();
     int pre_h, pre_f, H, Fc;
     {
         const int vh = (tid < nblk) ? blk_h[tid] : 0, vf = (tid < nblk) ? blk_f[tid] : 0;
-        block_exclusive_scan2(vh, vf, wave_tot, &pre_h, &pre_f, &H, &Fc);
+        block_exclusive_scan2<NW, false>(vh, vf, wave_tot, &pre_h, &pre_f, &H, &Fc);
         // the scan's barriers separate the reads of the counts above from these writes
         blk_h[tid] = pre_h;
         blk_f[tid] = pre_f;
     }
-    __syncthreads();
+    lds_barrier();
     const bool in_lds = H <= kHoleLds;
     for (int b = w, it = 0; b < nblk; b += NW, ++it) {
         const bool hole = (holebits >> it) & 1ull;
@@ -360,7 +358,9 @@ __global__ __launch_bounds__(kScanThreads) void k_window_plan(
             else hole_list[pos] = b * kWave + lane;
         }
     }
-    __syncthreads();   // the hole list (LDS, or global scratch when long) is read by other threads below
+    // the hole list (LDS, or global scratch when long) is read by other threads below
+    if (in_lds) lds_barrier();
+    else __syncthreads();
     for (int b = w, it = 0; b < nblk; b += NW, ++it) {
         const int s = b * kWave + lane;
         const bool fill = (fillbits >> it) & 1ull;
