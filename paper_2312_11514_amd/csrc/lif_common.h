@@ -74,12 +74,41 @@ __device__ __forceinline__ float dot_acc(f32x4 a, f32x4 b, float acc) {
     return acc;
 }
 
-// Sum over the 64 lanes of a wave; every lane receives the result.  The butterfly
-// adds the same pairs in every lane, so all lanes hold the bit-identical sum.
+// Sum over the 64 lanes of a wave; every lane receives the result.  Data-parallel-primitive moves instead of
+// shuffles through the LDS crossbar: an inclusive prefix sum (shifts by 1, 2, 4, 8 inside the rows of 16 lanes,
+// lane 15 of a row into the next row, lane 31 into the upper half) leaves the total in lane 63, which is then
+// broadcast.  Lanes without a source add 0.
+template <int CTRL, int ROWS>
+__device__ __forceinline__ float dpp_from(float v) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, ROWS, 0xf, false));
+}
+template <int CTRL, int ROWS>
+__device__ __forceinline__ double dpp_from(double v) {
+    const unsigned long long u = __builtin_bit_cast(unsigned long long, v);
+    const unsigned lo = (unsigned)__builtin_amdgcn_update_dpp(0, (int)(unsigned)u, CTRL, ROWS, 0xf, false);
+    const unsigned hi = (unsigned)__builtin_amdgcn_update_dpp(0, (int)(unsigned)(u >> 32), CTRL, ROWS, 0xf, false);
+    return __builtin_bit_cast(double, ((unsigned long long)hi << 32) | lo);
+}
 __device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, kWave);
-    return v;
+    v += dpp_from<0x111, 0xf>(v);   // row_shr:1
+    v += dpp_from<0x112, 0xf>(v);   // row_shr:2
+    v += dpp_from<0x114, 0xf>(v);   // row_shr:4
+    v += dpp_from<0x118, 0xf>(v);   // row_shr:8
+    v += dpp_from<0x142, 0xa>(v);   // row_bcast:15 into rows 1 and 3
+    v += dpp_from<0x143, 0xc>(v);   // row_bcast:31 into rows 2 and 3
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
+}
+__device__ __forceinline__ double wave_sum(double v) {
+    v += dpp_from<0x111, 0xf>(v);
+    v += dpp_from<0x112, 0xf>(v);
+    v += dpp_from<0x114, 0xf>(v);
+    v += dpp_from<0x118, 0xf>(v);
+    v += dpp_from<0x142, 0xa>(v);
+    v += dpp_from<0x143, 0xc>(v);
+    const unsigned long long u = __builtin_bit_cast(unsigned long long, v);
+    const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)u, 63);
+    const unsigned hi = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(u >> 32), 63);
+    return __builtin_bit_cast(double, ((unsigned long long)hi << 32) | lo);
 }
 
 // Workgroup barrier that orders LDS accesses only: unlike __syncthreads() it does not wait for the global

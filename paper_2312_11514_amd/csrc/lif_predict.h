@@ -61,8 +61,7 @@ __global__ __launch_bounds__(256) void k_predict_xa(const T* __restrict__ x, con
     double acc = 0.0;
 #pragma unroll
     for (int it = 0; it < NI; ++it) acc = dot_f64(a[it], xr[it], acc);
-#pragma unroll
-    for (int msk = 32; msk >= 1; msk >>= 1) acc += __shfl_xor(acc, msk, kWave);
+    acc = wave_sum(acc);
     if (lane == 0 && !err) t[(size_t)b * r + j] = acc;
 }
 
@@ -270,8 +269,7 @@ __global__ __launch_bounds__(256) void k_predict_gate(const T* __restrict__ Wg, 
                     if (XREG) acc = dot_f64(g[it], xr[it], acc);          // both are 0 past the end of the vector
                     else if (idx < nvec) acc = dot_f64(g[it], xs[t * nvec + idx], acc);
                 }
-#pragma unroll
-                for (int msk = 32; msk >= 1; msk >>= 1) acc += __shfl_xor(acc, msk, kWave);
+                acc = wave_sum(acc);
                 const double a = acc + bi;
                 if (a > th) bits |= 1ull << (8 * t + e);
                 if (lane == 0) gact[(size_t)t * F + i] = (float)(a > 0.0 ? a : 0.0);
