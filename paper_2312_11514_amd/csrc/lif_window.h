@@ -284,30 +284,7 @@ __global__ __launch_bounds__(kScanThreads) void k_window_plan(
         return;
     }
     rem64[tid] = rbits;
-    if (have) {
-        cur_set[tid] = now;
-        if (!multi) {
-            ring[(size_t)slot * ring_words + tid] = m;
-            for (int a = k_eff + 1; a <= k; ++a)             // masks dropped by the dynamic window leave it for good
-                ring[(size_t)((slot - (a - 1) + k) % k) * ring_words + tid] = 0ull;
-        } else {
-            for (int i = max(0, keep_tok - k); i < keep_tok; ++i)
-                ring[(size_t)((pos + i) % k) * ring_words + tid] =
-                    load_mask_word(step_mask + (size_t)i * nbytes, tid, nbytes);
-            // entries written before this pass that the dynamic window dropped (ages above k_eff) leave for good
-            for (int m_old = max(k_eff - keep_tok, 0) + 1; m_old <= k - keep_tok; ++m_old)
-                ring[(size_t)(((pos - m_old) % k + k) % k) * ring_words + tid] = 0ull;
-        }
-    }
-    while (abits) {
-        added[off_a++] = tid * 64 + __ffsll((long long)abits) - 1;
-        abits &= abits - 1;
-    }
-    while (rbits) {
-        removed[off_r++] = tid * 64 + __ffsll((long long)rbits) - 1;
-        rbits &= rbits - 1;
-    }
-    lds_barrier();                                   // rem64 is read below; nothing stored to global memory above is read here
+    lds_barrier();                                   // rem64 is read below
 
     // ---- deletion plan: classify the slots below n, block by block ----
     const int nblk = (n + kWave - 1) >> 6;           // <= 1024
@@ -373,6 +350,31 @@ __global__ __launch_bounds__(kScanThreads) void k_window_plan(
             }
             move_dst[s - n2] = dst;
         }
+    }
+    // ---- the new window and the id lists go out last: nothing in this kernel reads them back, and the plan above
+    // does not wait for them ----
+    if (have) {
+        cur_set[tid] = now;
+        if (!multi) {
+            ring[(size_t)slot * ring_words + tid] = m;
+            for (int a = k_eff + 1; a <= k; ++a)             // masks dropped by the dynamic window leave it for good
+                ring[(size_t)((slot - (a - 1) + k) % k) * ring_words + tid] = 0ull;
+        } else {
+            for (int i = max(0, keep_tok - k); i < keep_tok; ++i)
+                ring[(size_t)((pos + i) % k) * ring_words + tid] =
+                    load_mask_word(step_mask + (size_t)i * nbytes, tid, nbytes);
+            // entries written before this pass that the dynamic window dropped (ages above k_eff) leave for good
+            for (int m_old = max(k_eff - keep_tok, 0) + 1; m_old <= k - keep_tok; ++m_old)
+                ring[(size_t)(((pos - m_old) % k + k) % k) * ring_words + tid] = 0ull;
+        }
+    }
+    while (abits) {
+        added[off_a++] = tid * 64 + __ffsll((long long)abits) - 1;
+        abits &= abits - 1;
+    }
+    while (rbits) {
+        removed[off_r++] = tid * 64 + __ffsll((long long)rbits) - 1;
+        rbits &= rbits - 1;
     }
     if (tid == 0) {
         *n_added = tot_a;

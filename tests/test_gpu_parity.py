@@ -131,6 +131,33 @@ def test_threshold_extremes_full_and_empty_cache():
             assert not gpu.y.cpu().numpy().any()
 
 
+@pytest.mark.parametrize("ffn_mode", [0, 1])
+@pytest.mark.parametrize("d_model,glu,batch", [(256, False, 5), (264, True, 8), (96, False, 2)])
+def test_batched_ffn_over_a_cache_of_many_rows(d_model, glu, batch, ffn_mode):
+    """Several tokens over 40000 cached rows (theta = -inf caches every neuron): the chunks of the batched down
+    projection are 1536 rows here (three compaction passes each) and 27 of them are in use; d = 264 has a ragged last
+    column slice and takes the streaming activation stage (d is no multiple of 32), d = 256 the matrix-core one.
+    Checked against the dense FFN per token."""
+    from tests.harness import GpuLayer, rel_l2
+    F = 40000
+    w = wl.scaled(wl.WORKLOADS["C1"], name="many-rows", d_model=d_model, d_ffn=F, rank=8, window_k=2, dtype="f16", glu=glu,
+                  tokens=2, batch=batch, capacity_rows=F)
+    L = _random_predictor_layer(w, seed=11)
+    L.theta = -np.inf
+    X = wl.make_batch_inputs(w)
+    gpu = GpuLayer(w, L, ffn_mode=ffn_mode)
+    lay = gpu.layer
+    for t in range(2):
+        xd = gpu.upload_x(X[t])
+        lay.step(xd, gpu.y, batch=batch)
+        st = lay.state()
+        assert st["error"] == 0 and st["num_used"] == F
+        y = gpu.y.cpu().numpy().astype(np.float64)
+        for i in range(batch):
+            yd = O.dense_ffn(L.w_up, L.w_down, L.b, X[t][i], w_gate=L.w_gate if glu else None)
+            assert rel_l2(y[i], yd) <= 1e-3, (t, i)
+
+
 def test_maximum_sizes_long_hole_list():
     """F = capacity = 65536 (the largest the window kernel takes), half the neurons flipping per step:
     tens of thousands of holes, so the hole list spills from LDS to the global scratch list."""
