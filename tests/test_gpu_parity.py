@@ -385,6 +385,35 @@ def test_c5_all_32_layers_token_major():
     assert len(set(sizes)) > 8 and max(sizes) <= w.capacity_rows // 2       # every layer its own set, far below the cap
 
 
+@pytest.mark.parametrize("glu", [False, True])
+def test_row_count_hint_never_changes_results_batched(glu):
+    """Eight tokens per step, fp16: the grids of both matrix-core stages are sized from the hint (a smaller grid strides
+    over the tiles and chunks, a hint of 2048 rows or more moves lif_step to the shared load + activation launch);
+    the output bytes are the same for every hint and for both ways of driving the layer."""
+    from tests.harness import GpuLayer
+    w = wl.scaled(wl.WORKLOADS["C1"], name="hint-b8", d_model=512, d_ffn=4096, rank=32, window_k=3, p_active=0.1,
+                  dtype="f16", glu=glu, tokens=6, batch=8, capacity_rows=4096)
+    L = wl.make_layer(w)
+    X = wl.make_batch_inputs(w)
+    outs = set()
+    for hint in (0, 16, 900, 5000):
+        for api in ("step", "calls"):
+            gpu = GpuLayer(w, L)
+            if hint:
+                gpu.layer.set_expected_rows(hint)
+            ys = []
+            for t in range(len(X)):
+                xd = gpu.upload_x(X[t])
+                if api == "step":
+                    gpu.layer.step(xd, gpu.y, batch=8)
+                else:
+                    gpu.layer.step_calls(xd, gpu.y, batch=8)
+                ys.append(gpu.y.cpu().numpy().tobytes())
+            assert gpu.layer.state()["error"] == 0 and gpu.layer.state()["num_used"] > 600
+            outs.add(b"".join(ys))
+    assert len(outs) == 1
+
+
 @pytest.mark.parametrize("hint", [16, 900, 5000])
 def test_row_count_hint_never_changes_results(hint):
     """The speculative first pass of the FFN (hint below, near and above the rows in use) gives the same bytes."""
