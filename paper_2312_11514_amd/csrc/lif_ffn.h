@@ -246,18 +246,36 @@ __global__ __launch_bounds__(256) void k_ffn_down(const T* __restrict__ matrix, 
     // (the activation array spans the whole capacity, so the addresses are valid; values past
     // num_used are masked below): one memory round trip less on the critical path
     const bool first_row = blockIdx.y == 0;
+    // (uniform branches around unconditional loads from clamped slots: a predicate per load would cost a branch each)
     float hfirst[PER][BT], hnfirst[PER][BT];
     int sfirst[PER];
 #pragma unroll
     for (int q = 0; q < PER; ++q) {
-        const int s = q * 256 + tid;
+        sfirst[q] = -1;
+#pragma unroll
+        for (int b = 0; b < BT; ++b) hfirst[q][b] = hnfirst[q][b] = 0.f;
+    }
+    if (first_row) {
 #pragma unroll
         for (int b = 0; b < BT; ++b) {
-            hfirst[q][b] = (first_row && s < capacity && b < batch) ? h[(size_t)b * capacity + s] : 0.f;
-            // the loader-written activations travel in the same round trip as h and the stamps
-            hnfirst[q][b] = (first_row && stamp && s < capacity && b < batch) ? h_new[(size_t)b * capacity + s] : 0.f;
+            if (b < batch) {
+#pragma unroll
+                for (int q = 0; q < PER; ++q) hfirst[q][b] = h[(size_t)b * capacity + min(q * 256 + tid, capacity - 1)];
+            }
         }
-        sfirst[q] = (first_row && stamp && s < capacity) ? stamp[s] : -1;
+        if (stamp) {
+            // the loader-written activations travel in the same round trip as h and the stamps
+#pragma unroll
+            for (int q = 0; q < PER; ++q) sfirst[q] = stamp[min(q * 256 + tid, capacity - 1)];
+#pragma unroll
+            for (int b = 0; b < BT; ++b) {
+                if (b < batch) {
+#pragma unroll
+                    for (int q = 0; q < PER; ++q)
+                        hnfirst[q][b] = h_new[(size_t)b * capacity + min(q * 256 + tid, capacity - 1)];
+                }
+            }
+        }
     }
     const int err = st->error;
     const int n = err ? 0 : st->num_used;
@@ -299,14 +317,26 @@ __global__ __launch_bounds__(256) void k_ffn_down(const T* __restrict__ matrix, 
             float* whv = hv[0] + wv * WL;
             for (int s_base = r0; s_base < r1; s_base += TS) {
                 int cnt = 0, nz = 0;                     // uniform over the wave
+                float hval[PER];
+                if (s_base == 0) {                       // only chunk 0 (first workgroup row) starts at row 0
+#pragma unroll
+                    for (int q = 0; q < PER; ++q) hval[q] = hfirst[q][0];
+                } else {
+#pragma unroll
+                    for (int q = 0; q < PER; ++q) hval[q] = h[min(s_base + q * 256 + tid, capacity - 1)];
+                    if (stamp) {
+#pragma unroll
+                        for (int q = 0; q < PER; ++q) {
+                            const int sc = min(s_base + q * 256 + tid, capacity - 1);
+                            const float hn = h_new[sc];
+                            if (stamp[sc] == cur_step) hval[q] = hn;
+                        }
+                    }
+                }
 #pragma unroll
                 for (int q = 0; q < PER; ++q) {
                     const int s = s_base + q * 256 + tid;
-                    float v = 0.f;
-                    if (s < r1) {
-                        if (s_base == 0) v = hfirst[q][0];           // only chunk 0 (first workgroup row) starts at row 0
-                        else v = (stamp && stamp[s] == cur_step) ? h_new[s] : h[s];
-                    }
+                    const float v = (s < r1) ? hval[q] : 0.f;
                     const bool nonzero = v != 0.f;
                     const bool take = SKIP ? nonzero : s < r1;
                     const unsigned long long m = __ballot(take);
