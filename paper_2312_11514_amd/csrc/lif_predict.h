@@ -105,15 +105,28 @@ __global__ __launch_bounds__(256) void k_predict_mask(const T* __restrict__ B, c
 #pragma unroll
         for (int e = 0; e < 8; ++e) cv[e] = (c && tid < kMaskCols * BT && n2 < F) ? c[n2 + e] : 0.f;
     }
+    // one token per pass: the kMaskRows values of t this thread multiplies with come straight from global memory,
+    // requested with the rows (no staging in LDS, no barriers in front of the multiply-adds)
+    double tr[BT == 1 ? kMaskRows : 1];
+    if (BT == 1) {
+#pragma unroll
+        for (int u = 0; u < kMaskRows; ++u) tr[u] = t[min(jg + u * kMaskJg, r - 1)];
+    }
     const int err = st->error;
 
     for (int b0 = 0; b0 < batch; b0 += BT) {
-        __syncthreads();
-        for (int idx = tid; idx < BT * r; idx += 256) {
-            const int bt = idx / r, j = idx - bt * r;
-            tl[idx] = (b0 + bt < batch) ? t[(size_t)(b0 + bt) * r + j] : 0.0;
+        if (BT > 1 || r > kMaskRows * kMaskJg) {
+            __syncthreads();
+            for (int idx = tid; idx < BT * r; idx += 256) {
+                const int bt = idx / r, j = idx - bt * r;
+                tl[idx] = (b0 + bt < batch) ? t[(size_t)(b0 + bt) * r + j] : 0.0;
+            }
+            __syncthreads();
         }
-        __syncthreads();
+        if (BT == 1 && b0 > 0) {                     // batches served token by token (large ranks)
+#pragma unroll
+            for (int u = 0; u < kMaskRows; ++u) tr[u] = t[(size_t)b0 * r + min(jg + u * kMaskJg, r - 1)];
+        }
 
         double v[BT * 8];                    // v[bt * 8 + e]: logit sums of token bt, neuron e of this lane's byte
 #pragma unroll
@@ -123,7 +136,7 @@ __global__ __launch_bounds__(256) void k_predict_mask(const T* __restrict__ B, c
             const int j = min(jg + u * kMaskJg, r - 1);           // bv[u] is 0 past the end
 #pragma unroll
             for (int bt = 0; bt < BT; ++bt) {
-                const double tj = tl[bt * r + j];
+                const double tj = (BT == 1) ? tr[u] : tl[bt * r + j];
 #pragma unroll
                 for (int q = 0; q < LPB; ++q)
 #pragma unroll
@@ -160,13 +173,14 @@ __global__ __launch_bounds__(256) void k_predict_mask(const T* __restrict__ B, c
 #pragma unroll
             for (int i = 0; i < half; ++i) {
                 const double send = up ? v[i] : v[i + half], keep = up ? v[i + half] : v[i];
-                v[i] = keep + __shfl_xor(send, m, kWave);
+                // lanes 8 apart sit in one row of 16: a rotation by 8 (DPP) instead of a shuffle through LDS
+                v[i] = keep + (m == 8 ? dpp_from<0x128, 0xf>(send) : __shfl_xor(send, m, kWave));
             }
             owner = owner * 2 + (up ? 1 : 0);
         };
         auto full = [&](int m) {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) v[i] += __shfl_xor(v[i], m, kWave);
+            for (int i = 0; i < 8; ++i) v[i] += (m == 8 ? dpp_from<0x128, 0xf>(v[i]) : __shfl_xor(v[i], m, kWave));
         };
         if constexpr (BT == 8) {
             halve(std::integral_constant<int, 32>{}, 32);
@@ -177,14 +191,18 @@ __global__ __launch_bounds__(256) void k_predict_mask(const T* __restrict__ B, c
             halve(std::integral_constant<int, 8>{}, 16);
             full(8);
         } else {
-            full(32);
-            full(16);
-            full(8);
+            // one token: the 8 neurons of the byte are halved the same way (7 exchanges instead of 24), the step over
+            // lanes 8 apart first, while a lane still holds all 8: lane (g, cl) ends with neuron `owner`
+            halve(std::integral_constant<int, 4>{}, 8);
+            halve(std::integral_constant<int, 2>{}, 16);
+            halve(std::integral_constant<int, 1>{}, 32);
         }
         // which lanes hold a finished token: those whose bits of the non-halving steps are zero
         constexpr int kHalvings = (BT == 8) ? 3 : (BT == 4) ? 2 : 0;
         const bool holder = ((tid & 63) & ((64 >> kHalvings) - 8)) == 0;
-        if (holder) {
+        if (BT == 1) {
+            red[wave][cl][0][owner] = v[0];
+        } else if (holder) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) red[wave][cl][owner][e] = v[e];
         }
