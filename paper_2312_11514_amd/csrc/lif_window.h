@@ -321,21 +321,35 @@ __global__ __launch_bounds__(kScanThreads) void k_window_plan(
         }
     }
     lds_barrier();
-    int pre_h, pre_f, H, Fc;
-    {
+    int H, Fc;
+    // At most 64 blocks in use (4096 rows): every wave scans the block counts itself (one DPP prefix sum over
+    // the lanes, both counts in one value) and picks the prefixes of its own blocks out of the lanes: no scan
+    // across waves, no write-back, two barriers fewer.
+    const bool few = nblk <= kWave;                  // uniform
+    int ex_few = 0;
+    if (few) {
+        const int v = (lane < nblk) ? (blk_h[lane] | (blk_f[lane] << 16)) : 0;
+        const int inc = wave_inclusive_scan(v, lane);
+        ex_few = inc - v;
+        const int tot = __builtin_amdgcn_readlane(inc, kWave - 1);
+        H = tot & 0xffff;
+        Fc = tot >> 16;
+    } else {
+        int pre_h, pre_f;
         const int vh = (tid < nblk) ? blk_h[tid] : 0, vf = (tid < nblk) ? blk_f[tid] : 0;
         block_exclusive_scan2<NW, false>(vh, vf, wave_tot, &pre_h, &pre_f, &H, &Fc);
-        // the scan's barriers separate the reads of the counts above from these writes
+        // the scan's barrier separates the reads of the counts above from these writes
         blk_h[tid] = pre_h;
         blk_f[tid] = pre_f;
+        lds_barrier();
     }
-    lds_barrier();
     const bool in_lds = H <= kHoleLds;
     for (int b = w, it = 0; b < nblk; b += NW, ++it) {
         const bool hole = (holebits >> it) & 1ull;
         const unsigned long long bh = __ballot(hole);
+        const int ph = few ? (__builtin_amdgcn_readlane(ex_few, b) & 0xffff) : blk_h[b];
         if (hole) {
-            const int pos = blk_h[b] + __popcll(bh & lt);
+            const int pos = ph + __popcll(bh & lt);
             if (in_lds) hole_lds[pos] = b * kWave + lane;
             else hole_list[pos] = b * kWave + lane;
         }
@@ -347,10 +361,11 @@ __global__ __launch_bounds__(kScanThreads) void k_window_plan(
         const int s = b * kWave + lane;
         const bool fill = (fillbits >> it) & 1ull;
         const unsigned long long bf = __ballot(fill);
+        const int pf = few ? (int)((unsigned)__builtin_amdgcn_readlane(ex_few, b) >> 16) : blk_f[b];
         if (s >= n2 && s < n) {
             int dst = -1;
             if (fill) {
-                const int q = H - 1 - (blk_f[b] + __popcll(bf & lt));
+                const int q = H - 1 - (pf + __popcll(bf & lt));
                 if (q >= 0 && q < H) dst = in_lds ? hole_lds[q] : hole_list[q];
             }
             move_dst[s - n2] = dst;
