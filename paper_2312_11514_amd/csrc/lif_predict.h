@@ -115,6 +115,7 @@ __global__ __launch_bounds__(256) void k_predict_mask(const T* __restrict__ B, c
     const int err = st->error;
 
     for (int b0 = 0; b0 < batch; b0 += BT) {
+        if (BT == 1 && r <= kMaskRows * kMaskJg && b0 > 0) __syncthreads();   // red is still read from the pass before
         if (BT > 1 || r > kMaskRows * kMaskJg) {
             __syncthreads();
             for (int idx = tid; idx < BT * r; idx += 256) {
@@ -220,12 +221,15 @@ __global__ __launch_bounds__(256) void k_predict_mask(const T* __restrict__ B, c
                 }
                 if (!err) masks[(size_t)(b0 + bt) * mask_stride + (n2 >> 3)] = byte;
             }
-            bytes[bt][c2] = byte;
+            if (BT == 1) or_byte |= byte;            // one token per pass: this thread owns column tid of the step mask
+            else bytes[bt][c2] = byte;
         }
-        __syncthreads();
-        if (tid < kMaskCols) {
+        if (BT > 1) {
+            __syncthreads();
+            if (tid < kMaskCols) {
 #pragma unroll
-            for (int bt = 0; bt < BT; ++bt) or_byte |= bytes[bt][tid];
+                for (int bt = 0; bt < BT; ++bt) or_byte |= bytes[bt][tid];
+            }
         }
     }
     if (tid < kMaskCols && n0 < F && !err) step_mask[n0 >> 3] = or_byte;
