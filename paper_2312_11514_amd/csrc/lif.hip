@@ -247,9 +247,19 @@ void launch_ffn_down_as(lif_layer* L, int batch, void* y, float* h, float* ypart
                                                : c.capacity_rows;
     const int wg_rows = down_chunks<BT, SKIP>(rows_hint);
     const int down_off = (c.glu ? 2 : 1) * c.d_model;
-    hipLaunchKernelGGL((k_ffn_down<T, BT, SKIP, LANES>), dim3(slices, wg_rows), dim3(256), 0, s,
-                       (const T*)L->buf.matrix, h, use_new ? L->h_new : nullptr, use_new ? L->stamp : nullptr,
-                       (T*)y, ypart, c.d_model, batch, c.capacity_rows, L->row_elems, down_off, L->st);
+    // one token: groups of 256 slots whose activations the first workgroup row asks for before the row count arrives
+    // (from the hint; 2048 slots without one); several tokens: all of the first pass
+    const int spec_groups = BT > 1 ? (1 << 20) : L->expected_rows > 0 ? std::max(1, (rows_hint + 255) / 256) : 8;
+    // one token: compaction passes of 4096 slots when more than 2048 rows are expected (one pass instead of two;
+    // the sums are the same), of 2048 otherwise (half the registers and guards on the shortest path)
+    if (BT == 1 && L->expected_rows > 0 && rows_hint > kDownTile)
+        hipLaunchKernelGGL((k_ffn_down<T, BT, SKIP, LANES, 2 * kDownTile>), dim3(slices, wg_rows), dim3(256), 0, s,
+                           (const T*)L->buf.matrix, h, use_new ? L->h_new : nullptr, use_new ? L->stamp : nullptr,
+                           (T*)y, ypart, c.d_model, batch, c.capacity_rows, L->row_elems, down_off, spec_groups, L->st);
+    else
+        hipLaunchKernelGGL((k_ffn_down<T, BT, SKIP, LANES>), dim3(slices, wg_rows), dim3(256), 0, s,
+                           (const T*)L->buf.matrix, h, use_new ? L->h_new : nullptr, use_new ? L->stamp : nullptr,
+                           (T*)y, ypart, c.d_model, batch, c.capacity_rows, L->row_elems, down_off, spec_groups, L->st);
     if (wg_rows > 1)
         hipLaunchKernelGGL((k_ffn_down_finish<T, BT, SKIP>), dim3((batch * c.d_model + 255) / 256), dim3(256), 0, s,
                            ypart, (T*)y, c.d_model, batch, L->st);

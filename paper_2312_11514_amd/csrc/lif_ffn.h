@@ -179,14 +179,14 @@ constexpr int kDownChunksMax = 32;  // row chunks of the down projection (partia
 constexpr int kDownLanesB = 16;       // lanes per column slice for several tokens
 constexpr int kDownLanes1 = 4;        // ... single token skipping dead rows (latency bound)
 constexpr int kDownLanesN = 8;        // ... when most rows are read: 8 x 16 B = one 128-byte line per row
-constexpr int kDownRowsSparse = 2048; // rows per chunk: single token, rows without activation skipped
+constexpr int kDownRowsSparse = 4096; // rows per chunk: single token, rows without activation skipped
 constexpr int kDownRowsDense = 512;   // ... single token, every row read
 constexpr int kDownRowsBatch = 512;   // ... several tokens
 
-// Row chunks in use for n cached rows.  For a single token and up to 2048 rows (1024 in full-bundle mode), one
+// Row chunks in use for n cached rows.  For a single token and up to 4096 rows (1024 in full-bundle mode), one
 // chunk (one workgroup per column slice, no partial sums) is the shortest path: the kernel is latency bound
 // there.  Beyond that, the single-token
-// case that skips rows without activation keeps chunks of 2048 rows (one compaction pass each; few rows
+// case that skips rows without activation keeps chunks of 4096 rows (one compaction pass each; few rows
 // contribute); when most rows are read (full-bundle mode, or several tokens whose active sets add up) a
 // chunk is 512 rows so that several hundred workgroups stream at once: column slices alone (d / 64
 // workgroups) reach only about 3 TB/s.  The host sizes the grid with the same rule.
@@ -210,16 +210,18 @@ __host__ __device__ __forceinline__ int down_chunks(int n) {
 // chunk is summed from zero.  With one chunk in use the workgroup writes its columns of y.  With more,
 // a grid of one workgroup row adds its chunk sums in chunk order and writes y; a taller grid writes
 // them to ypart[chunk][token][d] (fp32) and k_ffn_down_finish adds them in the same order.  No atomics.
-template <typename T, int BT, bool SKIP, int LANES>
+template <typename T, int BT, bool SKIP, int LANES, int TS1 = kDownTile>
 __global__ __launch_bounds__(256) void k_ffn_down(const T* __restrict__ matrix, const float* __restrict__ h,
                                                   const float* __restrict__ h_new, const int32_t* __restrict__ stamp,
                                                   T* __restrict__ y, float* __restrict__ ypart, int d, int batch,
-                                                  int capacity, size_t row_elems, int down_off,
+                                                  int capacity, size_t row_elems, int down_off, int spec_groups,
                                                   DevState* __restrict__ st) {
     using V = typename Vec<T>::type;
     constexpr int VE = Vec<T>::N;
     constexpr int RG = 256 / LANES;                  // row groups per workgroup
-    constexpr int TS = (kDownTile / BT < 512) ? 512 : kDownTile / BT;   // rows per compaction pass
+    // rows per compaction pass (one token: TS1, 2048 or 4096 - the host picks by the row-count hint; both give the
+    // same bits, see below)
+    constexpr int TS = (BT == 1) ? TS1 : (kDownTile / BT < 512) ? 512 : kDownTile / BT;
     constexpr int PER = TS / 256;                    // slots per thread in the compaction
     __shared__ int list[TS];
     __shared__ float hv[BT][TS];
@@ -246,7 +248,9 @@ __global__ __launch_bounds__(256) void k_ffn_down(const T* __restrict__ matrix, 
     // (the activation array spans the whole capacity, so the addresses are valid; values past
     // num_used are masked below): one memory round trip less on the critical path
     const bool first_row = blockIdx.y == 0;
-    // (uniform branches around unconditional loads from clamped slots: a predicate per load would cost a branch each)
+    // (uniform branches around unconditional loads from clamped slots: a predicate per load would cost a branch each;
+    // spec_groups = how many groups of 256 slots to ask for now when a pass has more than 8: the host derives it from
+    // the row-count hint, the rest is read once the count is known)
     float hfirst[PER][BT], hnfirst[PER][BT];
     int sfirst[PER];
 #pragma unroll
@@ -260,19 +264,21 @@ __global__ __launch_bounds__(256) void k_ffn_down(const T* __restrict__ matrix, 
         for (int b = 0; b < BT; ++b) {
             if (b < batch) {
 #pragma unroll
-                for (int q = 0; q < PER; ++q) hfirst[q][b] = h[(size_t)b * capacity + min(q * 256 + tid, capacity - 1)];
+                for (int q = 0; q < PER; ++q)
+                    if (PER <= 8 || q < spec_groups) hfirst[q][b] = h[(size_t)b * capacity + min(q * 256 + tid, capacity - 1)];
             }
         }
         if (stamp) {
             // the loader-written activations travel in the same round trip as h and the stamps
 #pragma unroll
-            for (int q = 0; q < PER; ++q) sfirst[q] = stamp[min(q * 256 + tid, capacity - 1)];
+            for (int q = 0; q < PER; ++q)
+                if (PER <= 8 || q < spec_groups) sfirst[q] = stamp[min(q * 256 + tid, capacity - 1)];
 #pragma unroll
             for (int b = 0; b < BT; ++b) {
                 if (b < batch) {
 #pragma unroll
                     for (int q = 0; q < PER; ++q)
-                        hnfirst[q][b] = h_new[(size_t)b * capacity + min(q * 256 + tid, capacity - 1)];
+                        if (PER <= 8 || q < spec_groups) hnfirst[q][b] = h_new[(size_t)b * capacity + min(q * 256 + tid, capacity - 1)];
                 }
             }
         }
@@ -315,58 +321,69 @@ __global__ __launch_bounds__(256) void k_ffn_down(const T* __restrict__ matrix, 
             const int lane = tid & 63, wv = tid >> 6, rgw = lane / LANES;
             int* wlist = list + wv * WL;
             float* whv = hv[0] + wv * WL;
+            // A thread takes the list positions i with i mod RGW = its row group, counted over the whole chunk and
+            // not per pass, and adds them in ascending order: passes of 2048 or of 4096 slots give the same sums.
+            int cnt = 0;                                 // entries of this wave's list so far (uniform over the wave)
             for (int s_base = r0; s_base < r1; s_base += TS) {
-                int cnt = 0, nz = 0;                     // uniform over the wave
+                const int start = cnt;                   // list position of the first entry of this pass
+                int nz = 0;
                 float hval[PER];
-                if (s_base == 0) {                       // only chunk 0 (first workgroup row) starts at row 0
+                const int need = min(PER, (r1 - s_base + 255) >> 8);      // groups of 256 slots with rows in them
+                const int have = (s_base == 0) ? (PER <= 8 ? PER : min(spec_groups, PER)) : 0;   // ... of which requested at the start
 #pragma unroll
-                    for (int q = 0; q < PER; ++q) hval[q] = hfirst[q][0];
-                } else {
+                for (int q = 0; q < PER; ++q) hval[q] = hfirst[q][0];       // (only chunk 0 starts at row 0)
+                if (need > have) {
 #pragma unroll
-                    for (int q = 0; q < PER; ++q) hval[q] = h[min(s_base + q * 256 + tid, capacity - 1)];
+                    for (int q = 0; q < PER; ++q)
+                        if (q >= have && q < need) hval[q] = h[min(s_base + q * 256 + tid, capacity - 1)];
                     if (stamp) {
 #pragma unroll
                         for (int q = 0; q < PER; ++q) {
-                            const int sc = min(s_base + q * 256 + tid, capacity - 1);
-                            const float hn = h_new[sc];
-                            if (stamp[sc] == cur_step) hval[q] = hn;
+                            if (q >= have && q < need) {
+                                const int sc = min(s_base + q * 256 + tid, capacity - 1);
+                                const float hn = h_new[sc];
+                                if (stamp[sc] == cur_step) hval[q] = hn;
+                            }
                         }
                     }
                 }
 #pragma unroll
                 for (int q = 0; q < PER; ++q) {
-                    const int s = s_base + q * 256 + tid;
-                    const float v = (s < r1) ? hval[q] : 0.f;
-                    const bool nonzero = v != 0.f;
-                    const bool take = SKIP ? nonzero : s < r1;
-                    const unsigned long long m = __ballot(take);
-                    if (take) {
-                        const int pos = cnt + (int)__builtin_amdgcn_mbcnt_hi((unsigned)(m >> 32),
-                                                                              __builtin_amdgcn_mbcnt_lo((unsigned)m, 0u));
-                        wlist[pos] = s;
-                        whv[pos] = v;
+                    if (PER <= 8 || q < need) {           // uniform (short passes: all groups, empty ones cost little)
+                        const int s = s_base + q * 256 + tid;
+                        const float v = (s < r1) ? hval[q] : 0.f;
+                        const bool nonzero = v != 0.f;
+                        const bool take = SKIP ? nonzero : s < r1;
+                        const unsigned long long m = __ballot(take);
+                        if (take) {
+                            const int pos = cnt + (int)__builtin_amdgcn_mbcnt_hi((unsigned)(m >> 32),
+                                                                                  __builtin_amdgcn_mbcnt_lo((unsigned)m, 0u));
+                            wlist[pos - start] = s;
+                            whv[pos - start] = v;
+                        }
+                        cnt += __popcll(m);
+                        nz += SKIP ? __popcll(m) : __popcll(__ballot(nonzero));
                     }
-                    cnt += __popcll(m);
-                    nz += SKIP ? __popcll(m) : __popcll(__ballot(nonzero));
                 }
                 if (slice == 0 && lane == 0 && nz) atomicAdd(&n_active, nz);      // statistics only
                 __builtin_amdgcn_wave_barrier();
                 if (col_ok) {
                     // all row loads of a pass over kInFlight rows per thread are issued before the first use
                     constexpr int kInFlight = 8;
-                    for (int i0 = rgw; i0 < cnt; i0 += RGW * kInFlight) {
+                    const int first = start + ((rgw - start) & (RGW - 1));   // first position >= start of this row group
+                    for (int i0 = first; i0 < cnt; i0 += RGW * kInFlight) {
                         V v[kInFlight];
 #pragma unroll
                         for (int u = 0; u < kInFlight; ++u) {
                             const int i = i0 + u * RGW;
-                            const int sr = wlist[i < cnt ? i : i0];
+                            const int sr = wlist[(i < cnt ? i : i0) - start];
                             v[u] = (i < cnt) ? *reinterpret_cast<const V*>(base + (size_t)sr * row_elems) : V(0);
                         }
 #pragma unroll
                         for (int u = 0; u < kInFlight; ++u) {
                             const int i = i0 + u * RGW;
                             if (i < cnt) {
-                                const float hb = whv[i];
+                                const float hb = whv[i - start];
 #pragma unroll
                                 for (int e = 0; e < VE; ++e) acc[e] = __builtin_fmaf(hb, (float)v[u][e], acc[e]);
                             }

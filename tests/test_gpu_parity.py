@@ -385,6 +385,33 @@ def test_c5_all_32_layers_token_major():
     assert len(set(sizes)) > 8 and max(sizes) <= w.capacity_rows // 2       # every layer its own set, far below the cap
 
 
+@pytest.mark.parametrize("dtype", ["f16", "f32"])
+def test_row_count_hint_never_changes_results_above_2048_rows(dtype):
+    """About 3000 rows in use, one token: a hint above 2048 rows selects compaction passes of 4096 slots (one pass), a
+    smaller one or none passes of 2048 (two passes over the single chunk); the output bytes are the same, for both ways
+    of driving the layer."""
+    from tests.harness import GpuLayer
+    w = wl.scaled(wl.WORKLOADS["C1"], name="hint-3000", d_model=256, d_ffn=8192, rank=32, window_k=4, p_active=0.25,
+                  dtype=dtype, tokens=10, capacity_rows=8192)
+    L = wl.make_layer(w)
+    X = wl.make_inputs(w)
+    outs, rows = set(), []
+    for hint in (0, 700, 2000, 3300, 9000):
+        for api in ("step", "calls"):
+            gpu = GpuLayer(w, L)
+            if hint:
+                gpu.layer.set_expected_rows(hint)
+            xd = gpu.upload_x(X)
+            y = torch.zeros_like(xd)
+            for t in range(len(X)):
+                (gpu.layer.step if api == "step" else gpu.layer.step_calls)(xd[t], y[t])
+            assert gpu.layer.state()["error"] == 0
+            rows.append(gpu.layer.state()["num_used"])
+            outs.add(y.cpu().numpy().tobytes())
+    assert 2048 < min(rows) and max(rows) <= 4096          # the last step; most of the ten steps are in that range
+    assert len(outs) == 1
+
+
 @pytest.mark.parametrize("glu", [False, True])
 def test_row_count_hint_never_changes_results_batched(glu):
     """Eight tokens per step, fp16: the grids of both matrix-core stages are sized from the hint (a smaller grid strides
