@@ -13,18 +13,19 @@ namespace lif {
 
 constexpr int kMfmaUnroll = 8;     // k-steps (32 elements each) a wave keeps in flight
 
-// grid = ceil(capacity / 16) workgroups of 4 (or 16) waves; workgroup b owns 16 rows and exits at once if
-// they are not in use.  Each wave takes contiguous k-steps (a wave instruction reads 64 bytes of 16 rows;
-// consecutive instructions of one wave then complete whole 128-byte lines: measured 6.5 TB/s against
-// 4.6 TB/s when the waves interleave k-steps); the partial tiles are added in k order through LDS.
+// A workgroup owns the 16 rows of a tile and exits at once if they are not in use; its waves take contiguous
+// parts of the k range.  Two forms of the tile follow: ffn_up_mfma_tile loads the fragments directly (a wave
+// instruction reads 64 bytes of 16 rows; used with 16 waves for the few tiles a load wrote), and
+// ffn_up_mfma_tile_staged reads row-contiguous pieces and passes them through LDS (the pass over all rows and the
+// one next to the loaders).  Both give the same bits.
 // Fragment layout of the 16x16x32 MFMA: lane l supplies row (l mod 16) of A and column (l mod 16)
 // of B for the k sub-block (l div 16); it receives D[4 * (l div 16) + r][l mod 16], r = 0..3.
 // Here A = rows of the cache, B = tokens (columns >= batch are zero).
 // Requires d % 32 == 0.
-constexpr int kMfmaParts = 16;                   // parts of the k range, each summed from zero (see ffn_up_mfma_tile)
-constexpr int kMfmaWaves = 4;       // waves per 16-row tile (each takes a contiguous part of the k-steps)
-constexpr int kMfmaWavesFix = 16; // ... for the short pass over the rows a load wrote: few tiles, so a
-                                                  // tile is spread over 16 waves (one round of loads each)
+constexpr int kMfmaParts = 16;      // parts of the k range, each summed from zero, added as a tree (below)
+constexpr int kMfmaWaves = 4;       // waves per tile in the launch shared with the loaders (256 threads per workgroup)
+constexpr int kMfmaWavesFix = 16;   // ... for the short pass over the rows a load wrote: few tiles, so a
+                                    // tile is spread over 16 waves (one round of loads each)
 
 // How the 16 partial tiles of a row tile are added: as a balanced binary tree in part order,
 //   ((p0 + p1) + (p2 + p3)) + ((p4 + p5) + (p6 + p7)) + ...
